@@ -1,0 +1,121 @@
+/*
+ * CPU oracle for the AdaDecode hot path (arxiv 2506.03700) -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, double-precision implementation of what the GPU library computes: the Llama-style
+ * decoder layer step over m ragged rows, the exit head (Sec. 2.1; Eq. 1), the verification of early
+ * predictions (Sec. 2.2; Eq. 2 at temperature 0), plain greedy decoding, and Algorithm 1.
+ * It shares no code with the HIP path and must never be linked into, imported by or called from the
+ * product: only tests, the smoke check and the benchmark's CPU-baseline leg use it.
+ *
+ * Arithmetic: every value is a double; weights are read as stored (fp32, or bf16 bit patterns widened
+ * exactly) and never rounded again.  Dot products may be summed in any order (the compiler is allowed
+ * to vectorise them); nothing else is reordered, blocked or fused.
+ *
+ * Pins (tests/test_oracle_*.py): whole-sequence causal forward written with library matmul/softmax,
+ * closed forms for RMSNorm / RoPE / softmax confidence, AdaDecode == greedy by brute force, deferred
+ * KV == sequential KV, the worked example of Fig. 2 (left), gamma = 0 and gamma = 1 (Sec. 4.4).
+ * Parity unpinned: natural exit and rejection *rates* on random-init models (the paper's 5-6 % are
+ * for trained heads on real data); they are reported, not checked.
+ */
+#ifndef ADADECODE_ORACLE_H
+#define ADADECODE_ORACLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_MAX_EXIT = 8 };
+
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    double  rope_base, rms_eps;
+    int32_t wdtype;                       /* ORC_F32 or ORC_BF16: storage of every weight tensor */
+    int32_t n_exit;
+    int32_t exit_layers[ORC_MAX_EXIT];    /* 1-based, ascending, each < n_layers */
+} orc_config;
+
+/* All matrices are [out_features, in_features] row-major. */
+typedef struct { const void *attn_norm, *wq, *wk, *wv, *wo, *ffn_norm, *w_gate, *w_up, *w_down; } orc_layer_weights;
+typedef struct { const void *embed, *final_norm, *lm_head; const void *exit_T[ORC_MAX_EXIT]; /* NULL = identity */ } orc_top_weights;
+
+typedef struct orc_model orc_model;
+typedef struct orc_kv orc_kv;
+
+/* The model keeps the pointers; the caller keeps the buffers alive. */
+orc_model *orc_model_new(const orc_config *, const orc_layer_weights *layers, const orc_top_weights *);
+void       orc_model_free(orc_model *);
+orc_kv    *orc_kv_new(const orc_model *, int32_t max_pos);
+void       orc_kv_free(orc_kv *);
+int32_t    orc_kv_len(const orc_kv *, int32_t layer /*1-based*/);
+void       orc_kv_set_len(orc_kv *, int32_t layer, int32_t len);
+void       orc_kv_truncate(orc_kv *, int32_t new_len);                 /* every layer: len = min(len, new_len) */
+/* copy n positions starting at pos0; k and v are [n][n_kv_heads*head_dim] */
+void       orc_kv_write(orc_kv *, int32_t layer, int32_t pos0, int32_t n, const float *k, const float *v);
+void       orc_kv_read(const orc_kv *, int32_t layer, int32_t pos0, int32_t n, double *k, double *v);
+
+/* --- building blocks, exported so that tests can pin each one ------------------------------------ */
+void orc_rmsnorm(const double *x, const void *w, int32_t wdtype, int32_t n, double eps, double *out);
+void orc_rope(double *vec, int32_t head_dim, int32_t pos, double base);     /* one head vector, in place */
+/* logits z[V] -> lowest-index argmax, max-softmax confidence, top-2 logit margin */
+void orc_confidence(const double *z, int32_t n, int32_t *token, double *conf, double *margin);
+
+void orc_embed(const orc_model *, const int32_t *tokens, int32_t m, double *hidden /*[m][d]*/);
+/* One decoder layer over m rows at consecutive positions pos[0..m), pos[0] == kv_len(layer).
+ * Returns 0, or -1 (bad layer / m), -2 (positions not consecutive or not at the cache end), -3 (beyond max_pos). */
+int  orc_layer_step(const orc_model *, orc_kv *, int32_t layer, double *hidden /*[m][d] in place*/,
+                    const int32_t *pos, int32_t m);
+/* Head on one row. head_index: -1 = final head (no T); i >= 0 = exit head i (uses exit_T[i] if given).
+ * logits_out may be NULL. */
+void orc_head(const orc_model *, int32_t head_index, const double *h, int32_t *token, double *conf,
+              double *margin, double *logits_out);
+/* Verification at temperature 0 of m rows of final-layer hidden states against m-1 drafted tokens. */
+void orc_verify(const orc_model *, const double *hidden /*[m][d]*/, const int32_t *draft /*[m-1]*/, int32_t m,
+                int32_t *n_accept, int32_t *next_token, int32_t *row_argmax /*[m] or NULL*/,
+                double *row_margin /*[m] or NULL*/);
+
+/* --- generation ------------------------------------------------------------------------------------ */
+enum { ORC_EV_LAYER_STEP = 1, ORC_EV_HEAD = 2, ORC_EV_VERIFY = 3, ORC_EV_VERIFY_ROW = 4 };
+typedef struct {
+    int32_t kind;
+    int32_t layer;      /* LAYER_STEP, HEAD */
+    int32_t pos;        /* LAYER_STEP: first position; HEAD / VERIFY_ROW: the row's position; VERIFY: first row's position */
+    int32_t m;          /* LAYER_STEP / VERIFY: rows */
+    int32_t token;      /* HEAD: argmax; VERIFY: next token; VERIFY_ROW: argmax */
+    int32_t flag;       /* HEAD: 1 = exit taken; VERIFY: n_accept; VERIFY_ROW: 1 = row was compared and matched, 0 = mismatched, -1 = not compared */
+    double  conf;       /* HEAD */
+    double  margin;     /* HEAD / VERIFY_ROW: top-2 logit margin */
+} orc_event;
+
+typedef struct {
+    double  gamma;
+    int32_t max_pending;            /* cap on unverified early predictions */
+    int32_t max_new;
+    int32_t eos_id;                 /* -1: none */
+    const uint8_t *forced_exit;     /* NULL, or [max_pos]: 0 = full depth, else the exit layer forced for that position */
+    const int32_t *scripted_draft;  /* NULL, or [max_pos]: if >= 0, the token drafted when position pos exits early
+                                       (replaces the head's argmax; lets a test force a rejection) */
+} orc_gen_params;
+
+typedef struct {
+    int64_t tokens, layer_steps, layer_step_rows, head_evals, verifies, early_preds, rejections, rolled_back;
+    int64_t steps_by_m[9];
+} orc_stats;
+
+/* Plain greedy decoding.  margins may be NULL; else [max_new] top-2 logit margin of each emitted token. */
+int orc_generate_greedy(const orc_model *, orc_kv *, const int32_t *prompt, int32_t n_prompt, int32_t max_new,
+                        int32_t eos_id, int32_t *out_tokens, int32_t *n_out, double *margins);
+/* Algorithm 1.  events may be NULL; at most max_events are written, *n_events counts all of them. */
+int orc_generate_ada(const orc_model *, orc_kv *, const int32_t *prompt, int32_t n_prompt, const orc_gen_params *,
+                     int32_t *out_tokens, int32_t *n_out, orc_stats *, orc_event *events, int64_t max_events,
+                     int64_t *n_events);
+
+int orc_num_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
