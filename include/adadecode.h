@@ -1,0 +1,163 @@
+/*
+ * adadecode.h -- C ABI of the MI355X (gfx950) implementation of AdaDecode's hot path
+ * (arxiv 2506.03700, "Accelerating LLM Decoding with Adaptive Layer Parallelism").
+ *
+ * The library runs, on one GPU and at batch 1, the three operations Algorithm 1 is made of, plus the
+ * loop itself:
+ *   ad_layer_step   "update KV cache at layer l by processing all tokens in P[l] in parallel"
+ *   ad_exit_head    Eq. 1 at temperature 0: greedy token of an intermediate-layer head and its probability
+ *   ad_verify       Eq. 2 at temperature 0: accept the early predictions that equal the final layer's
+ *                   greedy tokens, replace the first that does not
+ *   ad_generate     Algorithm 1 (prefill, layer loop with early exits, deferred layers, verification,
+ *                   rollback) driven by the three calls above
+ *
+ * Conventions
+ *   - Layers are 1-based; positions are 0-based; all matrices are [out_features, in_features] row-major.
+ *   - "dev" pointers are device memory the caller allocated (for instance through PyTorch) and owns; the
+ *     library never allocates or frees device memory.  "host" pointers are ordinary host memory, read or
+ *     written before the call returns.  "pinned host or dev" pointers are written by a kernel: valid
+ *     after the stream has been synchronised.
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Every call returns an ad_status; nothing is thrown or aborted.  ad_last_error() gives the text of
+ *     the last failure on the calling thread.  A call that fails leaves the cache lengths unchanged.
+ *   - One call at a time per ad_model: calls share the model's scratch area, so calls on the same model
+ *     must be issued on one stream (or otherwise ordered); different models are independent.
+ */
+#ifndef ADADECODE_H
+#define ADADECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ad_model ad_model;   /* opaque: configuration, packed weights, scratch */
+typedef struct ad_kv ad_kv;         /* opaque: per-layer KV cache with per-layer lengths */
+
+typedef enum {
+    AD_OK = 0,
+    AD_EINVAL = 1,   /* null pointer, bad configuration */
+    AD_ERANGE = 2,   /* m outside [1, m_max], layer out of range, position beyond max_pos */
+    AD_ESTATE = 3,   /* positions not consecutive or not at the layer's cache end; head on a layer without one */
+    AD_EDEVICE = 4,  /* HIP error (text in ad_last_error) */
+    AD_ENOMEM = 5    /* workspace / storage too small */
+} ad_status;
+
+typedef enum { AD_F32 = 0, AD_BF16 = 1 } ad_dtype;
+
+enum { AD_MAX_EXIT = 8, AD_M_MAX = 8 };
+
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    float   rope_base, rms_eps;
+    int32_t dtype;                       /* ad_dtype: storage of the weights passed in and of the KV cache */
+    int32_t n_exit;                      /* number of exit heads */
+    int32_t exit_layers[AD_MAX_EXIT];    /* 1-based, ascending, each < n_layers (Sec. 2.1: heads at chosen layers) */
+    int32_t m_max;                       /* largest number of rows per call, 1..AD_M_MAX */
+} ad_config;
+
+/* One decoder layer.  Norm vectors have d_model elements; all tensors are of cfg.dtype. */
+typedef struct {
+    const void *attn_norm, *wq, *wk, *wv, *wo, *ffn_norm, *w_gate, *w_up, *w_down;   /* dev */
+} ad_layer_weights;
+
+/* embed [vocab, d], final_norm [d], lm_head [vocab, d] (may alias embed).  exit_T is NULL, or an array
+ * of n_exit dev pointers, each NULL (identity) or a [d, d] transform T: the exit head is then
+ * E = E* T as in Sec. 2.1 ("lightweight LM head"), applied after the shared final norm. */
+typedef struct {
+    const void *embed, *final_norm, *lm_head;   /* dev */
+    const void *const *exit_T;                  /* host array of dev pointers, or NULL */
+} ad_top_weights;
+
+/* Bytes of device workspace ad_model_create needs (0 if the configuration is invalid).  It holds the
+ * library's own streaming layout of every weight matrix plus scratch. */
+size_t    ad_workspace_bytes(const ad_config *);
+
+/* Re-lays the weights out into `workspace` (dev, 256-byte aligned, ad_workspace_bytes() bytes, zero-filled
+ * or not) on `stream` and returns a handle.  After the stream has been synchronised the caller may free
+ * the original weight buffers; `workspace` must stay alive until ad_model_destroy. */
+ad_status ad_model_create(const ad_config *, const ad_layer_weights *layers /*host [n_layers]*/,
+                          const ad_top_weights *, void *workspace, size_t workspace_bytes, void *stream,
+                          ad_model **out);
+ad_status ad_model_destroy(ad_model *);
+
+/* KV cache.  Storage layout (caller-visible, so that tests and benchmarks can fill or read it):
+ *   [layer 0..L)[K then V][kv head][position 0..max_pos)[head_dim], elements of cfg.dtype, K stored
+ *   after rotary embedding.  Entries at positions >= the layer's length are dead, not zeroed. */
+size_t    ad_kv_bytes(const ad_config *, int32_t max_pos);
+ad_status ad_kv_create(const ad_model *, void *kv_storage /*dev*/, size_t kv_storage_bytes, int32_t max_pos, ad_kv **out);
+ad_status ad_kv_destroy(ad_kv *);
+ad_status ad_kv_len(const ad_kv *, int32_t layer, int32_t *len);
+ad_status ad_kv_set_len(ad_kv *, int32_t layer, int32_t len);   /* declare a prefilled cache (benchmarks) */
+/* Rollback after a rejected early prediction (Sec. 2.2): every layer's length becomes min(len, new_len). */
+ad_status ad_kv_truncate(ad_kv *, int32_t new_len);
+
+/* hidden[r] = embedding row of tokens[r].  tokens: host [m]; hidden: dev [m, d] fp32. */
+ad_status ad_embed(const ad_model *, const int32_t *tokens, int32_t m, void *hidden, void *stream);
+
+/* One decoder layer over the m pending rows of that layer (Algorithm 1, the "update KV cache at layer l"
+ * step; Sec. 2.2).  hidden: dev [m, d] fp32, updated in place.  pos: host [m], consecutive, and
+ * pos[0] must equal the layer's current cache length; the rows' K/V are appended and the length grows
+ * by m.  Row r attends to positions 0..pos[r]. */
+ad_status ad_layer_step(const ad_model *, ad_kv *, int32_t layer, void *hidden, const int32_t *pos, int32_t m,
+                        void *stream);
+
+/* Eq. 1 at temperature 0 for the exit head at `layer` (which must be one of exit_layers; layer ==
+ * n_layers selects the final head): token = argmax_t z_t (lowest id among equals), conf = softmax
+ * probability of that token, with z = E* T norm(hidden_row).  hidden_row: dev [d] fp32.
+ * token, conf: pinned host or dev. */
+ad_status ad_exit_head(const ad_model *, int32_t layer, const void *hidden_row, int32_t *token, float *conf,
+                       void *stream);
+
+/* Eq. 2 at temperature 0 over the m rows of the last layer's pending list.  hidden: dev [m, d] fp32,
+ * outputs of layer L, in position order; draft: host [m-1], draft[j] = the token early-predicted after
+ * row j (i.e. row j+1's token).  With a_j = final-head argmax of row j: n_accept = the first j with
+ * a_j != draft[j] (or m-1 if none), next_token = a_{n_accept}.  n_accept, next_token: pinned host or dev.
+ * row_argmax: NULL, or pinned host or dev [m]. */
+ad_status ad_verify(const ad_model *, const void *hidden, const int32_t *draft, int32_t m, int32_t *n_accept,
+                    int32_t *next_token, int32_t *row_argmax, void *stream);
+
+/* For tests: the logits the head at `layer` assigns to m rows.  logits: dev [m, vocab] fp32. */
+ad_status ad_head_logits(const ad_model *, int32_t layer, const void *hidden, int32_t m, void *logits, void *stream);
+
+/* ---- Algorithm 1 --------------------------------------------------------------------------------- */
+typedef struct {
+    float   gamma;               /* early-prediction threshold of Eq. 1 (strict >) */
+    int32_t max_pending;         /* cap on unverified early predictions (App. D), 0..m_max-1 */
+    int32_t max_new;             /* number of tokens to generate (all returned tokens are verified) */
+    int32_t eos_id;              /* -1: none */
+    const uint8_t *forced_exit;  /* host; NULL, or [max_pos]: 0 = full depth, else the exit layer forced for the
+                                    token at that absolute position (confidence ignored) */
+    const int32_t *scripted_draft; /* host; NULL, or [max_pos]: if >= 0, replaces the head's token when the
+                                    token at that position exits early (failure injection for tests) */
+} ad_gen_params;
+
+typedef struct {
+    int64_t tokens, layer_steps, layer_step_rows, head_evals, verifies, early_preds, rejections, rolled_back;
+    int64_t steps_by_m[AD_M_MAX + 1];
+    int64_t bytes_algorithmic;   /* weight + KV bytes the steps above must move */
+} ad_stats;
+
+enum { AD_EV_LAYER_STEP = 1, AD_EV_HEAD = 2, AD_EV_VERIFY = 3, AD_EV_VERIFY_ROW = 4 };
+/* Decision trace, one record per scheduler action (same meaning of the fields for every kind:
+ * LAYER_STEP: layer, pos = first row's position, m.  HEAD: layer, pos, token, flag = exit taken, conf.
+ * VERIFY: pos = first row's position, m, token = next token, flag = n_accept.
+ * VERIFY_ROW: pos, token = final-head argmax, flag = 1 matched / 0 mismatched / -1 not compared.) */
+typedef struct { int32_t kind, layer, pos, m, token, flag; float conf; float reserved; } ad_event;
+
+/* Runs Algorithm 1 from an empty cache: prompt (host [n_prompt]) -> out_tokens (host [max_new]).
+ * events: NULL, or host [max_events]; *n_events counts every event even beyond max_events.
+ * Synchronises the stream internally. */
+ad_status ad_generate(const ad_model *, ad_kv *, const int32_t *prompt, int32_t n_prompt, const ad_gen_params *,
+                      int32_t *out_tokens, int32_t *n_out, ad_stats *stats, ad_event *events, int64_t max_events,
+                      int64_t *n_events, void *stream);
+
+const char *ad_last_error(void);   /* thread-local, never NULL */
+const char *ad_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,547 @@
+// C ABI of the library (include/adadecode.h): model and cache objects, argument checks, and the launch
+// sequences of the layer step (Algorithm 1's "update KV cache at layer l"), the exit head (Eq. 1) and the
+// verification (Eq. 2).  All arithmetic is in the kernels (ad_kernels.hip); this file only lays out
+// memory and enqueues work.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/adadecode.h"
+#include "ad_internal.h"
+#include "ad_sched.h"
+
+using namespace ad;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(int hip_code, const char *what) {
+    return fail(AD_EDEVICE, "%s: %s", what, hip_error_text(hip_code));
+}
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+struct LayerPacked {
+    char *wqkv, *wo, *wgu, *wd, *attn_norm, *ffn_norm;
+};
+
+struct Layout {
+    // sizes
+    size_t elem;
+    int planes;
+    int d, dq, dkv, nqkv, f, dh, V;
+    int kt_d, kt_q, kt_f;
+    size_t sz_wqkv, sz_wo, sz_wgu, sz_wd, sz_norm, sz_embed, sz_head, sz_T;
+    // offsets
+    std::vector<size_t> layer_off;   // start of each layer's block
+    size_t off_embed, off_final_norm, off_head, off_T[AD_MAX_EXIT];
+    size_t off_scratch, scratch_bytes;
+    size_t total;
+};
+
+bool config_ok(const ad_config *c, const char **why) {
+    *why = "";
+    if (!c) { *why = "null config"; return false; }
+    if (c->n_layers < 1 || c->d_model < 16 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 8 || c->vocab < 1) { *why = "non-positive dimension"; return false; }
+    if (c->d_model % 16) { *why = "d_model must be a multiple of 16"; return false; }
+    if (c->d_ffn % 8) { *why = "d_ffn must be a multiple of 8"; return false; }
+    if (c->head_dim != 64 && c->head_dim != 128) { *why = "head_dim must be 64 or 128"; return false; }
+    if (c->n_q_heads % c->n_kv_heads) { *why = "n_q_heads must be a multiple of n_kv_heads"; return false; }
+    if (c->dtype != AD_F32 && c->dtype != AD_BF16) { *why = "unknown dtype"; return false; }
+    if (c->m_max < 1 || c->m_max > AD_M_MAX) { *why = "m_max must be in 1..8"; return false; }
+    if (c->n_exit < 0 || c->n_exit > AD_MAX_EXIT) { *why = "n_exit out of range"; return false; }
+    for (int i = 0; i < c->n_exit; ++i) {
+        if (c->exit_layers[i] < 1 || c->exit_layers[i] >= c->n_layers) { *why = "exit layer must be in 1..n_layers-1"; return false; }
+        if (i && c->exit_layers[i] <= c->exit_layers[i - 1]) { *why = "exit layers must ascend"; return false; }
+    }
+    if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) { *why = "bad rope_base / rms_eps"; return false; }
+    return true;
+}
+
+void make_layout(const ad_config &c, Layout &L) {
+    L.elem = c.dtype == AD_BF16 ? 2 : 4;
+    L.planes = c.dtype == AD_BF16 ? 1 : 3;
+    L.d = c.d_model; L.dh = c.head_dim; L.dq = c.n_q_heads * c.head_dim; L.dkv = c.n_kv_heads * c.head_dim;
+    L.nqkv = L.dq + 2 * L.dkv; L.f = c.d_ffn; L.V = c.vocab;
+    L.kt_d = (L.d + 31) / 32; L.kt_q = (L.dq + 31) / 32; L.kt_f = (L.f + 31) / 32;
+    L.sz_wqkv = packed_bytes(L.nqkv, L.d, L.planes);
+    L.sz_wo = packed_bytes(L.d, L.dq, L.planes);
+    L.sz_wgu = packed_bytes(2 * (int64_t)L.f, L.d, L.planes);
+    L.sz_wd = packed_bytes(L.d, L.f, L.planes);
+    L.sz_norm = align_up(L.d * L.elem);
+    L.sz_embed = align_up((size_t)L.V * L.d * L.elem);
+    L.sz_head = packed_bytes(L.V, L.d, L.planes);
+    L.sz_T = packed_bytes(L.d, L.d, L.planes);
+    size_t off = 0;
+    L.layer_off.resize(c.n_layers);
+    for (int l = 0; l < c.n_layers; ++l) {
+        L.layer_off[l] = off;
+        off += L.sz_wqkv + L.sz_wo + L.sz_wgu + L.sz_wd + 2 * L.sz_norm;
+    }
+    L.off_embed = off; off += L.sz_embed;
+    L.off_final_norm = off; off += L.sz_norm;
+    L.off_head = off; off += L.sz_head;
+    for (int i = 0; i < AD_MAX_EXIT; ++i) { L.off_T[i] = off; if (i < c.n_exit) off += L.sz_T; }
+    L.off_scratch = off;
+    // scratch: see Scratch below
+    size_t s = 0;
+    s += 2 * align_up(act_packed_bytes(L.d));                  // B0, B1
+    s += align_up(act_packed_bytes(L.dq));                     // Bo
+    s += align_up(act_packed_bytes(L.f));                      // Bg
+    s += 2 * align_up((size_t)(L.d / 16) * 8 * 4);             // ssq0, ssq1
+    s += align_up((size_t)8 * L.nqkv * 4);                     // qkv
+    s += 2 * align_up((size_t)8 * L.d * 4);                    // x1, rows
+    s += align_up((size_t)8 * (L.dh / 2) * 2 * 4);             // rope
+    s += align_up((size_t)(L.dh / 2) * 8);                     // inv_freq
+    s += align_up((size_t)4096 * 8 * 4 * 4);                   // head partials (up to 4096 workgroups)
+    s += align_up(256 * 4);                                    // counters
+    L.scratch_bytes = s;
+    L.total = off + s;
+}
+
+}  // namespace
+
+struct ad_model {
+    ad_config cfg;
+    Layout lay;
+    char *ws;
+    int n_wg;
+    std::vector<LayerPacked> layers;
+    char *embed, *final_norm, *head, *T[AD_MAX_EXIT];
+    // scratch
+    char *B0, *B1, *Bo, *Bg;
+    float *ssq0, *ssq1, *qkv, *x1, *rows, *rope, *head_part;
+    double *inv_freq;
+    unsigned *counters;   // [0] head, [8..8+Hkv) attention
+    // pinned host results for ad_generate
+    int32_t *pin;         // [0..8) tok, [8] n_accept, [9] next, [16..24) row argmax
+    float *pin_conf;      // [8]
+};
+
+struct ad_kv {
+    const ad_model *model;
+    char *storage;
+    size_t layer_bytes, half_bytes;
+    float *part;
+    int32_t max_pos;
+    std::vector<int32_t> len;
+};
+
+extern "C" {
+
+const char *ad_last_error(void) { return g_err; }
+const char *ad_version(void) { return "adadecode-gfx950 0.1"; }
+
+size_t ad_workspace_bytes(const ad_config *cfg) {
+    const char *why;
+    if (!config_ok(cfg, &why)) { fail(AD_EINVAL, "%s", why); return 0; }
+    Layout L;
+    make_layout(*cfg, L);
+    return L.total;
+}
+
+ad_status ad_model_create(const ad_config *cfg, const ad_layer_weights *layers, const ad_top_weights *top, void *workspace,
+                          size_t workspace_bytes, void *stream, ad_model **out) {
+    const char *why;
+    if (!config_ok(cfg, &why)) return (ad_status)fail(AD_EINVAL, "ad_model_create: %s", why);
+    if (!layers || !top || !workspace || !out) return (ad_status)fail(AD_EINVAL, "ad_model_create: null argument");
+    if (((uintptr_t)workspace & 255u) != 0) return (ad_status)fail(AD_EINVAL, "ad_model_create: workspace must be 256-byte aligned");
+    if (!top->embed || !top->final_norm || !top->lm_head) return (ad_status)fail(AD_EINVAL, "ad_model_create: null top weight");
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const ad_layer_weights &w = layers[l];
+        if (!w.attn_norm || !w.wq || !w.wk || !w.wv || !w.wo || !w.ffn_norm || !w.w_gate || !w.w_up || !w.w_down)
+            return (ad_status)fail(AD_EINVAL, "ad_model_create: null weight in layer %d", l + 1);
+    }
+    ad_model *m = new (std::nothrow) ad_model();
+    if (!m) return (ad_status)fail(AD_ENOMEM, "ad_model_create: out of host memory");
+    m->cfg = *cfg;
+    make_layout(*cfg, m->lay);
+    const Layout &L = m->lay;
+    if (workspace_bytes < L.total) {
+        delete m;
+        return (ad_status)fail(AD_ENOMEM, "ad_model_create: workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+    }
+    int n_cu = 0, rc = device_info(&n_cu);
+    if (rc) { delete m; return (ad_status)hip_fail(rc, "device query"); }
+    m->n_wg = n_cu;
+    m->ws = (char *)workspace;
+    const int bf = cfg->dtype == AD_BF16;
+    const size_t tile_kb = (size_t)L.planes * 1024u;
+
+#define AD_TRY(expr, what) do { int rc_ = (expr); if (rc_) { delete m; return (ad_status)hip_fail(rc_, what); } } while (0)
+    AD_TRY(launch_zero(m->ws + L.off_scratch, L.scratch_bytes, stream), "zero scratch");
+    m->layers.resize(cfg->n_layers);
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        char *p = m->ws + L.layer_off[l];
+        LayerPacked &lp = m->layers[l];
+        lp.wqkv = p; p += L.sz_wqkv;
+        lp.wo = p; p += L.sz_wo;
+        lp.wgu = p; p += L.sz_wgu;
+        lp.wd = p; p += L.sz_wd;
+        lp.attn_norm = p; p += L.sz_norm;
+        lp.ffn_norm = p;
+        const ad_layer_weights &w = layers[l];
+        // q, k, v share one packed matrix: q rows first, then k, then v
+        AD_TRY(launch_pack_weights(w.wq, nullptr, bf, L.dq, L.d, 0, lp.wqkv, stream), "pack wq");
+        AD_TRY(launch_pack_weights(w.wk, nullptr, bf, L.dkv, L.d, 0, lp.wqkv + (size_t)(L.dq / 16) * L.kt_d * tile_kb, stream), "pack wk");
+        AD_TRY(launch_pack_weights(w.wv, nullptr, bf, L.dkv, L.d, 0, lp.wqkv + (size_t)((L.dq + L.dkv) / 16) * L.kt_d * tile_kb, stream), "pack wv");
+        AD_TRY(launch_pack_weights(w.wo, nullptr, bf, L.d, L.dq, 0, lp.wo, stream), "pack wo");
+        AD_TRY(launch_pack_weights(w.w_gate, w.w_up, bf, L.f, L.d, 1, lp.wgu, stream), "pack gate/up");
+        AD_TRY(launch_pack_weights(w.w_down, nullptr, bf, L.d, L.f, 0, lp.wd, stream), "pack down");
+        AD_TRY(launch_zero(lp.attn_norm, 2 * L.sz_norm, stream), "zero norms");
+        AD_TRY(launch_copy(w.attn_norm, lp.attn_norm, align_up(L.d * L.elem, 16), stream), "copy attn_norm");
+        AD_TRY(launch_copy(w.ffn_norm, lp.ffn_norm, align_up(L.d * L.elem, 16), stream), "copy ffn_norm");
+    }
+    m->embed = m->ws + L.off_embed;
+    m->final_norm = m->ws + L.off_final_norm;
+    m->head = m->ws + L.off_head;
+    AD_TRY(launch_copy(top->embed, m->embed, align_up((size_t)L.V * L.d * L.elem, 16), stream), "copy embed");
+    AD_TRY(launch_copy(top->final_norm, m->final_norm, align_up(L.d * L.elem, 16), stream), "copy final_norm");
+    AD_TRY(launch_pack_weights(top->lm_head, nullptr, bf, L.V, L.d, 0, m->head, stream), "pack lm_head");
+    for (int i = 0; i < AD_MAX_EXIT; ++i) {
+        m->T[i] = nullptr;
+        if (i < cfg->n_exit && top->exit_T && top->exit_T[i]) {
+            m->T[i] = m->ws + L.off_T[i];
+            AD_TRY(launch_pack_weights(top->exit_T[i], nullptr, bf, L.d, L.d, 0, m->T[i], stream), "pack exit transform");
+        }
+    }
+    char *s = m->ws + L.off_scratch;
+    auto take = [&](size_t bytes) { char *p = s; s += align_up(bytes); return p; };
+    m->B0 = take(act_packed_bytes(L.d));
+    m->B1 = take(act_packed_bytes(L.d));
+    m->Bo = take(act_packed_bytes(L.dq));
+    m->Bg = take(act_packed_bytes(L.f));
+    m->ssq0 = (float *)take((size_t)(L.d / 16) * 8 * 4);
+    m->ssq1 = (float *)take((size_t)(L.d / 16) * 8 * 4);
+    m->qkv = (float *)take((size_t)8 * L.nqkv * 4);
+    m->x1 = (float *)take((size_t)8 * L.d * 4);
+    m->rows = (float *)take((size_t)8 * L.d * 4);
+    m->rope = (float *)take((size_t)8 * (L.dh / 2) * 2 * 4);
+    m->inv_freq = (double *)take((size_t)(L.dh / 2) * 8);
+    m->head_part = (float *)take((size_t)4096 * 8 * 4 * 4);
+    m->counters = (unsigned *)take(256 * 4);
+    // rotary frequencies base^(-2i/dh), computed in double on the host and staged through pinned memory
+    m->pin = (int32_t *)pinned_alloc(4096);
+    if (!m->pin) { delete m; return (ad_status)fail(AD_ENOMEM, "ad_model_create: pinned allocation failed"); }
+    m->pin_conf = (float *)(m->pin + 32);
+    double *pf = (double *)(m->pin + 64);
+    for (int i = 0; i < L.dh / 2; ++i) pf[i] = pow((double)cfg->rope_base, -2.0 * (double)i / (double)L.dh);
+    AD_TRY(launch_copy(pf, m->inv_freq, align_up((size_t)(L.dh / 2) * 8, 16), stream), "copy inv_freq");
+    AD_TRY(stream_sync(stream), "model creation");
+#undef AD_TRY
+    *out = m;
+    return AD_OK;
+}
+
+ad_status ad_model_destroy(ad_model *m) {
+    if (!m) return AD_OK;
+    pinned_free(m->pin);
+    delete m;
+    return AD_OK;
+}
+
+// ---- KV cache --------------------------------------------------------------------------------------
+
+static size_t attn_part_bytes(const ad_config &c, int32_t max_pos) {
+    const int C = attn_chunk(c.dtype == AD_BF16, c.head_dim);
+    const size_t S = (size_t)(max_pos + C - 1) / C + 1;
+    return align_up((size_t)c.n_q_heads * 8 * S * (c.head_dim + 2) * 4);
+}
+
+size_t ad_kv_bytes(const ad_config *cfg, int32_t max_pos) {
+    const char *why;
+    if (!config_ok(cfg, &why) || max_pos < 1) { fail(AD_EINVAL, "ad_kv_bytes: %s", max_pos < 1 ? "max_pos < 1" : why); return 0; }
+    const size_t elem = cfg->dtype == AD_BF16 ? 2 : 4;
+    const size_t cache = (size_t)cfg->n_layers * 2 * cfg->n_kv_heads * (size_t)max_pos * cfg->head_dim * elem;
+    return align_up(cache) + attn_part_bytes(*cfg, max_pos);
+}
+
+ad_status ad_kv_create(const ad_model *model, void *kv_storage, size_t kv_storage_bytes, int32_t max_pos, ad_kv **out) {
+    if (!model || !kv_storage || !out || max_pos < 1) return (ad_status)fail(AD_EINVAL, "ad_kv_create: bad argument");
+    if (((uintptr_t)kv_storage & 255u) != 0) return (ad_status)fail(AD_EINVAL, "ad_kv_create: storage must be 256-byte aligned");
+    const size_t need = ad_kv_bytes(&model->cfg, max_pos);
+    if (kv_storage_bytes < need) return (ad_status)fail(AD_ENOMEM, "ad_kv_create: storage has %zu bytes, %zu needed", kv_storage_bytes, need);
+    ad_kv *kv = new (std::nothrow) ad_kv();
+    if (!kv) return (ad_status)fail(AD_ENOMEM, "ad_kv_create: out of host memory");
+    const ad_config &c = model->cfg;
+    const size_t elem = c.dtype == AD_BF16 ? 2 : 4;
+    kv->model = model;
+    kv->storage = (char *)kv_storage;
+    kv->half_bytes = (size_t)c.n_kv_heads * (size_t)max_pos * c.head_dim * elem;
+    kv->layer_bytes = 2 * kv->half_bytes;
+    kv->part = (float *)(kv->storage + align_up((size_t)c.n_layers * kv->layer_bytes));
+    kv->max_pos = max_pos;
+    kv->len.assign(c.n_layers, 0);
+    *out = kv;
+    return AD_OK;
+}
+
+ad_status ad_kv_destroy(ad_kv *kv) { delete kv; return AD_OK; }
+
+ad_status ad_kv_len(const ad_kv *kv, int32_t layer, int32_t *len) {
+    if (!kv || !len) return (ad_status)fail(AD_EINVAL, "ad_kv_len: null argument");
+    if (layer < 1 || layer > (int32_t)kv->len.size()) return (ad_status)fail(AD_ERANGE, "ad_kv_len: layer %d out of range", layer);
+    *len = kv->len[layer - 1];
+    return AD_OK;
+}
+
+ad_status ad_kv_set_len(ad_kv *kv, int32_t layer, int32_t len) {
+    if (!kv) return (ad_status)fail(AD_EINVAL, "ad_kv_set_len: null argument");
+    if (layer < 1 || layer > (int32_t)kv->len.size()) return (ad_status)fail(AD_ERANGE, "ad_kv_set_len: layer %d out of range", layer);
+    if (len < 0 || len > kv->max_pos) return (ad_status)fail(AD_ERANGE, "ad_kv_set_len: length %d outside 0..%d", len, kv->max_pos);
+    kv->len[layer - 1] = len;
+    return AD_OK;
+}
+
+ad_status ad_kv_truncate(ad_kv *kv, int32_t new_len) {
+    if (!kv) return (ad_status)fail(AD_EINVAL, "ad_kv_truncate: null argument");
+    if (new_len < 0) return (ad_status)fail(AD_ERANGE, "ad_kv_truncate: negative length");
+    for (auto &l : kv->len)
+        if (l > new_len) l = new_len;
+    return AD_OK;
+}
+
+// ---- steps -----------------------------------------------------------------------------------------
+
+ad_status ad_embed(const ad_model *m, const int32_t *tokens, int32_t n, void *hidden, void *stream) {
+    if (!m || !tokens || !hidden) return (ad_status)fail(AD_EINVAL, "ad_embed: null argument");
+    if (n < 1 || n > m->cfg.m_max) return (ad_status)fail(AD_ERANGE, "ad_embed: m = %d outside 1..%d", n, m->cfg.m_max);
+    EmbedArgs a;
+    a.table = m->embed; a.is_bf16 = m->cfg.dtype == AD_BF16; a.d = m->cfg.d_model; a.m = n; a.out = (float *)hidden;
+    for (int i = 0; i < n; ++i) {
+        if (tokens[i] < 0 || tokens[i] >= m->cfg.vocab) return (ad_status)fail(AD_ERANGE, "ad_embed: token %d outside the vocabulary", tokens[i]);
+        a.tok[i] = tokens[i];
+    }
+    int rc = launch_embed(a, stream);
+    return rc ? (ad_status)hip_fail(rc, "ad_embed") : AD_OK;
+}
+
+static int64_t layer_step_bytes(const ad_config &c, int32_t ctx, int32_t m) {
+    const int64_t s = c.dtype == AD_BF16 ? 2 : 4;
+    const int64_t dq = (int64_t)c.n_q_heads * c.head_dim, dkv = (int64_t)c.n_kv_heads * c.head_dim, d = c.d_model, f = c.d_ffn;
+    const int64_t w = ((dq + 2 * dkv) * d + d * dq + 3 * d * f) * s;
+    return w + 2 * dkv * s * ((int64_t)ctx + m) + 2 * dkv * s * m;
+}
+
+ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidden, const int32_t *pos, int32_t n, void *stream) {
+    if (!m || !kv || !hidden || !pos) return (ad_status)fail(AD_EINVAL, "ad_layer_step: null argument");
+    if (kv->model != m) return (ad_status)fail(AD_EINVAL, "ad_layer_step: cache belongs to another model");
+    const ad_config &c = m->cfg;
+    if (layer < 1 || layer > c.n_layers) return (ad_status)fail(AD_ERANGE, "ad_layer_step: layer %d outside 1..%d", layer, c.n_layers);
+    if (n < 1 || n > c.m_max) return (ad_status)fail(AD_ERANGE, "ad_layer_step: m = %d outside 1..%d", n, c.m_max);
+    for (int i = 1; i < n; ++i)
+        if (pos[i] != pos[0] + i) return (ad_status)fail(AD_ESTATE, "ad_layer_step: positions are not consecutive");
+    if (pos[0] != kv->len[layer - 1])
+        return (ad_status)fail(AD_ESTATE, "ad_layer_step: pos[0] = %d but layer %d's cache ends at %d", pos[0], layer, kv->len[layer - 1]);
+    if (pos[0] < 0 || pos[n - 1] >= kv->max_pos) return (ad_status)fail(AD_ERANGE, "ad_layer_step: position %d beyond max_pos %d", pos[n - 1], kv->max_pos);
+
+    const Layout &L = m->lay;
+    const LayerPacked &lp = m->layers[layer - 1];
+    const LaunchCtx ctx{stream, m->n_wg};
+    const int bf = c.dtype == AD_BF16;
+    int rc;
+    // 1. pack x * attn_norm, partial sums of squares, rotary table
+    PackArgs pa;
+    pa.x = (const float *)hidden; pa.m = n; pa.d = L.d; pa.norm_w = lp.attn_norm; pa.norm_is_bf16 = bf; pa.B = m->B0; pa.ssq = m->ssq0;
+    pa.rope = m->rope; pa.pos0 = pos[0]; pa.head_dim = L.dh; pa.inv_freq = m->inv_freq;
+    if ((rc = launch_pack(pa, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: pack");
+    // 2. q, k, v
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.W = lp.wqkv; g.B = m->B0; g.NT = L.nqkv / 16; g.KT = L.kt_d; g.N = L.nqkv; g.m = n;
+    g.ssq = m->ssq0; g.n_ssq = L.d / 16; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
+    g.epi = EPI_STORE; g.out = m->qkv; g.ld = L.nqkv;
+    if ((rc = launch_gemm(g, L.planes, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: qkv");
+    // 3. rotary embedding, KV append, attention
+    AttnArgs a;
+    memset(&a, 0, sizeof a);
+    a.qkv = m->qkv; a.ld = L.nqkv; a.rope = m->rope;
+    a.Kc = kv->storage + (size_t)(layer - 1) * kv->layer_bytes; a.Vc = (char *)a.Kc + kv->half_bytes;
+    a.max_pos = kv->max_pos; a.pos0 = pos[0]; a.m = n; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = L.dh;
+    a.C = attn_chunk(bf, L.dh);
+    a.S = pos[0] > 0 ? (pos[0] + a.C - 1) / a.C : 1;
+    a.part = kv->part; a.counters = m->counters + 8; a.Bo = m->Bo; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_is_bf16 = bf;
+    if ((rc = launch_attn(a, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: attention");
+    // 4. x' = x + Wo o, and pack x' * ffn_norm
+    memset(&g, 0, sizeof g);
+    g.W = lp.wo; g.B = m->Bo; g.NT = L.d / 16; g.KT = L.kt_q; g.N = L.d; g.m = n;
+    g.epi = EPI_RESID; g.resid = (const float *)hidden; g.out = m->x1; g.ld = L.d;
+    g.norm_w = lp.ffn_norm; g.norm_is_bf16 = bf; g.Bnext = m->B1; g.ssq_next = m->ssq1;
+    if ((rc = launch_gemm(g, L.planes, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: wo");
+    // 5. silu(Wg b) * (Wu b)
+    memset(&g, 0, sizeof g);
+    g.W = lp.wgu; g.B = m->B1; g.NT = (2 * L.f) / 16; g.KT = L.kt_d; g.N = 2 * L.f; g.m = n;
+    g.ssq = m->ssq1; g.n_ssq = L.d / 16; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
+    g.epi = EPI_SWIGLU; g.Bnext = m->Bg;
+    if ((rc = launch_gemm(g, L.planes, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: gate/up");
+    // 6. y = x' + Wd g
+    memset(&g, 0, sizeof g);
+    g.W = lp.wd; g.B = m->Bg; g.NT = L.d / 16; g.KT = L.kt_f; g.N = L.d; g.m = n;
+    g.epi = EPI_RESID; g.resid = m->x1; g.out = (float *)hidden; g.ld = L.d;
+    if ((rc = launch_gemm(g, L.planes, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: down");
+    kv->len[layer - 1] += n;
+    return AD_OK;
+}
+
+// Head at `layer` over n rows; shared by ad_exit_head, ad_verify and ad_head_logits.
+static int run_head(const ad_model *m, int32_t layer, const void *hidden, int32_t n, GemmArgs &g, void *stream, const char *who) {
+    const ad_config &c = m->cfg;
+    int slot = -1;
+    if (layer != c.n_layers) {
+        for (int i = 0; i < c.n_exit; ++i)
+            if (c.exit_layers[i] == layer) slot = i;
+        if (slot < 0) return fail(AD_ESTATE, "%s: layer %d has no exit head", who, layer);
+    }
+    const Layout &L = m->lay;
+    const LaunchCtx ctx{stream, m->n_wg};
+    const int bf = c.dtype == AD_BF16;
+    int rc;
+    PackArgs pa;
+    memset(&pa, 0, sizeof pa);
+    pa.x = (const float *)hidden; pa.m = n; pa.d = L.d; pa.norm_w = m->final_norm; pa.norm_is_bf16 = bf; pa.B = m->B0; pa.ssq = m->ssq0;
+    if ((rc = launch_pack(pa, ctx))) return hip_fail(rc, who);
+    const void *B = m->B0;
+    const float *ssq = m->ssq0;
+    if (slot >= 0 && m->T[slot]) {
+        // lightweight head of Sec. 2.1: E = E* T, applied as E* (T n)
+        GemmArgs t;
+        memset(&t, 0, sizeof t);
+        t.W = m->T[slot]; t.B = m->B0; t.NT = L.d / 16; t.KT = L.kt_d; t.N = L.d; t.m = n;
+        t.ssq = m->ssq0; t.n_ssq = L.d / 16; t.inv_dim = 1.0f / (float)L.d; t.eps = c.rms_eps;
+        t.epi = EPI_PACK; t.Bnext = m->B1;
+        if ((rc = launch_gemm(t, L.planes, ctx))) return hip_fail(rc, who);
+        B = m->B1;
+        ssq = nullptr;
+    }
+    g.W = m->head; g.B = B; g.NT = (L.V + 15) / 16; g.KT = L.kt_d; g.N = L.V; g.m = n;
+    g.ssq = ssq; g.n_ssq = L.d / 16; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
+    g.epi = EPI_HEAD; g.head_part = m->head_part; g.head_counter = m->counters;
+    if ((rc = launch_gemm(g, L.planes, ctx))) return hip_fail(rc, who);
+    return AD_OK;
+}
+
+ad_status ad_exit_head(const ad_model *m, int32_t layer, const void *hidden_row, int32_t *token, float *conf, void *stream) {
+    if (!m || !hidden_row || !token || !conf) return (ad_status)fail(AD_EINVAL, "ad_exit_head: null argument");
+    if (layer < 1 || layer > m->cfg.n_layers) return (ad_status)fail(AD_ERANGE, "ad_exit_head: layer %d outside 1..%d", layer, m->cfg.n_layers);
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.tok_out = token; g.conf_out = conf;
+    return (ad_status)run_head(m, layer, hidden_row, 1, g, stream, "ad_exit_head");
+}
+
+ad_status ad_verify(const ad_model *m, const void *hidden, const int32_t *draft, int32_t n, int32_t *n_accept, int32_t *next_token,
+                    int32_t *row_argmax, void *stream) {
+    if (!m || !hidden || !n_accept || !next_token || (n > 1 && !draft)) return (ad_status)fail(AD_EINVAL, "ad_verify: null argument");
+    if (n < 1 || n > m->cfg.m_max) return (ad_status)fail(AD_ERANGE, "ad_verify: m = %d outside 1..%d", n, m->cfg.m_max);
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.verify = 1; g.n_accept_out = n_accept; g.next_out = next_token; g.tok_out = row_argmax;
+    for (int i = 0; i + 1 < n; ++i) g.draft[i] = draft[i];
+    return (ad_status)run_head(m, m->cfg.n_layers, hidden, n, g, stream, "ad_verify");
+}
+
+ad_status ad_head_logits(const ad_model *m, int32_t layer, const void *hidden, int32_t n, void *logits, void *stream) {
+    if (!m || !hidden || !logits) return (ad_status)fail(AD_EINVAL, "ad_head_logits: null argument");
+    if (layer < 1 || layer > m->cfg.n_layers) return (ad_status)fail(AD_ERANGE, "ad_head_logits: layer %d outside 1..%d", layer, m->cfg.n_layers);
+    if (n < 1 || n > m->cfg.m_max) return (ad_status)fail(AD_ERANGE, "ad_head_logits: m = %d outside 1..%d", n, m->cfg.m_max);
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.logits = (float *)logits;
+    return (ad_status)run_head(m, layer, hidden, n, g, stream, "ad_head_logits");
+}
+
+// ---- Algorithm 1 over the GPU steps ------------------------------------------------------------------
+
+namespace {
+
+struct GpuBackend : Backend {
+    const ad_model *m;
+    ad_kv *kv;
+    void *stream;
+    int64_t bytes = 0;
+    bool in_prefill = false;   // the prompt pass is not part of the decode-step byte count
+    int32_t pos_buf[AD_M_MAX];
+
+    float *row(int32_t r) const { return m->rows + (size_t)r * m->cfg.d_model; }
+
+    int layer_step(int32_t layer, int32_t row0, int32_t n, int32_t pos0) override {
+        for (int i = 0; i < n; ++i) pos_buf[i] = pos0 + i;
+        if (!in_prefill) bytes += layer_step_bytes(m->cfg, pos0, n);
+        return ad_layer_step(m, kv, layer, row(row0), pos_buf, n, stream);
+    }
+    int prefill(const int32_t *tokens, int32_t n) override {
+        const int32_t chunk = m->cfg.m_max;
+        in_prefill = true;
+        int rc = AD_OK;
+        for (int32_t s = 0; s < n && rc == AD_OK; s += chunk) {
+            const int32_t k = (n - s < chunk) ? n - s : chunk;
+            rc = ad_embed(m, tokens + s, k, row(0), stream);
+            for (int32_t l = 1; l <= m->cfg.n_layers && rc == AD_OK; ++l) rc = layer_step(l, 0, k, s);
+        }
+        in_prefill = false;
+        return rc;
+    }
+    int embed(int32_t token, int32_t r) override { return ad_embed(m, &token, 1, row(r), stream); }
+    int exit_head(int32_t layer, int32_t r, int32_t, int32_t *token, float *conf) override {
+        int rc = ad_exit_head(m, layer, row(r), m->pin, m->pin_conf, stream);
+        if (rc != AD_OK) return rc;
+        if ((rc = stream_sync(stream))) return hip_fail(rc, "ad_generate: exit head");
+        *token = m->pin[0];
+        *conf = m->pin_conf[0];
+        const int64_t s = m->cfg.dtype == AD_BF16 ? 2 : 4;
+        bytes += (int64_t)m->cfg.vocab * m->cfg.d_model * s;
+        return AD_OK;
+    }
+    int verify(int32_t n, int32_t, const int32_t *draft, int32_t *n_accept, int32_t *next, int32_t *row_argmax) override {
+        int rc = ad_verify(m, row(0), draft, n, m->pin + 8, m->pin + 9, m->pin + 16, stream);
+        if (rc != AD_OK) return rc;
+        if ((rc = stream_sync(stream))) return hip_fail(rc, "ad_generate: verify");
+        *n_accept = m->pin[8];
+        *next = m->pin[9];
+        for (int i = 0; i < n; ++i) row_argmax[i] = m->pin[16 + i];
+        const int64_t s = m->cfg.dtype == AD_BF16 ? 2 : 4;
+        bytes += (int64_t)m->cfg.vocab * m->cfg.d_model * s;
+        return AD_OK;
+    }
+    int truncate(int32_t new_len) override { return ad_kv_truncate(kv, new_len); }
+};
+
+}  // namespace
+
+ad_status ad_generate(const ad_model *m, ad_kv *kv, const int32_t *prompt, int32_t n_prompt, const ad_gen_params *gp,
+                      int32_t *out_tokens, int32_t *n_out, ad_stats *stats, ad_event *events, int64_t max_events,
+                      int64_t *n_events, void *stream) {
+    if (!m || !kv || !prompt || !gp || !out_tokens || !n_out) return (ad_status)fail(AD_EINVAL, "ad_generate: null argument");
+    if (kv->model != m) return (ad_status)fail(AD_EINVAL, "ad_generate: cache belongs to another model");
+    if (n_prompt < 1 || gp->max_new < 1) return (ad_status)fail(AD_EINVAL, "ad_generate: empty prompt or max_new < 1");
+    if (gp->max_pending < 0 || gp->max_pending + 1 > m->cfg.m_max)
+        return (ad_status)fail(AD_ERANGE, "ad_generate: max_pending %d outside 0..%d", gp->max_pending, m->cfg.m_max - 1);
+    if ((int64_t)n_prompt + gp->max_new > kv->max_pos)
+        return (ad_status)fail(AD_ERANGE, "ad_generate: prompt + max_new = %lld exceeds max_pos %d", (long long)n_prompt + gp->max_new, kv->max_pos);
+    for (int i = 0; i < n_prompt; ++i)
+        if (prompt[i] < 0 || prompt[i] >= m->cfg.vocab) return (ad_status)fail(AD_ERANGE, "ad_generate: prompt token outside the vocabulary");
+    SchedConfig sc;
+    sc.n_layers = m->cfg.n_layers; sc.n_exit = m->cfg.n_exit; sc.m_max = m->cfg.m_max;
+    for (int i = 0; i < AD_MAX_EXIT; ++i) sc.exit_layers[i] = m->cfg.exit_layers[i];
+    GpuBackend be;
+    be.m = m; be.kv = kv; be.stream = stream;
+    int rc = run_algorithm1(be, sc, *gp, prompt, n_prompt, out_tokens, n_out, stats, events, max_events, n_events);
+    if (stats) stats->bytes_algorithmic = be.bytes;
+    if (rc == AD_OK && (rc = stream_sync(stream))) return (ad_status)hip_fail(rc, "ad_generate");
+    return (ad_status)rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,118 @@
+// Internal interface between the host side of the library (C ABI, model and cache objects, scheduler)
+// and its gfx950 kernels.  Not installed; the public interface is include/adadecode.h.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ad {
+
+// ---- packed operand layouts ---------------------------------------------------------------------------
+// Weight matrix W [N, K] -> tiles of 16 output rows x 32 inputs.  Tile (rt, ks) is stored as P planes of
+// 64 lanes x 8 bf16 (1 KiB per plane): lane l holds W[rt*16 + (l & 15)][ks*32 + (l >> 4)*8 .. +8), which
+// is the A operand of one 16x16x32 bf16 MFMA, so that a wavefront loads a whole tile plane with one
+// 128-bit load per lane from 1 KiB of contiguous memory.  Tiles are ordered [rt][ks][plane].
+// bf16 weights have one plane; fp32 weights are split exactly into three bf16 planes (W = p0 + p1 + p2).
+// Rows >= N and inputs >= K are zero.
+//
+// Activation block [m <= 8 tokens, K] -> per k-step 64 lanes x 8 bf16 (1 KiB): lane l holds column
+// (l & 15) and inputs ks*32 + (l >> 4)*8 .. +8; columns 0..7 are the tokens' bf16 "hi" parts and columns
+// 8..15 their "lo" parts (x = hi + lo to 16 mantissa bits), so one MFMA yields both partial products and
+// the activations keep near-fp32 precision.  This is the MFMA's B operand.
+constexpr int kTileRows = 16;
+constexpr int kTileK = 32;
+constexpr int kThreads = 1024;   // one workgroup per CU, 16 wavefronts
+constexpr int kWaves = kThreads / 64;
+constexpr int kMaxTilesPerRound = 32;
+
+inline size_t packed_bytes(int64_t N, int64_t K, int planes) {
+    const int64_t nt = (N + kTileRows - 1) / kTileRows, kt = (K + kTileK - 1) / kTileK;
+    return (size_t)(nt * kt * planes) * 1024u;
+}
+inline size_t act_packed_bytes(int64_t K) { return (size_t)((K + kTileK - 1) / kTileK) * 1024u; }
+
+enum EpiKind : int { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3, EPI_PACK = 4 };
+
+struct GemmArgs {
+    const void *W;        // packed weights
+    const void *B;        // packed activations
+    int NT, KT;           // row tiles, k-steps
+    int N;                // valid output rows (EPI_SWIGLU: rows of the interleaved gate/up matrix = 2F)
+    int m;                // tokens
+    const float *ssq;     // [n_ssq][8] partial sums of squares of the un-normalised input, or null (scale 1)
+    int n_ssq;
+    float inv_dim, eps;   // scale_t = rsqrt(sum_t * inv_dim + eps)
+    int epi;
+    // EPI_STORE: out[t*ld + n] = scale_t * acc
+    // EPI_RESID: y = resid[t*ld + n] + acc; out[t*ld + n] = y; optionally pack y*norm_w for the next GEMM
+    // EPI_SWIGLU: tile rows 0..7 gate, 8..15 up of features tile*8 .. +8; packs silu(gate)*up into Bnext
+    // EPI_PACK: packs scale_t * acc into Bnext (used for the exit-head transform T)
+    // EPI_HEAD: per-token argmax / log-sum-exp over all rows, combined across workgroups
+    float *out;
+    const float *resid;
+    int ld;
+    const void *norm_w;   // next norm weights (cfg dtype) or null
+    int norm_is_bf16;
+    void *Bnext;          // packed activations written by the epilogue, or null
+    float *ssq_next;      // [NT][8]
+    // head
+    float *head_part;     // [nwg][8][4] (max, sumexp, argmax as int bits, unused)
+    unsigned *head_counter;
+    float *logits;        // null or [m][N]
+    int32_t *tok_out;     // [m] (or null)
+    float *conf_out;      // [m] (or null)
+    int32_t *n_accept_out, *next_out;   // verify outputs or null
+    int32_t draft[8];
+    int verify;
+};
+
+struct PackArgs {
+    const float *x;       // [m][d]
+    int m, d;
+    const void *norm_w;
+    int norm_is_bf16;
+    void *B;              // packed out
+    float *ssq;           // [d/16][8]
+    // rotary table
+    float *rope;          // [m][dh/2][2] (cos, sin) or null
+    int pos0, head_dim;
+    const double *inv_freq;  // [dh/2]
+};
+
+struct AttnArgs {
+    const float *qkv;     // [m][ld]: q heads, then k heads, then v heads
+    int ld;
+    const float *rope;    // [m][dh/2][2]
+    void *Kc, *Vc;        // this layer's cache: [Hkv][max_pos][dh]
+    int max_pos, pos0, m, Hq, Hkv, dh;
+    int C, S;             // chunk (positions per work item), splits
+    float *part;          // [Hkv][S][R][dh+2]
+    unsigned *counters;   // [Hkv]
+    void *Bo;             // packed attention output for the Wo GEMM
+    float scale;
+    int kv_is_bf16;
+};
+
+struct EmbedArgs {
+    const void *table; int is_bf16; int d; int m; int32_t tok[8]; float *out;
+};
+
+struct LaunchCtx { void *stream; int n_wg; };
+
+// All launchers return 0 or a hipError_t value.
+// mode 0: W [N, K] -> packed.  mode 1: gate (src) and up (src2), each [N, K], interleaved 8 rows at a time.
+int launch_pack_weights(const void *src, const void *src2, int src_is_bf16, int64_t N, int64_t K, int mode, void *dst,
+                        void *stream);
+int launch_copy(const void *src, void *dst, size_t bytes, void *stream);
+int launch_zero(void *dst, size_t bytes, void *stream);
+int launch_embed(const EmbedArgs &, void *stream);
+int launch_pack(const PackArgs &, const LaunchCtx &);
+int launch_gemm(const GemmArgs &, int planes, const LaunchCtx &);
+int launch_attn(const AttnArgs &, const LaunchCtx &);
+int attn_chunk(int kv_is_bf16, int dh);   // cached positions per attention work item
+int device_info(int *n_cu);
+const char *hip_error_text(int code);
+int stream_sync(void *stream);
+void *pinned_alloc(size_t bytes);
+void pinned_free(void *);
+
+}  // namespace ad

@@ -1,0 +1,39 @@
+// Host scheduler of Algorithm 1 (adaptive layer parallelism): which rows go through which layer when,
+// when an early prediction is taken, and what a verification keeps.  It talks to the model only through
+// the Backend interface, so the same code drives the GPU kernels and, in CPU tests, a scripted stand-in.
+#pragma once
+#include <stdint.h>
+#include <vector>
+
+#include "../../include/adadecode.h"
+
+namespace ad {
+
+struct Backend {
+    virtual ~Backend() {}
+    // Full-depth pass over prompt tokens [0, n): "KV cache <- LM(x)".
+    virtual int prefill(const int32_t *tokens, int32_t n) = 0;
+    // hidden row `row` <- embedding of token
+    virtual int embed(int32_t token, int32_t row) = 0;
+    // layer `layer` over hidden rows [row0, row0 + m) at positions pos0 .. pos0 + m - 1
+    virtual int layer_step(int32_t layer, int32_t row0, int32_t m, int32_t pos0) = 0;
+    // Eq. 1 at temperature 0 on one row; the result must be final when the call returns
+    virtual int exit_head(int32_t layer, int32_t row, int32_t pos, int32_t *token, float *conf) = 0;
+    // Eq. 2 at temperature 0 on rows [0, m)
+    virtual int verify(int32_t m, int32_t pos0, const int32_t *draft, int32_t *n_accept, int32_t *next, int32_t *row_argmax) = 0;
+    virtual int truncate(int32_t new_len) = 0;
+};
+
+struct SchedConfig {
+    int32_t n_layers;
+    int32_t n_exit;
+    int32_t exit_layers[AD_MAX_EXIT];
+    int32_t m_max;
+};
+
+// Returns an ad_status.  out_tokens must hold max_new entries.
+int run_algorithm1(Backend &be, const SchedConfig &cfg, const ad_gen_params &gp, const int32_t *prompt, int32_t n_prompt,
+                   int32_t *out_tokens, int32_t *n_out, ad_stats *stats, ad_event *events, int64_t max_events,
+                   int64_t *n_events);
+
+}  // namespace ad

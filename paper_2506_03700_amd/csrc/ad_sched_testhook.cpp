@@ -1,0 +1,95 @@
+// CPU-only test hook for the host scheduler: runs Algorithm 1 over a scripted backend whose "model" is a
+// table of head outputs per position, so that every scheduling path (exit, cap, budget flush, rejection,
+// rollback) can be driven from a test without a GPU.  Built into libad_sched_test.so, never into the
+// product library.
+#include <string.h>
+
+#include "ad_sched.h"
+
+namespace {
+
+struct Scripted : ad::Backend {
+    int32_t n_layers, n_exit, max_pos;
+    const int32_t *exit_layers;
+    // table mode: head_tok/head_conf are [max_pos][n_exit] and final_tok is [max_pos], indexed by position.
+    // sequence mode: the k-th exit_head call returns head_tok[k], head_conf[k]; the verify calls consume
+    // final_tok in order, one entry per row (for replaying a recorded run, where a position can be visited
+    // again with a different token after a rollback).
+    int32_t seq_mode, n_head, n_final;
+    int32_t head_cursor = 0, final_cursor = 0;
+    const int32_t *head_tok;
+    const float *head_conf;
+    const int32_t *final_tok;
+    int32_t len[256];
+    int32_t row_pos[AD_M_MAX];
+    int fail_code = 0;
+
+    int prefill(const int32_t *, int32_t n) override {
+        for (int l = 0; l < n_layers; ++l) len[l] = n;
+        return AD_OK;
+    }
+    int embed(int32_t, int32_t) override { return AD_OK; }
+    int layer_step(int32_t layer, int32_t row0, int32_t m, int32_t pos0) override {
+        if (layer < 1 || layer > n_layers || m < 1 || row0 + m > AD_M_MAX) return AD_ERANGE;
+        if (pos0 != len[layer - 1]) return AD_ESTATE;                 // must continue the layer's cache
+        if (layer > 1 && len[layer - 1] + m > len[layer - 2]) return AD_ESTATE;   // a layer never overtakes the one below
+        if (pos0 + m > max_pos) return AD_ERANGE;
+        for (int i = 0; i < m; ++i) row_pos[row0 + i] = pos0 + i;
+        len[layer - 1] += m;
+        return AD_OK;
+    }
+    int exit_head(int32_t layer, int32_t row, int32_t pos, int32_t *token, float *conf) override {
+        int slot = -1;
+        for (int i = 0; i < n_exit; ++i)
+            if (exit_layers[i] == layer) slot = i;
+        if (slot < 0 || row_pos[row] != pos) return AD_ESTATE;
+        if (seq_mode) {
+            if (head_cursor >= n_head) return AD_ERANGE;
+            *token = head_tok[head_cursor];
+            *conf = head_conf[head_cursor++];
+            return AD_OK;
+        }
+        *token = head_tok[(size_t)pos * n_exit + slot];
+        *conf = head_conf[(size_t)pos * n_exit + slot];
+        return AD_OK;
+    }
+    int verify(int32_t m, int32_t pos0, const int32_t *draft, int32_t *n_accept, int32_t *next, int32_t *row_argmax) override {
+        for (int l = 1; l < n_layers; ++l)
+            if (len[l] != len[0]) return AD_ESTATE;                   // every layer must have caught up
+        if (len[0] != pos0 + m) return AD_ESTATE;
+        int acc = m - 1;
+        if (seq_mode && final_cursor + m > n_final) return AD_ERANGE;
+        for (int j = 0; j < m; ++j) row_argmax[j] = seq_mode ? final_tok[final_cursor + j] : final_tok[pos0 + j];
+        if (seq_mode) final_cursor += m;
+        for (int j = 0; j < m - 1; ++j)
+            if (row_argmax[j] != draft[j]) { acc = j; break; }
+        *n_accept = acc;
+        *next = row_argmax[acc];
+        return AD_OK;
+    }
+    int truncate(int32_t new_len) override {
+        for (int l = 0; l < n_layers; ++l)
+            if (len[l] > new_len) len[l] = new_len;
+        return AD_OK;
+    }
+};
+
+}  // namespace
+
+extern "C" int ad_sched_test_run(int32_t n_layers, int32_t n_exit, const int32_t *exit_layers, int32_t m_max, int32_t max_pos,
+                                 int32_t seq_mode, int32_t n_head, int32_t n_final,
+                                 const int32_t *head_tok, const float *head_conf, const int32_t *final_tok,
+                                 const ad_gen_params *gp, const int32_t *prompt, int32_t n_prompt, int32_t *out_tokens,
+                                 int32_t *n_out, ad_stats *stats, ad_event *events, int64_t max_events, int64_t *n_events) {
+    if (n_layers < 1 || n_layers > 256 || n_exit < 0 || n_exit > AD_MAX_EXIT) return AD_EINVAL;
+    Scripted be;
+    be.n_layers = n_layers; be.n_exit = n_exit; be.max_pos = max_pos; be.exit_layers = exit_layers;
+    be.head_tok = head_tok; be.head_conf = head_conf; be.final_tok = final_tok;
+    be.seq_mode = seq_mode; be.n_head = n_head; be.n_final = n_final;
+    memset(be.len, 0, sizeof be.len);
+    ad::SchedConfig sc;
+    memset(&sc, 0, sizeof sc);
+    sc.n_layers = n_layers; sc.n_exit = n_exit; sc.m_max = m_max;
+    for (int i = 0; i < n_exit; ++i) sc.exit_layers[i] = exit_layers[i];
+    return ad::run_algorithm1(be, sc, *gp, prompt, n_prompt, out_tokens, n_out, stats, events, max_events, n_events);
+}

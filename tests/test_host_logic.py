@@ -1,0 +1,166 @@
+"""CPU-only tests of the library's host side: the C ABI exports, argument checks that need no GPU, and the
+host scheduler (Algorithm 1) driven through a scripted backend -- including a replay of the oracle's
+recorded decisions, which the scheduler must reproduce event for event."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2506_03700_amd import binding as ad
+from paper_2506_03700_amd import build as ad_build
+from paper_2506_03700_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    ad_build.build_sched_test(force=False)
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(ad.LIB_PATH):
+        ad_build.build_hip(force=False)
+    header = open(os.path.join(ROOT, "include", "adadecode.h")).read()
+    declared = set(re.findall(r"\b(ad_[a-z_]+)\s*\(", header))
+    assert declared == set(ad.EXPORTS)
+    L = C.CDLL(ad.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_size_queries_and_config_checks_without_gpu():
+    L = ad.lib()
+    cfg = ad.make_config(synth.LLAMA8B)
+    ws = L.ad_workspace_bytes(C.byref(cfg))
+    # the library keeps one copy of every weight (same bytes as the originals for bf16), room for one d x d
+    # transform per exit head (Sec. 2.1), and small scratch
+    s = synth.LLAMA8B
+    weights = (s.n_layers * s.layer_weight_elems() + 2 * s.vocab * s.d_model + len(s.exit_layers) * s.d_model ** 2) * 2
+    assert weights <= ws <= weights + (8 << 20)
+    kvb = L.ad_kv_bytes(C.byref(cfg), 4096 + 8)
+    assert kvb >= s.n_layers * 2 * s.n_kv_heads * s.head_dim * (4096 + 8) * 2
+    # per cached position, one layer reads K and V rows of 2 * Hkv * dh * 2 bytes = 4096 B (8B shape)
+    assert 2 * s.n_kv_heads * s.head_dim * s.elem_bytes() == 4096
+    bad = ad.make_config(synth.LLAMA8B.with_(head_dim=96))
+    assert L.ad_workspace_bytes(C.byref(bad)) == 0 and b"head_dim" in L.ad_last_error()
+    bad = ad.make_config(synth.TINY.with_(exit_layers=(4,)))
+    assert L.ad_workspace_bytes(C.byref(bad)) == 0 and b"exit layer" in L.ad_last_error()
+    bad = ad.make_config(synth.TINY, m_max=9)
+    assert L.ad_workspace_bytes(C.byref(bad)) == 0
+    assert L.ad_kv_bytes(C.byref(cfg), 0) == 0
+    assert L.ad_model_create(None, None, None, None, 0, None, None) == ad.AD_EINVAL
+    assert L.ad_kv_truncate(None, 0) == ad.AD_EINVAL
+
+
+# ---- scheduler over scripted heads -------------------------------------------------------------------
+
+def _events(ev):
+    return [(int(e["kind"]), int(e["layer"]), int(e["pos"]), int(e["m"]), int(e["token"]), int(e["flag"])) for e in ev]
+
+
+def test_fig2_left_schedule():
+    # 3 layers, heads at 1 and 2; position 5 (t1) exits at layer 2, position 6 (t2) at layer 1
+    n_pos = 16
+    head_tok = np.zeros((n_pos, 2), dtype=np.int32)
+    head_conf = np.zeros((n_pos, 2), dtype=np.float32)
+    final_tok = np.arange(100, 100 + n_pos, dtype=np.int32)       # the token after position p is 100 + p
+    head_tok[5] = [0, 105]; head_conf[5] = [0.1, 0.95]
+    head_tok[6] = [106, 0]; head_conf[6] = [0.99, 0.0]
+    rc, out, st, ev = ad.sched_test_run(3, [1, 2], 8, head_tok, head_conf, final_tok, prompt=[1, 2, 3, 4, 5, 6], max_new=3,
+                                        gamma=0.9, max_pending=5)
+    assert rc == ad.AD_OK and list(out) == [105, 106, 107]
+    steps = [(l, p, m) for k, l, p, m, _, _ in _events(ev) if k == ad.EV_LAYER_STEP]
+    assert steps == [(1, 5, 1), (2, 5, 1), (1, 6, 1), (1, 7, 1), (2, 6, 2), (3, 5, 3)]
+    assert st["layer_steps"] == 6 and st["layer_step_rows"] == 9 and st["early_preds"] == 2 and st["verifies"] == 1
+    assert st["steps_by_m"][1:4] == [4, 1, 1]
+
+
+def test_threshold_is_strict_and_cap_and_budget():
+    n_pos, L = 64, 4
+    final_tok = (np.arange(n_pos) * 7 % 50).astype(np.int32)
+    head_tok = final_tok[:, None].copy()                           # the head always drafts the right token
+    head_conf = np.full((n_pos, 1), 0.9, dtype=np.float32)
+    prompt = [3, 1, 4, 1, 5]
+    # conf == gamma does not exit (Eq. 1 uses >)
+    rc, out, st, ev = ad.sched_test_run(L, [2], 8, head_tok, head_conf, final_tok, prompt, 10, np.float32(0.9), 5)
+    assert rc == ad.AD_OK and st["early_preds"] == 0 and st["head_evals"] == 9
+    assert list(out) == list(final_tok[4:14])
+    # just below: every token exits until the cap of 3 unverified drafts, then one runs to depth L
+    rc, out, st, ev = ad.sched_test_run(L, [2], 8, head_tok, head_conf, final_tok, prompt, 10, 0.89, 3)
+    assert rc == ad.AD_OK and list(out) == list(final_tok[4:14])
+    ver = [e for e in _events(ev) if e[0] == ad.EV_VERIFY]
+    assert [v[3] for v in ver] == [4, 4, 2] and all(v[5] == v[3] - 1 for v in ver)    # all drafts accepted
+    # budget: the last token is never drafted -> last verify has the remaining rows only, 10 tokens exactly
+    assert st["tokens"] == 10 and st["early_preds"] == 7 and st["rejections"] == 0
+    # max_pending = 0 is plain sequential decoding, no head is ever evaluated
+    rc, out, st, ev = ad.sched_test_run(L, [2], 8, head_tok, head_conf, final_tok, prompt, 6, 0.0, 0)
+    assert st["head_evals"] == 0 and st["layer_steps"] == 6 * L and list(out) == list(final_tok[4:10])
+    # a cap that would need more rows than m_max is refused
+    rc, *_ = ad.sched_test_run(L, [2], 4, head_tok, head_conf, final_tok, prompt, 6, 0.0, 4)
+    assert rc == ad.AD_ERANGE
+
+
+def test_rejection_rolls_back_and_resumes():
+    n_pos, L = 64, 4
+    final_tok = (np.arange(n_pos) * 11 % 97).astype(np.int32)
+    head_tok = final_tok[:, None].copy()
+    head_conf = np.ones((n_pos, 1), dtype=np.float32)
+    head_tok[6, 0] = 1000                                           # wrong draft for the token after position 6
+    prompt = [9, 8, 7, 6, 5]
+    rc, out, st, ev = ad.sched_test_run(L, [1], 8, head_tok, head_conf, final_tok, prompt, 12, 0.5, 5)
+    assert rc == ad.AD_OK and list(out) == list(final_tok[4:16])
+    ver = [e for e in _events(ev) if e[0] == ad.EV_VERIFY]
+    # first verification: rows at positions 4..9; drafts after 4 and 5 accepted, the one after 6 rejected
+    assert ver[0][2:] == (4, 6, int(final_tok[6]), 2)
+    assert st["rejections"] == 1 and st["rolled_back"] == 2
+    rows = [e for e in _events(ev) if e[0] == ad.EV_VERIFY_ROW][:6]
+    assert [r[5] for r in rows] == [1, 1, 0, -1, -1, -1]
+    # the scripted backend checks on every layer step that the step continues the layer's (truncated) cache
+    after = [e for e in _events(ev)[_events(ev).index(ver[0]):] if e[0] == ad.EV_LAYER_STEP][0]
+    assert after[1:4] == (1, 7, 1)
+
+
+def test_eos_only_from_the_last_layer():
+    n_pos, L = 32, 3
+    final_tok = np.arange(200, 200 + n_pos, dtype=np.int32)
+    head_tok = final_tok[:, None].copy()
+    head_conf = np.ones((n_pos, 1), dtype=np.float32)
+    eos = int(final_tok[7])
+    rc, out, st, ev = ad.sched_test_run(L, [1], 8, head_tok, head_conf, final_tok, [1, 2, 3], 20, 0.5, 5, eos_id=eos)
+    assert rc == ad.AD_OK and list(out) == list(final_tok[2:8]) and out[-1] == eos
+    assert not any(e[0] == ad.EV_HEAD and e[5] == 1 and e[4] == eos for e in _events(ev))
+
+
+UNTIED = synth.TINY.with_(name="tiny-untied", tied_head=False, vocab=512, exit_layers=(1, 2, 3))
+
+
+@pytest.mark.parametrize("shape", [UNTIED, synth.TINY_GQA], ids=lambda s: s.name)
+@pytest.mark.parametrize("gamma,cap,forced_seed", [(0.0, 5, None), (0.0045, 7, None), (0.9, 7, 3), (0.9, 2, 4)])
+def test_scheduler_replays_the_oracle_run(shape, gamma, cap, forced_seed):
+    """Feed the oracle's recorded head outputs to the library's scheduler: tokens, statistics and the whole
+    event sequence must be identical (the two loops are separate implementations of Algorithm 1)."""
+    w = synth.make_weights(shape, 0)
+    o = orc.Oracle(shape, w, max_pos=128)
+    p = synth.make_prompt(shape, 0, n=10)
+    forced = None if forced_seed is None else synth.make_forced_schedule(shape, forced_seed, 128, probs=[0.7 / len(shape.exit_layers)] * len(shape.exit_layers))
+    script = None
+    if forced_seed == 4:
+        script = np.full(128, -1, dtype=np.int32)
+        script[[12, 15, 21, 30]] = [1, 2, 3, 4]
+    toks, st_o, ev_o = o.generate_ada(p, 40, gamma, cap, forced_exit=forced, scripted_draft=script)
+    heads = ev_o[ev_o["kind"] == orc.EV_HEAD]
+    rows = ev_o[ev_o["kind"] == orc.EV_VERIFY_ROW]
+    # with a scripted draft the recorded token is the scripted one; the scheduler applies the script itself
+    rc, out, st, ev = ad.sched_test_run(shape.n_layers, shape.exit_layers, 8, heads["token"], heads["conf"].astype(np.float32),
+                                        rows["token"], p, 40, gamma, cap, forced_exit=forced, scripted_draft=script,
+                                        max_pos=128, sequence=True)
+    assert rc == ad.AD_OK
+    np.testing.assert_array_equal(out, toks)
+    for k in ("tokens", "layer_steps", "layer_step_rows", "head_evals", "verifies", "early_preds", "rejections", "rolled_back"):
+        assert st[k] == st_o[k], k
+    assert st["steps_by_m"] == st_o["steps_by_m"]
+    assert _events(ev) == [(int(e["kind"]), int(e["layer"]), int(e["pos"]), int(e["m"]), int(e["token"]), int(e["flag"])) for e in ev_o]
