@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the AdaDecode hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic input: Algorithm 1 generating `gen_len` tokens
+from a `prompt_len`-token random prompt on the Llama-3-8B-shaped bf16 model (32 layers, exit heads at layers
+8/16/24, threshold 0.9, random-init weights), inputs and weights resident in HBM before the timed region.
+value = generated tokens / wall time of the timed steps (prefill of the prompt included).
+
+The same JSON line also carries:
+  roofline      the weight-streaming kernel sampled live with stream events during the timed steps
+  layer_step    the single-layer microbenchmark: ragged calls with m rows at context 4096, rotating over the
+                model's 32 distinct layers so that no cache can hold the weights
+  forced        the same generation with exits forced from a seeded schedule (0.2/0.2/0.2 at layers 8/16/24)
+  cpu_baseline  the CPU oracle, as it stands, timed on a bounded sample on this machine's host cores
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def layer_step_bytes(shape, ctx, m):
+    s = shape.elem_bytes()
+    return shape.layer_weight_elems() * s + 2 * shape.d_kv * s * (ctx + m) + 2 * shape.d_kv * s * m
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="8b", choices=["8b", "13b", "8b-mini", "tiny"])
+    ap.add_argument("--gen-len", type=int, default=None)
+    ap.add_argument("--prompt-len", type=int, default=None)
+    ap.add_argument("--micro-calls", type=int, default=320, help="layer-step calls per m in the microbenchmark")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--skip-micro", action="store_true")
+    ap.add_argument("--skip-forced", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (no sharding, no collectives); run with --gpus 1")
+        sys.exit(2)
+
+    import torch
+    from paper_2506_03700_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    binding.lib()
+    shape = synth.SHAPES[args.workload]
+    gen_len = args.gen_len or shape.gen_len
+    prompt_len = args.prompt_len or shape.prompt_len
+    cap = 7
+    ctx_micro = 4096
+    max_pos = max(prompt_len + gen_len + 8, ctx_micro + 16)
+
+    t0 = time.time()
+    w = synth.make_weights(shape, seed=0)
+    log(f"[bench] weights for {shape.name} generated in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    g = binding.Model(shape, w, max_pos=max_pos)
+    log(f"[bench] model on device in {time.time() - t0:.1f}s")
+    prompt = synth.make_prompt(shape, 0, n=prompt_len)
+
+    def run(**kw):
+        return g.ad_generate(prompt, gen_len, shape.gamma, cap, want_events=False, **kw)
+
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    g.ad_profile_start(period=7, max_samples=16384)
+    t0 = time.perf_counter()
+    stats = None
+    for _ in range(args.steps):
+        toks, stats, _ = run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = g.ad_profile_stop()
+    tokens_per_s = args.steps * gen_len / dt
+    log(f"[bench] {args.steps} x {gen_len} tokens in {dt:.3f}s -> {tokens_per_s:.1f} tok/s; stats {stats}")
+
+    avg_ms = prof["sampled_ms"] / max(1, prof["samples"])
+    avg_bytes = prof["sampled_bytes"] / max(1, prof["samples"])
+    achieved = avg_bytes / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+    roofline = {"bound": "hbm", "kernel": "k_gemm<1,8> (weight-streaming skinny GEMM, all projections + vocabulary pass)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None, "avg_launch_us": round(avg_ms * 1e3, 2), "avg_bytes_per_launch": int(avg_bytes),
+                "launches": prof["launches"], "sampled": prof["samples"]}
+    decode_bytes = stats["bytes_algorithmic"]
+    e2e = {"algorithmic_GB_per_step": round(decode_bytes / 1e9, 3),
+           "achieved_GBps_whole_step": round(args.steps * decode_bytes / dt / 1e9, 1),
+           "layer_steps_per_s": round(args.steps * stats["layer_steps"] / dt, 1),
+           "early_preds": stats["early_preds"], "rejections": stats["rejections"], "head_evals": stats["head_evals"]}
+
+    forced = None
+    if not args.skip_forced and shape.exit_layers:
+        sched = synth.make_forced_schedule(shape, 0, max_pos)
+        g.ad_generate(prompt, min(gen_len, 64), shape.gamma, cap, forced_exit=sched, want_events=False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        _, fst, _ = g.ad_generate(prompt, gen_len, shape.gamma, cap, forced_exit=sched, want_events=False)
+        torch.cuda.synchronize()
+        fdt = time.perf_counter() - t0
+        forced = {"schedule": "each token exits at an exit layer with probability 0.2 each, else full depth (seeded)",
+                  "tokens_per_s": round(gen_len / fdt, 1), "layer_steps": fst["layer_steps"], "steps_by_m": fst["steps_by_m"],
+                  "early_preds": fst["early_preds"], "rejections": fst["rejections"],
+                  "achieved_GBps": round(fst["bytes_algorithmic"] / fdt / 1e9, 1)}
+        log(f"[bench] forced schedule: {forced}")
+
+    micro = None
+    if not args.skip_micro:
+        micro = {}
+        view = g.kv_view()
+        gen = torch.Generator(device="cuda").manual_seed(0)
+        view[:, :, :, :ctx_micro, :] = torch.randn(view[:, :, :, :ctx_micro, :].shape, generator=gen, device="cuda").to(view.dtype)
+        L = shape.n_layers
+        for m in (1, 2, 3, 4, 6, 8):
+            h = torch.from_numpy(synth.make_hidden(shape, 1000 + m, m)).to("cuda")
+            pos = np.arange(ctx_micro, ctx_micro + m)
+            calls = args.micro_calls
+
+            def one(i):
+                layer = i % L + 1
+                g.kv_set_len(layer, ctx_micro)
+                g.ad_layer_step(layer, h, pos)
+
+            for i in range(min(64, calls)):
+                one(i)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(calls):
+                one(i)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / calls
+            gbs = layer_step_bytes(shape, ctx_micro, m) / (us * 1e-6) / 1e9
+            micro[str(m)] = {"us": round(us, 2), "GBps": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4)}
+            log(f"[bench] layer step m={m}: {us:.2f} us, {gbs:.1f} GB/s ({gbs / HBM_PEAK_GBS:.1%} of peak)")
+        micro = {"ctx": ctx_micro, "calls_per_m": args.micro_calls, "distinct_weight_copies": L,
+                 "algorithmic_bytes_m1": layer_step_bytes(shape, ctx_micro, 1), "by_m": micro}
+
+    cpu = None
+    if not args.skip_cpu:
+        from oracle import oracle as orc
+        n_prompt, n_new = 9, 8
+        o = orc.Oracle(shape, w, max_pos=64)
+        t0 = time.perf_counter()
+        ot, ost, _ = o.generate_ada(prompt[:n_prompt], n_new, shape.gamma, cap)
+        cdt = time.perf_counter() - t0
+        cpu = {"value": round(n_new / cdt, 4), "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+               "sample": f"Algorithm 1 on the same model and weights, prompt {n_prompt} tokens, {n_new} generated tokens, "
+                         f"gamma {shape.gamma}; {cdt:.1f}s wall, prefill included",
+               "layer_steps_per_s": round((ost["layer_steps"] + (n_prompt - 1)) / cdt, 3)}
+        log(f"[bench] cpu oracle: {cpu}")
+        o.close()
+
+    out = {"metric": "decoded tokens/sec @batch1 (8B-shape bf16); layer-step HBM GB/s vs peak",
+           "value": round(tokens_per_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(dt / args.steps * 1e3, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if shape.dtype == synth.BF16 else "f32", "data": "synthetic",
+           "config": {"workload": f"{shape.name}: {shape.n_layers} layers d={shape.d_model} heads {shape.n_q_heads}/{shape.n_kv_heads}x{shape.head_dim} "
+                                  f"ffn {shape.d_ffn} vocab {shape.vocab}, exit heads at {list(shape.exit_layers)}, gamma {shape.gamma}, "
+                                  f"cap {cap}, prompt {prompt_len}, generate {gen_len}, batch 1, random-init N(0,0.02)",
+                      "global_batch": 1, "seq_len": prompt_len + gen_len},
+           "roofline": roofline, "end_to_end": e2e, "forced": forced, "layer_step": micro, "cpu_baseline": cpu}
+    print(json.dumps(out), flush=True)
+    g.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -154,6 +154,17 @@ ad_status ad_generate(const ad_model *, ad_kv *, const int32_t *prompt, int32_t 
                       int32_t *out_tokens, int32_t *n_out, ad_stats *stats, ad_event *events, int64_t max_events,
                       int64_t *n_events, void *stream);
 
+/* ---- measurement ------------------------------------------------------------------------------------
+ * Samples the library's weight-streaming kernel (the kernel that runs every projection of the layer step
+ * and the vocabulary pass of Eq. 1 / Eq. 2): every `period`-th launch is bracketed by a pair of events on
+ * the launch stream.  ad_profile_stop synchronises, and reports the number of launches seen, the number
+ * sampled, the summed duration of the sampled launches and the weight bytes those launches had to read
+ * (rows x inputs x element size of the matrix, the algorithmic figure), and the same byte count over all
+ * launches.  At most max_samples launches are sampled (bounded event pool, 1..65536). */
+ad_status ad_profile_start(ad_model *, int32_t period, int32_t max_samples);
+ad_status ad_profile_stop(ad_model *, int64_t *n_launches, int64_t *n_samples, double *sampled_ms, int64_t *sampled_bytes,
+                          int64_t *total_bytes);
+
 const char *ad_last_error(void);   /* thread-local, never NULL */
 const char *ad_version(void);
 

@@ -23,7 +23,7 @@ EV_LAYER_STEP, EV_HEAD, EV_VERIFY, EV_VERIFY_ROW = 1, 2, 3, 4
 
 EXPORTS = ["ad_workspace_bytes", "ad_model_create", "ad_model_destroy", "ad_kv_bytes", "ad_kv_create", "ad_kv_destroy",
            "ad_kv_len", "ad_kv_set_len", "ad_kv_truncate", "ad_embed", "ad_layer_step", "ad_exit_head", "ad_verify",
-           "ad_head_logits", "ad_generate", "ad_last_error", "ad_version"]
+           "ad_head_logits", "ad_generate", "ad_profile_start", "ad_profile_stop", "ad_last_error", "ad_version"]
 
 
 class Config(C.Structure):
@@ -96,6 +96,8 @@ def lib() -> C.CDLL:
         L.ad_verify.argtypes = [P, P, P, i32, P, P, P, P]
         L.ad_head_logits.argtypes = [P, i32, P, i32, P, P]
         L.ad_generate.argtypes = [P, P, P, i32, C.POINTER(GenParams), P, P, C.POINTER(Stats), P, C.c_int64, P, P]
+        L.ad_profile_start.argtypes = [P, i32, i32]
+        L.ad_profile_stop.argtypes = [P, P, P, P, P, P]
         L.ad_last_error.restype = C.c_char_p
         L.ad_version.restype = C.c_char_p
         for n in EXPORTS:
@@ -277,6 +279,15 @@ class Model:
                                   ev.ctypes.data if want_events else None, max_events if want_events else 0, C.byref(nev),
                                   _stream_ptr(torch)))
         return out[:n.value].copy(), st.as_dict(), ev[:min(nev.value, len(ev))].copy() if want_events else None
+
+
+    def ad_profile_start(self, period: int = 1, max_samples: int = 65536) -> None:
+        _check(self.L.ad_profile_start(self.model, period, max_samples))
+
+    def ad_profile_stop(self) -> dict:
+        nl, ns, sb, tb, ms = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64(), C.c_double()
+        _check(self.L.ad_profile_stop(self.model, C.byref(nl), C.byref(ns), C.byref(ms), C.byref(sb), C.byref(tb)))
+        return {"launches": nl.value, "samples": ns.value, "sampled_ms": ms.value, "sampled_bytes": sb.value, "total_bytes": tb.value}
 
 
 # ---- CPU-only hook over the host scheduler (tests) ------------------------------------------------------

@@ -114,7 +114,16 @@ void make_layout(const ad_config &c, Layout &L) {
 
 }  // namespace
 
+struct Profile {
+    bool on = false;
+    int32_t period = 1, max_samples = 0;
+    int64_t launches = 0, total_bytes = 0;
+    std::vector<void *> start, stop;
+    std::vector<int64_t> bytes;
+};
+
 struct ad_model {
+    mutable Profile prof;
     ad_config cfg;
     Layout lay;
     char *ws;
@@ -248,6 +257,8 @@ ad_status ad_model_create(const ad_config *cfg, const ad_layer_weights *layers, 
 
 ad_status ad_model_destroy(ad_model *m) {
     if (!m) return AD_OK;
+    for (void *e : m->prof.start) event_destroy(e);
+    for (void *e : m->prof.stop) event_destroy(e);
     pinned_free(m->pin);
     delete m;
     return AD_OK;
@@ -316,6 +327,26 @@ ad_status ad_kv_truncate(ad_kv *kv, int32_t new_len) {
 
 // ---- steps -----------------------------------------------------------------------------------------
 
+// Launches the weight-streaming kernel; when profiling is on, every period-th launch is timed with events.
+static int gemm(const ad_model *m, const GemmArgs &g, int64_t rows, int64_t cols, const LaunchCtx &ctx) {
+    Profile &p = m->prof;
+    const int64_t bytes = rows * cols * (int64_t)m->lay.elem;
+    bool sample = false;
+    if (p.on) {
+        sample = (p.launches % p.period == 0) && (int32_t)p.bytes.size() < p.max_samples;
+        ++p.launches;
+        p.total_bytes += bytes;
+    }
+    if (sample) {
+        void *a = event_create(), *b = event_create();
+        if (!a || !b) { event_destroy(a); event_destroy(b); sample = false; }
+        else { p.start.push_back(a); p.stop.push_back(b); p.bytes.push_back(bytes); (void)event_record(a, ctx.stream); }
+    }
+    const int rc = launch_gemm(g, m->lay.planes, ctx);
+    if (sample) (void)event_record(p.stop.back(), ctx.stream);
+    return rc;
+}
+
 ad_status ad_embed(const ad_model *m, const int32_t *tokens, int32_t n, void *hidden, void *stream) {
     if (!m || !tokens || !hidden) return (ad_status)fail(AD_EINVAL, "ad_embed: null argument");
     if (n < 1 || n > m->cfg.m_max) return (ad_status)fail(AD_ERANGE, "ad_embed: m = %d outside 1..%d", n, m->cfg.m_max);
@@ -364,7 +395,7 @@ ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidde
     g.W = lp.wqkv; g.B = m->B0; g.NT = L.nqkv / 16; g.KT = L.kt_d; g.N = L.nqkv; g.m = n;
     g.ssq = m->ssq0; g.n_ssq = L.d / 16; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
     g.epi = EPI_STORE; g.out = m->qkv; g.ld = L.nqkv;
-    if ((rc = launch_gemm(g, L.planes, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: qkv");
+    if ((rc = gemm(m, g, L.nqkv, L.d, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: qkv");
     // 3. rotary embedding, KV append, attention
     AttnArgs a;
     memset(&a, 0, sizeof a);
@@ -380,18 +411,18 @@ ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidde
     g.W = lp.wo; g.B = m->Bo; g.NT = L.d / 16; g.KT = L.kt_q; g.N = L.d; g.m = n;
     g.epi = EPI_RESID; g.resid = (const float *)hidden; g.out = m->x1; g.ld = L.d;
     g.norm_w = lp.ffn_norm; g.norm_is_bf16 = bf; g.Bnext = m->B1; g.ssq_next = m->ssq1;
-    if ((rc = launch_gemm(g, L.planes, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: wo");
+    if ((rc = gemm(m, g, L.d, L.dq, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: wo");
     // 5. silu(Wg b) * (Wu b)
     memset(&g, 0, sizeof g);
     g.W = lp.wgu; g.B = m->B1; g.NT = (2 * L.f) / 16; g.KT = L.kt_d; g.N = 2 * L.f; g.m = n;
     g.ssq = m->ssq1; g.n_ssq = L.d / 16; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
     g.epi = EPI_SWIGLU; g.Bnext = m->Bg;
-    if ((rc = launch_gemm(g, L.planes, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: gate/up");
+    if ((rc = gemm(m, g, 2 * (int64_t)L.f, L.d, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: gate/up");
     // 6. y = x' + Wd g
     memset(&g, 0, sizeof g);
     g.W = lp.wd; g.B = m->Bg; g.NT = L.d / 16; g.KT = L.kt_f; g.N = L.d; g.m = n;
     g.epi = EPI_RESID; g.resid = m->x1; g.out = (float *)hidden; g.ld = L.d;
-    if ((rc = launch_gemm(g, L.planes, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: down");
+    if ((rc = gemm(m, g, L.d, L.f, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: down");
     kv->len[layer - 1] += n;
     return AD_OK;
 }
@@ -422,14 +453,14 @@ static int run_head(const ad_model *m, int32_t layer, const void *hidden, int32_
         t.W = m->T[slot]; t.B = m->B0; t.NT = L.d / 16; t.KT = L.kt_d; t.N = L.d; t.m = n;
         t.ssq = m->ssq0; t.n_ssq = L.d / 16; t.inv_dim = 1.0f / (float)L.d; t.eps = c.rms_eps;
         t.epi = EPI_PACK; t.Bnext = m->B1;
-        if ((rc = launch_gemm(t, L.planes, ctx))) return hip_fail(rc, who);
+        if ((rc = gemm(m, t, L.d, L.d, ctx))) return hip_fail(rc, who);
         B = m->B1;
         ssq = nullptr;
     }
     g.W = m->head; g.B = B; g.NT = (L.V + 15) / 16; g.KT = L.kt_d; g.N = L.V; g.m = n;
     g.ssq = ssq; g.n_ssq = L.d / 16; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
     g.epi = EPI_HEAD; g.head_part = m->head_part; g.head_counter = m->counters;
-    if ((rc = launch_gemm(g, L.planes, ctx))) return hip_fail(rc, who);
+    if ((rc = gemm(m, g, L.V, L.d, ctx))) return hip_fail(rc, who);
     return AD_OK;
 }
 
@@ -461,6 +492,45 @@ ad_status ad_head_logits(const ad_model *m, int32_t layer, const void *hidden, i
     memset(&g, 0, sizeof g);
     g.logits = (float *)logits;
     return (ad_status)run_head(m, layer, hidden, n, g, stream, "ad_head_logits");
+}
+
+// ---- measurement -------------------------------------------------------------------------------------
+
+static void profile_clear(Profile &p) {
+    for (void *e : p.start) event_destroy(e);
+    for (void *e : p.stop) event_destroy(e);
+    p.start.clear(); p.stop.clear(); p.bytes.clear();
+    p.launches = 0; p.total_bytes = 0; p.on = false;
+}
+
+ad_status ad_profile_start(ad_model *m, int32_t period, int32_t max_samples) {
+    if (!m) return (ad_status)fail(AD_EINVAL, "ad_profile_start: null model");
+    if (period < 1 || max_samples < 1 || max_samples > 65536) return (ad_status)fail(AD_ERANGE, "ad_profile_start: period >= 1 and 1 <= max_samples <= 65536");
+    profile_clear(m->prof);
+    m->prof.period = period;
+    m->prof.max_samples = max_samples;
+    m->prof.on = true;
+    return AD_OK;
+}
+
+ad_status ad_profile_stop(ad_model *m, int64_t *n_launches, int64_t *n_samples, double *sampled_ms, int64_t *sampled_bytes,
+                          int64_t *total_bytes) {
+    if (!m || !n_launches || !n_samples || !sampled_ms || !sampled_bytes || !total_bytes) return (ad_status)fail(AD_EINVAL, "ad_profile_stop: null argument");
+    Profile &p = m->prof;
+    if (!p.on) return (ad_status)fail(AD_ESTATE, "ad_profile_stop: profiling is not on");
+    double ms = 0.0;
+    int64_t bytes = 0, n = 0;
+    for (size_t i = 0; i < p.start.size(); ++i) {
+        float t = 0.f;
+        // waits for the stop event, so every sampled launch has finished when this loop ends
+        int rc = stream_sync_event(p.stop[i]);
+        if (!rc) rc = event_elapsed_ms(p.start[i], p.stop[i], &t);
+        if (rc) { profile_clear(p); return (ad_status)hip_fail(rc, "ad_profile_stop"); }
+        ms += t; bytes += p.bytes[i]; ++n;
+    }
+    *n_launches = p.launches; *n_samples = n; *sampled_ms = ms; *sampled_bytes = bytes; *total_bytes = p.total_bytes;
+    profile_clear(p);
+    return AD_OK;
 }
 
 // ---- Algorithm 1 over the GPU steps ------------------------------------------------------------------

@@ -112,6 +112,11 @@ int attn_chunk(int kv_is_bf16, int dh);   // cached positions per attention work
 int device_info(int *n_cu);
 const char *hip_error_text(int code);
 int stream_sync(void *stream);
+void *event_create();
+void event_destroy(void *ev);
+int event_record(void *ev, void *stream);
+int event_elapsed_ms(void *start, void *stop, float *ms);
+int stream_sync_event(void *ev);
 void *pinned_alloc(size_t bytes);
 void pinned_free(void *);
 

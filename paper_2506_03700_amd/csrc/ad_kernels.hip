@@ -675,6 +675,15 @@ int device_info(int *n_cu) {
 
 const char *hip_error_text(int code) { return hipGetErrorString((hipError_t)code); }
 int stream_sync(void *stream) { return (int)hipStreamSynchronize(S(stream)); }
+void *event_create() {
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return (void *)e;
+}
+void event_destroy(void *ev) { if (ev) (void)hipEventDestroy((hipEvent_t)ev); }
+int event_record(void *ev, void *stream) { return (int)hipEventRecord((hipEvent_t)ev, S(stream)); }
+int event_elapsed_ms(void *start, void *stop, float *ms) { return (int)hipEventElapsedTime(ms, (hipEvent_t)start, (hipEvent_t)stop); }
+int stream_sync_event(void *ev) { return (int)hipEventSynchronize((hipEvent_t)ev); }
 void *pinned_alloc(size_t bytes) {
     void *p = nullptr;
     if (hipHostMalloc(&p, bytes, hipHostMallocDefault) != hipSuccess) return nullptr;
