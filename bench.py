@@ -121,9 +121,10 @@ def main():
     micro = None
     if not args.skip_micro:
         micro = {}
-        view = g.kv_view()
+        K, V = g.kv_views()
         gen = torch.Generator(device="cuda").manual_seed(0)
-        view[:, :, :, :ctx_micro, :] = torch.randn(view[:, :, :, :ctx_micro, :].shape, generator=gen, device="cuda").to(view.dtype)
+        K[:, :, :ctx_micro, :] = torch.randn(K[:, :, :ctx_micro, :].shape, generator=gen, device="cuda").to(K.dtype)
+        V[:, :, :, :ctx_micro] = torch.randn(V[:, :, :, :ctx_micro].shape, generator=gen, device="cuda").to(V.dtype)
         L = shape.n_layers
         for m in (1, 2, 3, 4, 6, 8):
             h = torch.from_numpy(synth.make_hidden(shape, 1000 + m, m)).to("cuda")

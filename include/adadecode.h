@@ -83,9 +83,11 @@ ad_status ad_model_create(const ad_config *, const ad_layer_weights *layers /*ho
                           ad_model **out);
 ad_status ad_model_destroy(ad_model *);
 
-/* KV cache.  Storage layout (caller-visible, so that tests and benchmarks can fill or read it):
- *   [layer 0..L)[K then V][kv head][position 0..max_pos)[head_dim], elements of cfg.dtype, K stored
- *   after rotary embedding.  Entries at positions >= the layer's length are dead, not zeroed. */
+/* KV cache.  Storage layout (caller-visible, so that tests and benchmarks can fill or read it), with
+ * stride = max_pos rounded up to a multiple of 64 and elements of cfg.dtype:
+ *   per layer: K [kv head][position 0..stride)[head_dim]   (keys after rotary embedding)
+ *        then  V [kv head][head_dim][position 0..stride)   (transposed: positions are contiguous)
+ * Entries at positions >= the layer's length are dead, not zeroed. */
 size_t    ad_kv_bytes(const ad_config *, int32_t max_pos);
 ad_status ad_kv_create(const ad_model *, void *kv_storage /*dev*/, size_t kv_storage_bytes, int32_t max_pos, ad_kv **out);
 ad_status ad_kv_destroy(ad_kv *);

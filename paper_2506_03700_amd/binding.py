@@ -206,12 +206,35 @@ class Model:
     def kv_truncate(self, n: int) -> None:
         _check(self.L.ad_kv_truncate(self.kv, n))
 
-    def kv_view(self):
-        """The cache as a tensor [layer][K/V][kv head][position][head_dim] of the storage dtype (bf16 or fp32)."""
+    @property
+    def kv_stride(self) -> int:
+        return (self.max_pos + 63) // 64 * 64
+
+    def kv_views(self):
+        """(K, V): K as [layer][kv head][position][head_dim], V as [layer][kv head][head_dim][position]
+        (the library stores V transposed), positions 0..stride, of the storage dtype."""
         s, torch = self.shape, self.torch
         dt = torch.bfloat16 if s.dtype == AD_BF16 else torch.float32
-        n = s.n_layers * 2 * s.n_kv_heads * self.max_pos * s.head_dim
-        return self.kv_storage[: n * s.elem_bytes()].view(dt).view(s.n_layers, 2, s.n_kv_heads, self.max_pos, s.head_dim)
+        half = s.n_kv_heads * self.kv_stride * s.head_dim
+        flat = self.kv_storage[: s.n_layers * 2 * half * s.elem_bytes()].view(dt).view(s.n_layers, 2, half)
+        k = flat[:, 0].view(s.n_layers, s.n_kv_heads, self.kv_stride, s.head_dim)
+        v = flat[:, 1].view(s.n_layers, s.n_kv_heads, s.head_dim, self.kv_stride)
+        return k, v
+
+    def kv_fill(self, layer: int, k, v) -> None:
+        """Write positions [0, n) of one layer from arrays [n, kv heads, head_dim] (benchmarks, tests)."""
+        torch = self.torch
+        K, V = self.kv_views()
+        n = k.shape[0]
+        K[layer - 1, :, :n, :] = torch.as_tensor(k).permute(1, 0, 2).to(K.device).to(K.dtype)
+        V[layer - 1, :, :, :n] = torch.as_tensor(v).permute(1, 2, 0).to(V.device).to(V.dtype)
+
+    def kv_read(self, layer: int, n: int):
+        """Positions [0, n) of one layer as float64 numpy arrays [n, kv heads, head_dim]."""
+        K, V = self.kv_views()
+        k = K[layer - 1, :, :n, :].float().permute(1, 0, 2).cpu().numpy().astype(np.float64)
+        v = V[layer - 1, :, :, :n].float().permute(2, 0, 1).cpu().numpy().astype(np.float64)
+        return k, v
 
     # ---- steps (device tensors in, device tensors out) ----
     def ad_embed(self, tokens: Sequence[int]):

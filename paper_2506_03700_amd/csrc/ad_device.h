@@ -1,0 +1,46 @@
+// Device-side helpers shared by the library's kernels: vector types, bf16 conversion, and the index
+// function of the packed activation layout (see ad_internal.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ad {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+
+// ---------------------------------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// round-to-nearest-even fp32 -> bf16 bits (finite inputs)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ void split_hi_lo(float x, uint16_t &hi, uint16_t &lo) {
+    hi = f32_to_bf16_bits(x);
+    lo = f32_to_bf16_bits(x - bf16_bits_to_f32(hi));
+}
+
+__device__ __forceinline__ float load_w(const void *p, int is_bf16, size_t i) {
+    return is_bf16 ? bf16_bits_to_f32(((const uint16_t *)p)[i]) : ((const float *)p)[i];
+}
+
+// index (in bf16 elements) of input k of column col in a packed activation block
+__device__ __forceinline__ size_t act_index(int k, int col) {
+    return ((size_t)((k >> 5) * 4 + ((k & 31) >> 3)) * 16 + col) * 8 + (k & 7);
+}
+
+__device__ __forceinline__ void store_act(uint16_t *B, int k, int t, float v) {
+    uint16_t hi, lo;
+    split_hi_lo(v, hi, lo);
+    B[act_index(k, t)] = hi;
+    B[act_index(k, 8 + t)] = lo;
+}
+
+}  // namespace ad

@@ -144,6 +144,7 @@ struct ad_kv {
     const ad_model *model;
     char *storage;
     size_t layer_bytes, half_bytes;
+    int32_t stride;       // max_pos rounded up to 64: positions per (head, dim) row of V, rows per head of K
     float *part;
     int32_t max_pos;
     std::vector<int32_t> len;
@@ -276,7 +277,8 @@ size_t ad_kv_bytes(const ad_config *cfg, int32_t max_pos) {
     const char *why;
     if (!config_ok(cfg, &why) || max_pos < 1) { fail(AD_EINVAL, "ad_kv_bytes: %s", max_pos < 1 ? "max_pos < 1" : why); return 0; }
     const size_t elem = cfg->dtype == AD_BF16 ? 2 : 4;
-    const size_t cache = (size_t)cfg->n_layers * 2 * cfg->n_kv_heads * (size_t)max_pos * cfg->head_dim * elem;
+    const size_t stride = ((size_t)max_pos + 63) / 64 * 64;
+    const size_t cache = (size_t)cfg->n_layers * 2 * cfg->n_kv_heads * stride * cfg->head_dim * elem;
     return align_up(cache) + attn_part_bytes(*cfg, max_pos);
 }
 
@@ -291,7 +293,8 @@ ad_status ad_kv_create(const ad_model *model, void *kv_storage, size_t kv_storag
     const size_t elem = c.dtype == AD_BF16 ? 2 : 4;
     kv->model = model;
     kv->storage = (char *)kv_storage;
-    kv->half_bytes = (size_t)c.n_kv_heads * (size_t)max_pos * c.head_dim * elem;
+    kv->stride = (max_pos + 63) / 64 * 64;
+    kv->half_bytes = (size_t)c.n_kv_heads * (size_t)kv->stride * c.head_dim * elem;
     kv->layer_bytes = 2 * kv->half_bytes;
     kv->part = (float *)(kv->storage + align_up((size_t)c.n_layers * kv->layer_bytes));
     kv->max_pos = max_pos;
@@ -401,10 +404,10 @@ ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidde
     memset(&a, 0, sizeof a);
     a.qkv = m->qkv; a.ld = L.nqkv; a.rope = m->rope;
     a.Kc = kv->storage + (size_t)(layer - 1) * kv->layer_bytes; a.Vc = (char *)a.Kc + kv->half_bytes;
-    a.max_pos = kv->max_pos; a.pos0 = pos[0]; a.m = n; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = L.dh;
+    a.stride = kv->stride; a.pos0 = pos[0]; a.m = n; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = L.dh;
     a.C = attn_chunk(bf, L.dh);
     a.S = pos[0] > 0 ? (pos[0] + a.C - 1) / a.C : 1;
-    a.part = kv->part; a.counters = m->counters + 8; a.Bo = m->Bo; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_is_bf16 = bf;
+    a.part = kv->part; a.Bo = m->Bo; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_is_bf16 = bf;
     if ((rc = launch_attn(a, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: attention");
     // 4. x' = x + Wo o, and pack x' * ffn_norm
     memset(&g, 0, sizeof g);
@@ -459,7 +462,7 @@ static int run_head(const ad_model *m, int32_t layer, const void *hidden, int32_
     }
     g.W = m->head; g.B = B; g.NT = (L.V + 15) / 16; g.KT = L.kt_d; g.N = L.V; g.m = n;
     g.ssq = ssq; g.n_ssq = L.d / 16; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
-    g.epi = EPI_HEAD; g.head_part = m->head_part; g.head_counter = m->counters;
+    g.epi = EPI_HEAD; g.head_part = m->head_part;
     if ((rc = gemm(m, g, L.V, L.d, ctx))) return hip_fail(rc, who);
     return AD_OK;
 }

@@ -56,7 +56,7 @@ struct GemmArgs {
     float *ssq_next;      // [NT][8]
     // head
     float *head_part;     // [nwg][8][4] (max, sumexp, argmax as int bits, unused)
-    unsigned *head_counter;
+    int n_parts;          // workgroups that wrote head_part (set by the launcher)
     float *logits;        // null or [m][N]
     int32_t *tok_out;     // [m] (or null)
     float *conf_out;      // [m] (or null)
@@ -82,11 +82,11 @@ struct AttnArgs {
     const float *qkv;     // [m][ld]: q heads, then k heads, then v heads
     int ld;
     const float *rope;    // [m][dh/2][2]
-    void *Kc, *Vc;        // this layer's cache: [Hkv][max_pos][dh]
-    int max_pos, pos0, m, Hq, Hkv, dh;
+    void *Kc, *Vc;        // this layer's cache: K [Hkv][stride][dh], V [Hkv][dh][stride]
+    int stride;           // positions per cache row block (max_pos rounded up to 64)
+    int pos0, m, Hq, Hkv, dh;
     int C, S;             // chunk (positions per work item), splits
     float *part;          // [Hkv][S][R][dh+2]
-    unsigned *counters;   // [Hkv]
     void *Bo;             // packed attention output for the Wo GEMM
     float scale;
     int kv_is_bf16;
@@ -106,7 +106,7 @@ int launch_copy(const void *src, void *dst, size_t bytes, void *stream);
 int launch_zero(void *dst, size_t bytes, void *stream);
 int launch_embed(const EmbedArgs &, void *stream);
 int launch_pack(const PackArgs &, const LaunchCtx &);
-int launch_gemm(const GemmArgs &, int planes, const LaunchCtx &);
+int launch_gemm(const GemmArgs &, int planes, const LaunchCtx &);   // EPI_HEAD: also launches the vocabulary combine
 int launch_attn(const AttnArgs &, const LaunchCtx &);
 int attn_chunk(int kv_is_bf16, int dh);   // cached positions per attention work item
 int device_info(int *n_cu);

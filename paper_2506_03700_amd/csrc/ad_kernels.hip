@@ -9,46 +9,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "ad_device.h"
 #include "ad_internal.h"
 
 namespace ad {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
-
-// ---------------------------------------------------------------------------------------------------
-// small helpers
-// ---------------------------------------------------------------------------------------------------
-__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-
-// round-to-nearest-even fp32 -> bf16 bits (finite inputs)
-__device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
-    uint32_t u = __float_as_uint(x);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
-__device__ __forceinline__ void split_hi_lo(float x, uint16_t &hi, uint16_t &lo) {
-    hi = f32_to_bf16_bits(x);
-    lo = f32_to_bf16_bits(x - bf16_bits_to_f32(hi));
-}
-
-__device__ __forceinline__ float load_w(const void *p, int is_bf16, size_t i) {
-    return is_bf16 ? bf16_bits_to_f32(((const uint16_t *)p)[i]) : ((const float *)p)[i];
-}
-
-// index (in bf16 elements) of input k of column col in a packed activation block
-__device__ __forceinline__ size_t act_index(int k, int col) {
-    return ((size_t)((k >> 5) * 4 + ((k & 31) >> 3)) * 16 + col) * 8 + (k & 7);
-}
-
-__device__ __forceinline__ void store_act(uint16_t *B, int k, int t, float v) {
-    uint16_t hi, lo;
-    split_hi_lo(v, hi, lo);
-    B[act_index(k, t)] = hi;
-    B[act_index(k, 8 + t)] = lo;
-}
 
 // ---------------------------------------------------------------------------------------------------
 // weight re-layout (runs once, at model creation)
@@ -114,23 +78,29 @@ __global__ void k_embed(EmbedArgs a) {
 // 16 inputs of chunk c.  Also fills the rotary table for the call's positions.
 __device__ void pack_phase(const PackArgs &a, int wg, int nwg) {
     const int gtid = wg * blockDim.x + threadIdx.x, gsize = nwg * blockDim.x;
-    const int chunks = a.d / 16;
-    for (int idx = gtid; idx < chunks * a.m; idx += gsize) {
-        const int t = idx / chunks, c = idx % chunks;
-        const float *x = a.x + (size_t)t * a.d + c * 16;
+    const int groups = a.d / 8;       // one thread per (token, 8 consecutive inputs): two 128-bit stores
+    const int work = groups * a.m;
+    const int rounds = (work + gsize - 1) / gsize;
+    for (int it = 0; it < rounds; ++it) {
+        const int idx = gtid + it * gsize;
         float s = 0.0f;
-        uint16_t hi[16], lo[16];
-        for (int e = 0; e < 16; ++e) {
-            const float v = x[e];
-            s += v * v;
-            split_hi_lo(v * load_w(a.norm_w, a.norm_is_bf16, (size_t)c * 16 + e), hi[e], lo[e]);
+        if (idx < work) {
+            const int t = idx / groups, c = idx % groups;
+            const f32x4 x0 = *(const f32x4 *)(a.x + (size_t)t * a.d + c * 8), x1 = *(const f32x4 *)(a.x + (size_t)t * a.d + c * 8 + 4);
+            union { u32x4 v; uint16_t u[8]; } hi, lo;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float v = e < 4 ? x0[e] : x1[e - 4];
+                s += v * v;
+                split_hi_lo(v * load_w(a.norm_w, a.norm_is_bf16, (size_t)c * 8 + e), hi.u[e], lo.u[e]);
+            }
+            uint16_t *B = (uint16_t *)a.B;
+            *(u32x4 *)(B + act_index(c * 8, t)) = hi.v;
+            *(u32x4 *)(B + act_index(c * 8, 8 + t)) = lo.v;
         }
-        uint16_t *B = (uint16_t *)a.B;
-        for (int e = 0; e < 16; ++e) {
-            B[act_index(c * 16 + e, t)] = hi[e];
-            B[act_index(c * 16 + e, 8 + t)] = lo[e];
-        }
-        a.ssq[c * 8 + t] = s;
+        // ssq is kept per 16 inputs (the row-tile granularity of the GEMM epilogues): pairs of lanes
+        const float s2 = s + __shfl_xor(s, 1);
+        if (idx < work && (idx % groups) % 2 == 0) a.ssq[((idx % groups) / 2) * 8 + idx / groups] = s2;
     }
     if (a.rope) {
         const int half = a.head_dim / 2;
@@ -162,7 +132,6 @@ struct GemmLds {
     float scale[8];
     float run_max[8], run_sum[8];
     int run_idx[8];
-    int flag;
 };
 
 template <int NPL, int U>
@@ -332,33 +301,28 @@ __device__ void gemm_phase(const GemmArgs &g, int wg, int nwg, GemmLds &L) {
     }
     if (g.epi != EPI_HEAD) return;
 
-    // Vocabulary-wide combine: every workgroup publishes its per-token partial; the workgroup that arrives
-    // last folds all partials in workgroup order (fixed order, lowest token id wins ties) and writes the result.
+    // every workgroup publishes its per-token partial; k_head_combine folds them
     if (tid < g.m) {
         float *p = g.head_part + ((size_t)wg * 8 + tid) * 4;
         p[0] = L.run_max[tid];
         p[1] = L.run_sum[tid];
         p[2] = __int_as_float(L.run_idx[tid]);
     }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned old = __hip_atomic_fetch_add(g.head_counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        L.flag = (old + 1u == (unsigned)nwg);
-        if (L.flag) __hip_atomic_store(g.head_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    if (!L.flag) return;
-    __threadfence();
+}
+
+// Second pass of the vocabulary reduction: fold the per-workgroup (max, sum of exp, argmax) partials in
+// workgroup order (fixed order; the lowest token id wins ties), one wavefront per token, then apply the
+// verification rule of Eq. 2 at temperature 0 if asked.
+__global__ void __launch_bounds__(512) k_head_combine(GemmArgs g) {
+    __shared__ int idx_sh[8];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (wave < g.m) {
         const int t = wave;
         float M = -INFINITY, S = 0.f;
         int I = 0x7fffffff;
-        for (int w = lane; w < nwg; w += 64) {
+        for (int w = lane; w < g.n_parts; w += 64) {
             const float *p = g.head_part + ((size_t)w * 8 + t) * 4;
-            const float pm = __builtin_nontemporal_load(p), ps = __builtin_nontemporal_load(p + 1);
-            const int pi = __float_as_int(__builtin_nontemporal_load(p + 2));
-            lse_merge(M, S, I, pm, ps, pi);
+            lse_merge(M, S, I, p[0], p[1], __float_as_int(p[2]));
         }
         for (int off = 32; off > 0; off >>= 1) {
             const float m2 = __shfl_xor(M, off), s2 = __shfl_xor(S, off);
@@ -366,21 +330,20 @@ __device__ void gemm_phase(const GemmArgs &g, int wg, int nwg, GemmLds &L) {
             lse_merge(M, S, I, m2, s2, i2);
         }
         if (lane == 0) {
-            L.run_idx[t] = I;
-            L.run_sum[t] = S;
+            idx_sh[t] = I;
             if (g.tok_out) g.tok_out[t] = I;
             if (g.conf_out) g.conf_out[t] = 1.0f / S;   // exp(max - logsumexp)
         }
     }
     __syncthreads();
-    if (g.verify && tid == 0) {
-        // Eq. 2 at temperature 0: the first row whose final-layer token differs from the token drafted
-        // after it ends the accepted run and supplies the replacement.
+    if (g.verify && threadIdx.x == 0) {
+        // the first row whose final-layer token differs from the token drafted after it ends the accepted
+        // run and supplies the replacement
         int acc = g.m - 1;
         for (int j = 0; j < g.m - 1; ++j)
-            if (L.run_idx[j] != g.draft[j]) { acc = j; break; }
+            if (idx_sh[j] != g.draft[j]) { acc = j; break; }
         *g.n_accept_out = acc;
-        *g.next_out = L.run_idx[acc];
+        *g.next_out = idx_sh[acc];
     }
 }
 
@@ -388,196 +351,6 @@ template <int NPL, int U>
 __global__ void __launch_bounds__(kThreads) k_gemm(GemmArgs g) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     gemm_phase<NPL, U>(g, blockIdx.x, gridDim.x, *reinterpret_cast<GemmLds *>(lds_raw));
-}
-
-// ---------------------------------------------------------------------------------------------------
-// phase: rotary embedding + KV append + split-context grouped-query attention
-// ---------------------------------------------------------------------------------------------------
-// Work item (kv head g, split s): the cache positions [s*C, min((s+1)*C, pos0)) of that head, and for the
-// last split also the call's m new rows (rotated, rounded to the cache type, appended to the cache, and
-// attended to under the causal mask).  All G*m query rows of the group share the K/V tile staged in LDS.
-// Each item writes an unnormalised partial (max, sum, o[dh]) per query row; the workgroup that finishes a
-// head's last item combines the head's partials in split order and packs the result for the Wo GEMM.
-template <typename KVT>
-__device__ __forceinline__ float kv_to_f32(KVT v);
-template <>
-__device__ __forceinline__ float kv_to_f32<float>(float v) { return v; }
-template <>
-__device__ __forceinline__ float kv_to_f32<uint16_t>(uint16_t v) { return bf16_bits_to_f32(v); }
-template <typename KVT>
-__device__ __forceinline__ KVT f32_to_kv(float v);
-template <>
-__device__ __forceinline__ float f32_to_kv<float>(float v) { return v; }
-template <>
-__device__ __forceinline__ uint16_t f32_to_kv<uint16_t>(float v) { return f32_to_bf16_bits(v); }
-
-constexpr int kAttnMaxRows = 32;    // G*m query rows per kv head (more are processed in passes)
-// keys per work item: a chunk of cached positions plus up to 8 new rows; sized so that the K and V tiles fit LDS
-constexpr int attn_max_keys(size_t kv_elem, int dh) { return (kv_elem * dh <= 256) ? 136 : 72; }
-
-template <typename KVT, int DH>
-__device__ void attn_phase(const AttnArgs &a, int wg, int nwg, char *lds_raw) {
-    constexpr int KPAD = 16 / sizeof(KVT);            // row padding (elements) against LDS bank conflicts
-    constexpr int KROW = DH + KPAD;
-    constexpr int kAttnMaxKeys = attn_max_keys(sizeof(KVT), DH);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int G = a.Hq / a.Hkv, R = G * a.m;
-    float *qs = (float *)lds_raw;                                  // [kAttnMaxRows][DH]
-    float *sc = qs + kAttnMaxRows * DH;                            // [kAttnMaxRows][kAttnMaxKeys]
-    float *st = sc + kAttnMaxRows * kAttnMaxKeys;                  // [kAttnMaxRows][2]
-    int *flag = (int *)(st + kAttnMaxRows * 2);
-    KVT *Ks = (KVT *)(flag + 4);                                   // [kAttnMaxKeys][KROW]
-    KVT *Vs = Ks + kAttnMaxKeys * KROW;
-    const int half = DH / 2;
-    const int n_items = a.Hkv * a.S;
-    const size_t part_row = DH + 2;
-
-    for (int item = wg; item < n_items; item += nwg) {
-        const int g = item / a.S, s = item % a.S;
-        const int c0 = s * a.C, c1 = (c0 + a.C < a.pos0) ? c0 + a.C : a.pos0;
-        const int nc = (c1 > c0) ? c1 - c0 : 0;
-        const bool last = (s == a.S - 1);
-        const int nk = nc + (last ? a.m : 0);
-        KVT *Kg = (KVT *)a.Kc + (size_t)g * a.max_pos * DH, *Vg = (KVT *)a.Vc + (size_t)g * a.max_pos * DH;
-        // stage the cached chunk (contiguous in memory) with 128-bit loads
-        constexpr int VEC = 16 / sizeof(KVT);
-        for (int idx = tid; idx < nc * (DH / VEC); idx += kThreads) {
-            const int j = idx / (DH / VEC), c = idx % (DH / VEC);
-            *(u32x4 *)(Ks + j * KROW + c * VEC) = *(const u32x4 *)(Kg + (size_t)(c0 + j) * DH + c * VEC);
-            *(u32x4 *)(Vs + j * KROW + c * VEC) = *(const u32x4 *)(Vg + (size_t)(c0 + j) * DH + c * VEC);
-        }
-        // the call's own rows: rotate k, round to the cache type, append, and stage
-        if (last) {
-            for (int idx = tid; idx < a.m * half; idx += kThreads) {
-                const int t = idx / half, i = idx % half;
-                const float *kp = a.qkv + (size_t)t * a.ld + (size_t)a.Hq * DH + (size_t)g * DH;
-                const float *vp = kp + (size_t)a.Hkv * DH;
-                const float c = a.rope[(t * half + i) * 2], sn = a.rope[(t * half + i) * 2 + 1];
-                const float x = kp[i], y = kp[i + half];
-                const KVT k0 = f32_to_kv<KVT>(x * c - y * sn), k1 = f32_to_kv<KVT>(x * sn + y * c);
-                const KVT v0 = f32_to_kv<KVT>(vp[i]), v1 = f32_to_kv<KVT>(vp[i + half]);
-                Ks[(nc + t) * KROW + i] = k0;
-                Ks[(nc + t) * KROW + i + half] = k1;
-                Vs[(nc + t) * KROW + i] = v0;
-                Vs[(nc + t) * KROW + i + half] = v1;
-                const size_t o = (size_t)(a.pos0 + t) * DH;
-                Kg[o + i] = k0;
-                Kg[o + i + half] = k1;
-                Vg[o + i] = v0;
-                Vg[o + i + half] = v1;
-            }
-        }
-        for (int r0 = 0; r0 < R; r0 += kAttnMaxRows) {
-            const int nr = (R - r0 < kAttnMaxRows) ? R - r0 : kAttnMaxRows;
-            // rotated, pre-scaled queries
-            for (int idx = tid; idx < nr * half; idx += kThreads) {
-                const int rr = idx / half, i = idx % half, r = r0 + rr, t = r / G, hq = g * G + r % G;
-                const float *qp = a.qkv + (size_t)t * a.ld + (size_t)hq * DH;
-                const float c = a.rope[(t * half + i) * 2], sn = a.rope[(t * half + i) * 2 + 1];
-                const float x = qp[i], y = qp[i + half];
-                qs[rr * DH + i] = (x * c - y * sn) * a.scale;
-                qs[rr * DH + i + half] = (x * sn + y * c) * a.scale;
-            }
-            __syncthreads();
-            // scores
-            for (int p = tid; p < nr * nk; p += kThreads) {
-                const int rr = p / nk, j = p % nk, t = (r0 + rr) / G;
-                float acc = 0.f;
-                const KVT *kr = Ks + j * KROW;
-                const float *qr = qs + rr * DH;
-#pragma unroll 2
-                for (int e = 0; e < DH; e += VEC) {
-                    const u32x4 kw = *(const u32x4 *)(kr + e);
-                    if constexpr (sizeof(KVT) == 2) {
-                        const f32x4 q0 = *(const f32x4 *)(qr + e), q1 = *(const f32x4 *)(qr + e + 4);
-                        acc += q0[0] * __uint_as_float(kw[0] << 16) + q0[1] * __uint_as_float(kw[0] & 0xffff0000u) +
-                               q0[2] * __uint_as_float(kw[1] << 16) + q0[3] * __uint_as_float(kw[1] & 0xffff0000u) +
-                               q1[0] * __uint_as_float(kw[2] << 16) + q1[1] * __uint_as_float(kw[2] & 0xffff0000u) +
-                               q1[2] * __uint_as_float(kw[3] << 16) + q1[3] * __uint_as_float(kw[3] & 0xffff0000u);
-                    } else {
-                        const f32x4 q0 = *(const f32x4 *)(qr + e);
-                        acc += q0[0] * __uint_as_float(kw[0]) + q0[1] * __uint_as_float(kw[1]) +
-                               q0[2] * __uint_as_float(kw[2]) + q0[3] * __uint_as_float(kw[3]);
-                    }
-                }
-                if (j >= nc && j - nc > t) acc = -INFINITY;     // causal mask among the call's own rows
-                sc[rr * kAttnMaxKeys + j] = acc;
-            }
-            __syncthreads();
-            // per-row max and sum of exponentials (one wavefront per row)
-            for (int rr = wave; rr < nr; rr += kWaves) {
-                float mx = -INFINITY;
-                for (int j = lane; j < nk; j += 64) mx = fmaxf(mx, sc[rr * kAttnMaxKeys + j]);
-                for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-                float sum = 0.f;
-                for (int j = lane; j < nk; j += 64) {
-                    const float sv = sc[rr * kAttnMaxKeys + j];
-                    const float pv = (sv == -INFINITY) ? 0.f : __expf(sv - mx);
-                    sc[rr * kAttnMaxKeys + j] = pv;
-                    sum += pv;
-                }
-                for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-                if (lane == 0) {
-                    st[rr * 2] = mx;
-                    st[rr * 2 + 1] = sum;
-                }
-            }
-            __syncthreads();
-            // o = P V
-            for (int idx = tid; idx < nr * DH; idx += kThreads) {
-                const int rr = idx / DH, e = idx % DH;
-                float acc = 0.f;
-                for (int j = 0; j < nk; ++j) acc += sc[rr * kAttnMaxKeys + j] * kv_to_f32<KVT>(Vs[j * KROW + e]);
-                float *pr = a.part + (((size_t)g * a.S + s) * R + (r0 + rr)) * part_row;
-                pr[e] = acc;
-                if (e == 0) {
-                    pr[DH] = st[rr * 2];
-                    pr[DH + 1] = st[rr * 2 + 1];
-                }
-            }
-            __syncthreads();
-        }
-        // publish; the last item of this head to finish combines
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) {
-            const unsigned old = __hip_atomic_fetch_add(a.counters + g, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-            flag[0] = (old + 1u == (unsigned)a.S);
-            if (flag[0]) __hip_atomic_store(a.counters + g, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        __syncthreads();
-        if (flag[0]) {
-            __threadfence();
-            for (int idx = tid; idx < R * DH; idx += kThreads) {
-                const int r = idx / DH, e = idx % DH, t = r / G, hq = g * G + r % G;
-                float M = -INFINITY;
-                for (int ss = 0; ss < a.S; ++ss)
-                    M = fmaxf(M, __builtin_nontemporal_load(a.part + (((size_t)g * a.S + ss) * R + r) * part_row + DH));
-                float den = 0.f, num = 0.f;
-                for (int ss = 0; ss < a.S; ++ss) {
-                    const float *pr = a.part + (((size_t)g * a.S + ss) * R + r) * part_row;
-                    const float pm = __builtin_nontemporal_load(pr + DH);
-                    const float w = (pm == -INFINITY) ? 0.f : __expf(pm - M);
-                    den += w * __builtin_nontemporal_load(pr + DH + 1);
-                    num += w * __builtin_nontemporal_load(pr + e);
-                }
-                store_act((uint16_t *)a.Bo, hq * DH + e, t, num / den);
-            }
-        }
-        __syncthreads();
-    }
-}
-
-constexpr size_t attn_lds_bytes(size_t kv_elem, int dh) {
-    return (size_t)kAttnMaxRows * dh * 4 + (size_t)kAttnMaxRows * attn_max_keys(kv_elem, dh) * 4 + kAttnMaxRows * 2 * 4 + 16 +
-           2 * (size_t)attn_max_keys(kv_elem, dh) * (dh + 16 / kv_elem) * kv_elem;
-}
-int attn_chunk(int kv_is_bf16, int dh) { return attn_max_keys(kv_is_bf16 ? 2 : 4, dh) - 8; }
-
-template <typename KVT, int DH>
-__global__ void __launch_bounds__(kThreads) k_attn(AttnArgs a) {
-    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    attn_phase<KVT, DH>(a, blockIdx.x, gridDim.x, lds_raw);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -611,7 +384,7 @@ int launch_embed(const EmbedArgs &a, void *stream) {
 }
 
 int launch_pack(const PackArgs &a, const LaunchCtx &c) {
-    const int work = (a.d / 16) * a.m;
+    const int work = (a.d / 8) * a.m;
     int grid = (work + 255) / 256;
     if (grid < 1) grid = 1;
     hipLaunchKernelGGL(k_pack, dim3(grid), dim3(256), 0, S(c.stream), a);
@@ -633,33 +406,12 @@ int launch_gemm(const GemmArgs &g, int planes, const LaunchCtx &c) {
         hipLaunchKernelGGL((k_gemm<1, 8>), dim3(grid), dim3(kThreads), sizeof(GemmLds), S(c.stream), g);
     else
         hipLaunchKernelGGL((k_gemm<3, 2>), dim3(grid), dim3(kThreads), sizeof(GemmLds), S(c.stream), g);
-    return (int)hipGetLastError();
-}
-
-template <typename KVT, int DH>
-static int launch_attn_t(const AttnArgs &a, const LaunchCtx &c) {
-    const size_t lds = attn_lds_bytes(sizeof(KVT), DH);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_attn<KVT, DH>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return (int)e;
-        attr_set = true;
+    if (g.epi == EPI_HEAD) {
+        GemmArgs h = g;
+        h.n_parts = grid;
+        hipLaunchKernelGGL(k_head_combine, dim3(1), dim3(512), 0, S(c.stream), h);
     }
-    int grid = a.Hkv * a.S;
-    if (grid > c.n_wg) grid = c.n_wg;
-    hipLaunchKernelGGL((k_attn<KVT, DH>), dim3(grid), dim3(kThreads), lds, S(c.stream), a);
     return (int)hipGetLastError();
-}
-
-int launch_attn(const AttnArgs &a, const LaunchCtx &c) {
-    if (a.kv_is_bf16) {
-        if (a.dh == 128) return launch_attn_t<uint16_t, 128>(a, c);
-        if (a.dh == 64) return launch_attn_t<uint16_t, 64>(a, c);
-    } else {
-        if (a.dh == 128) return launch_attn_t<float, 128>(a, c);
-        if (a.dh == 64) return launch_attn_t<float, 64>(a, c);
-    }
-    return (int)hipErrorInvalidValue;
 }
 
 int device_info(int *n_cu) {

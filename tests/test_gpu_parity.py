@@ -34,8 +34,7 @@ def ad():
 
 def gpu_kv(model, layer, n):
     """K, V of one layer for positions [0, n) as float64 [n, Hkv, dh]."""
-    v = model.kv_view()[layer - 1, :, :, :n, :].float().cpu().numpy().astype(np.float64)
-    return v[0].transpose(1, 0, 2), v[1].transpose(1, 0, 2)
+    return model.kv_read(layer, n)
 
 
 UNTIED = synth.TINY.with_(name="tiny-untied", tied_head=False, vocab=512, exit_layers=(1, 2, 3))
@@ -97,9 +96,7 @@ def test_layer_step_full_width_shapes(ad, shape, ctx):
     g = ad.Model(shape, w, max_pos=ctx + 8)
     k, v = synth.make_kv_prefill(shape, 0, 0, ctx)
     o.kv_write(1, 0, k.reshape(ctx, -1), v.reshape(ctx, -1))
-    view = g.kv_view()
-    view[0, 0, :, :ctx, :] = torch.from_numpy(k.transpose(1, 0, 2).copy()).to(view.dtype).to(view.device)
-    view[0, 1, :, :ctx, :] = torch.from_numpy(v.transpose(1, 0, 2).copy()).to(view.dtype).to(view.device)
+    g.kv_fill(1, k, v)
     for call, m in enumerate([1, 2, 3, 4, 6, 8, 8, 1]):
         print(f"case {shape.name} m={m} call={call}", flush=True)
         o.kv_set_len(1, ctx)
