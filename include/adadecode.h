@@ -50,7 +50,8 @@ typedef enum { AD_F32 = 0, AD_BF16 = 1 } ad_dtype;
 enum { AD_MAX_EXIT = 8, AD_M_MAX = 8 };
 
 typedef struct {
-    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;   /* d_model % 16 == 0, <= 5120 (fp32: 2048),
+                                                                                   head_dim 64 or 128, d_ffn % 8 == 0 */
     float   rope_base, rms_eps;
     int32_t dtype;                       /* ad_dtype: storage of the weights passed in and of the KV cache */
     int32_t n_exit;                      /* number of exit heads */
@@ -89,7 +90,9 @@ ad_status ad_model_destroy(ad_model *);
  *        then  V [kv head][head_dim][position 0..stride)   (transposed: positions are contiguous)
  * Entries at positions >= the layer's length are dead, not zeroed. */
 size_t    ad_kv_bytes(const ad_config *, int32_t max_pos);
-ad_status ad_kv_create(const ad_model *, void *kv_storage /*dev*/, size_t kv_storage_bytes, int32_t max_pos, ad_kv **out);
+/* Also fills the cache's rotary table on `stream` and synchronises it. */
+ad_status ad_kv_create(const ad_model *, void *kv_storage /*dev*/, size_t kv_storage_bytes, int32_t max_pos, void *stream,
+                       ad_kv **out);
 ad_status ad_kv_destroy(ad_kv *);
 ad_status ad_kv_len(const ad_kv *, int32_t layer, int32_t *len);
 ad_status ad_kv_set_len(ad_kv *, int32_t layer, int32_t len);   /* declare a prefilled cache (benchmarks) */

@@ -85,7 +85,7 @@ def lib() -> C.CDLL:
         L.ad_model_destroy.argtypes = [P]
         L.ad_kv_bytes.restype = sz
         L.ad_kv_bytes.argtypes = [C.POINTER(Config), i32]
-        L.ad_kv_create.argtypes = [P, P, sz, i32, C.POINTER(P)]
+        L.ad_kv_create.argtypes = [P, P, sz, i32, P, C.POINTER(P)]
         L.ad_kv_destroy.argtypes = [P]
         L.ad_kv_len.argtypes = [P, i32, C.POINTER(i32)]
         L.ad_kv_set_len.argtypes = [P, i32, i32]
@@ -173,7 +173,7 @@ class Model:
         self.max_pos = max_pos
         kv_bytes = self.L.ad_kv_bytes(C.byref(self.cfg), max_pos)
         self.kv_storage = torch.zeros(kv_bytes, dtype=torch.uint8, device=self.device)
-        _check(self.L.ad_kv_create(self.model, C.c_void_p(self.kv_storage.data_ptr()), kv_bytes, max_pos, C.byref(self.kv)))
+        _check(self.L.ad_kv_create(self.model, C.c_void_p(self.kv_storage.data_ptr()), kv_bytes, max_pos, _stream_ptr(torch), C.byref(self.kv)))
         self._pinned = torch.zeros(64, dtype=torch.int32).pin_memory()
 
     def close(self) -> None:

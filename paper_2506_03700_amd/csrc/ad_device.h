@@ -31,6 +31,28 @@ __device__ __forceinline__ float load_w(const void *p, int is_bf16, size_t i) {
     return is_bf16 ? bf16_bits_to_f32(((const uint16_t *)p)[i]) : ((const float *)p)[i];
 }
 
+// eight consecutive weights starting at element k (k a multiple of 8); a null vector means all ones
+__device__ __forceinline__ void load_w8(const void *p, int is_bf16, size_t k, float (&w)[8]) {
+    if (!p) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[e] = 1.0f;
+    } else if (is_bf16) {
+        const u32x4 v = *(const u32x4 *)((const uint16_t *)p + k);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            w[2 * e] = __uint_as_float(v[e] << 16);
+            w[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
+        }
+    } else {
+        const f32x4 v0 = *(const f32x4 *)((const float *)p + k), v1 = *(const f32x4 *)((const float *)p + k + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            w[e] = v0[e];
+            w[4 + e] = v1[e];
+        }
+    }
+}
+
 // index (in bf16 elements) of input k of column col in a packed activation block
 __device__ __forceinline__ size_t act_index(int k, int col) {
     return ((size_t)((k >> 5) * 4 + ((k & 31) >> 3)) * 16 + col) * 8 + (k & 7);

@@ -68,6 +68,7 @@ bool config_ok(const ad_config *c, const char **why) {
         if (i && c->exit_layers[i] <= c->exit_layers[i - 1]) { *why = "exit layers must ascend"; return false; }
     }
     if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) { *why = "bad rope_base / rms_eps"; return false; }
+    if (c->d_model > gemm_max_stationary_k(c->dtype == AD_BF16 ? 1 : 3)) { *why = "d_model too large (bf16: up to 5120, fp32: up to 2048)"; return false; }
     return true;
 }
 
@@ -96,18 +97,13 @@ void make_layout(const ad_config &c, Layout &L) {
     L.off_head = off; off += L.sz_head;
     for (int i = 0; i < AD_MAX_EXIT; ++i) { L.off_T[i] = off; if (i < c.n_exit) off += L.sz_T; }
     L.off_scratch = off;
-    // scratch: see Scratch below
     size_t s = 0;
-    s += 2 * align_up(act_packed_bytes(L.d));                  // B0, B1
-    s += align_up(act_packed_bytes(L.dq));                     // Bo
-    s += align_up(act_packed_bytes(L.f));                      // Bg
-    s += 2 * align_up((size_t)(L.d / 16) * 8 * 4);             // ssq0, ssq1
+    s += align_up(act_packed_bytes(L.d));                      // B1 (exit-head transform output)
+    s += align_up(act_packed_bytes(L.dq));                     // Bo (attention output)
+    s += align_up(act_packed_bytes(L.f));                      // Bg (SwiGLU output)
     s += align_up((size_t)8 * L.nqkv * 4);                     // qkv
     s += 2 * align_up((size_t)8 * L.d * 4);                    // x1, rows
-    s += align_up((size_t)8 * (L.dh / 2) * 2 * 4);             // rope
-    s += align_up((size_t)(L.dh / 2) * 8);                     // inv_freq
     s += align_up((size_t)4096 * 8 * 4 * 4);                   // head partials (up to 4096 workgroups)
-    s += align_up(256 * 4);                                    // counters
     L.scratch_bytes = s;
     L.total = off + s;
 }
@@ -131,10 +127,8 @@ struct ad_model {
     std::vector<LayerPacked> layers;
     char *embed, *final_norm, *head, *T[AD_MAX_EXIT];
     // scratch
-    char *B0, *B1, *Bo, *Bg;
-    float *ssq0, *ssq1, *qkv, *x1, *rows, *rope, *head_part;
-    double *inv_freq;
-    unsigned *counters;   // [0] head, [8..8+Hkv) attention
+    char *B1, *Bo, *Bg;
+    float *qkv, *x1, *rows, *head_part;
     // pinned host results for ad_generate
     int32_t *pin;         // [0..8) tok, [8] n_accept, [9] next, [16..24) row argmax
     float *pin_conf;      // [8]
@@ -144,6 +138,7 @@ struct ad_kv {
     const ad_model *model;
     char *storage;
     size_t layer_bytes, half_bytes;
+    float *rope;          // [stride][dh/2][2]
     int32_t stride;       // max_pos rounded up to 64: positions per (head, dim) row of V, rows per head of K
     float *part;
     int32_t max_pos;
@@ -230,26 +225,16 @@ ad_status ad_model_create(const ad_config *cfg, const ad_layer_weights *layers, 
     }
     char *s = m->ws + L.off_scratch;
     auto take = [&](size_t bytes) { char *p = s; s += align_up(bytes); return p; };
-    m->B0 = take(act_packed_bytes(L.d));
     m->B1 = take(act_packed_bytes(L.d));
     m->Bo = take(act_packed_bytes(L.dq));
     m->Bg = take(act_packed_bytes(L.f));
-    m->ssq0 = (float *)take((size_t)(L.d / 16) * 8 * 4);
-    m->ssq1 = (float *)take((size_t)(L.d / 16) * 8 * 4);
     m->qkv = (float *)take((size_t)8 * L.nqkv * 4);
     m->x1 = (float *)take((size_t)8 * L.d * 4);
     m->rows = (float *)take((size_t)8 * L.d * 4);
-    m->rope = (float *)take((size_t)8 * (L.dh / 2) * 2 * 4);
-    m->inv_freq = (double *)take((size_t)(L.dh / 2) * 8);
     m->head_part = (float *)take((size_t)4096 * 8 * 4 * 4);
-    m->counters = (unsigned *)take(256 * 4);
-    // rotary frequencies base^(-2i/dh), computed in double on the host and staged through pinned memory
     m->pin = (int32_t *)pinned_alloc(4096);
     if (!m->pin) { delete m; return (ad_status)fail(AD_ENOMEM, "ad_model_create: pinned allocation failed"); }
     m->pin_conf = (float *)(m->pin + 32);
-    double *pf = (double *)(m->pin + 64);
-    for (int i = 0; i < L.dh / 2; ++i) pf[i] = pow((double)cfg->rope_base, -2.0 * (double)i / (double)L.dh);
-    AD_TRY(launch_copy(pf, m->inv_freq, align_up((size_t)(L.dh / 2) * 8, 16), stream), "copy inv_freq");
     AD_TRY(stream_sync(stream), "model creation");
 #undef AD_TRY
     *out = m;
@@ -267,6 +252,11 @@ ad_status ad_model_destroy(ad_model *m) {
 
 // ---- KV cache --------------------------------------------------------------------------------------
 
+static size_t rope_table_bytes(const ad_config &c, int32_t max_pos) {
+    const size_t stride = ((size_t)max_pos + 63) / 64 * 64;
+    return align_up(stride * (c.head_dim / 2) * 2 * 4);
+}
+
 static size_t attn_part_bytes(const ad_config &c, int32_t max_pos) {
     const int C = attn_chunk(c.dtype == AD_BF16, c.head_dim);
     const size_t S = (size_t)(max_pos + C - 1) / C + 1;
@@ -279,10 +269,10 @@ size_t ad_kv_bytes(const ad_config *cfg, int32_t max_pos) {
     const size_t elem = cfg->dtype == AD_BF16 ? 2 : 4;
     const size_t stride = ((size_t)max_pos + 63) / 64 * 64;
     const size_t cache = (size_t)cfg->n_layers * 2 * cfg->n_kv_heads * stride * cfg->head_dim * elem;
-    return align_up(cache) + attn_part_bytes(*cfg, max_pos);
+    return align_up(cache) + attn_part_bytes(*cfg, max_pos) + rope_table_bytes(*cfg, max_pos);
 }
 
-ad_status ad_kv_create(const ad_model *model, void *kv_storage, size_t kv_storage_bytes, int32_t max_pos, ad_kv **out) {
+ad_status ad_kv_create(const ad_model *model, void *kv_storage, size_t kv_storage_bytes, int32_t max_pos, void *stream, ad_kv **out) {
     if (!model || !kv_storage || !out || max_pos < 1) return (ad_status)fail(AD_EINVAL, "ad_kv_create: bad argument");
     if (((uintptr_t)kv_storage & 255u) != 0) return (ad_status)fail(AD_EINVAL, "ad_kv_create: storage must be 256-byte aligned");
     const size_t need = ad_kv_bytes(&model->cfg, max_pos);
@@ -297,8 +287,16 @@ ad_status ad_kv_create(const ad_model *model, void *kv_storage, size_t kv_storag
     kv->half_bytes = (size_t)c.n_kv_heads * (size_t)kv->stride * c.head_dim * elem;
     kv->layer_bytes = 2 * kv->half_bytes;
     kv->part = (float *)(kv->storage + align_up((size_t)c.n_layers * kv->layer_bytes));
+    kv->rope = (float *)((char *)kv->part + attn_part_bytes(c, max_pos));
     kv->max_pos = max_pos;
     kv->len.assign(c.n_layers, 0);
+    // rotary table for every position of this cache; frequencies base^(-2i/dh) in double
+    RopeArgs ra;
+    ra.table = kv->rope; ra.n_pos = kv->stride; ra.half = c.head_dim / 2;
+    for (int i = 0; i < ra.half; ++i) ra.inv_freq[i] = pow((double)c.rope_base, -2.0 * (double)i / (double)c.head_dim);
+    int rc = launch_rope_table(ra, stream);
+    if (!rc) rc = stream_sync(stream);
+    if (rc) { delete kv; return (ad_status)hip_fail(rc, "ad_kv_create: rotary table"); }
     *out = kv;
     return AD_OK;
 }
@@ -387,43 +385,37 @@ ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidde
     const LaunchCtx ctx{stream, m->n_wg};
     const int bf = c.dtype == AD_BF16;
     int rc;
-    // 1. pack x * attn_norm, partial sums of squares, rotary table
-    PackArgs pa;
-    pa.x = (const float *)hidden; pa.m = n; pa.d = L.d; pa.norm_w = lp.attn_norm; pa.norm_is_bf16 = bf; pa.B = m->B0; pa.ssq = m->ssq0;
-    pa.rope = m->rope; pa.pos0 = pos[0]; pa.head_dim = L.dh; pa.inv_freq = m->inv_freq;
-    if ((rc = launch_pack(pa, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: pack");
-    // 2. q, k, v
+    // 1. q, k, v = W (RMSNorm(x)): the norm is fused into the GEMM (B operand built from x in its prologue)
     GemmArgs g;
     memset(&g, 0, sizeof g);
-    g.W = lp.wqkv; g.B = m->B0; g.NT = L.nqkv / 16; g.KT = L.kt_d; g.N = L.nqkv; g.m = n;
-    g.ssq = m->ssq0; g.n_ssq = L.d / 16; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
+    g.W = lp.wqkv; g.NT = L.nqkv / 16; g.KT = L.kt_d; g.N = L.nqkv; g.K = L.d; g.m = n; g.mode = GEMM_STATIONARY;
+    g.x = (const float *)hidden; g.ldx = L.d; g.norm_w = lp.attn_norm; g.norm_is_bf16 = bf; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
     g.epi = EPI_STORE; g.out = m->qkv; g.ld = L.nqkv;
     if ((rc = gemm(m, g, L.nqkv, L.d, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: qkv");
-    // 3. rotary embedding, KV append, attention
+    // 2. rotary embedding, KV append, attention (partials + combine)
     AttnArgs a;
     memset(&a, 0, sizeof a);
-    a.qkv = m->qkv; a.ld = L.nqkv; a.rope = m->rope;
+    a.qkv = m->qkv; a.ld = L.nqkv; a.rope = kv->rope + (size_t)pos[0] * (L.dh / 2) * 2;
     a.Kc = kv->storage + (size_t)(layer - 1) * kv->layer_bytes; a.Vc = (char *)a.Kc + kv->half_bytes;
     a.stride = kv->stride; a.pos0 = pos[0]; a.m = n; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = L.dh;
     a.C = attn_chunk(bf, L.dh);
     a.S = pos[0] > 0 ? (pos[0] + a.C - 1) / a.C : 1;
     a.part = kv->part; a.Bo = m->Bo; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_is_bf16 = bf;
     if ((rc = launch_attn(a, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: attention");
-    // 4. x' = x + Wo o, and pack x' * ffn_norm
+    // 3. x' = x + Wo o
     memset(&g, 0, sizeof g);
-    g.W = lp.wo; g.B = m->Bo; g.NT = L.d / 16; g.KT = L.kt_q; g.N = L.d; g.m = n;
+    g.W = lp.wo; g.B = m->Bo; g.NT = L.d / 16; g.KT = L.kt_q; g.N = L.d; g.K = L.dq; g.m = n; g.mode = GEMM_STREAMED;
     g.epi = EPI_RESID; g.resid = (const float *)hidden; g.out = m->x1; g.ld = L.d;
-    g.norm_w = lp.ffn_norm; g.norm_is_bf16 = bf; g.Bnext = m->B1; g.ssq_next = m->ssq1;
     if ((rc = gemm(m, g, L.d, L.dq, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: wo");
-    // 5. silu(Wg b) * (Wu b)
+    // 4. g = silu(Wg b) * (Wu b), b = RMSNorm(x') fused as in step 1
     memset(&g, 0, sizeof g);
-    g.W = lp.wgu; g.B = m->B1; g.NT = (2 * L.f) / 16; g.KT = L.kt_d; g.N = 2 * L.f; g.m = n;
-    g.ssq = m->ssq1; g.n_ssq = L.d / 16; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
+    g.W = lp.wgu; g.NT = (2 * L.f) / 16; g.KT = L.kt_d; g.N = 2 * L.f; g.K = L.d; g.m = n; g.mode = GEMM_STATIONARY;
+    g.x = m->x1; g.ldx = L.d; g.norm_w = lp.ffn_norm; g.norm_is_bf16 = bf; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
     g.epi = EPI_SWIGLU; g.Bnext = m->Bg;
     if ((rc = gemm(m, g, 2 * (int64_t)L.f, L.d, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: gate/up");
-    // 6. y = x' + Wd g
+    // 5. y = x' + Wd g
     memset(&g, 0, sizeof g);
-    g.W = lp.wd; g.B = m->Bg; g.NT = L.d / 16; g.KT = L.kt_f; g.N = L.d; g.m = n;
+    g.W = lp.wd; g.B = m->Bg; g.NT = L.d / 16; g.KT = L.kt_f; g.N = L.d; g.K = L.f; g.m = n; g.mode = GEMM_STREAMED;
     g.epi = EPI_RESID; g.resid = m->x1; g.out = (float *)hidden; g.ld = L.d;
     if ((rc = gemm(m, g, L.d, L.f, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: down");
     kv->len[layer - 1] += n;
@@ -443,26 +435,20 @@ static int run_head(const ad_model *m, int32_t layer, const void *hidden, int32_
     const LaunchCtx ctx{stream, m->n_wg};
     const int bf = c.dtype == AD_BF16;
     int rc;
-    PackArgs pa;
-    memset(&pa, 0, sizeof pa);
-    pa.x = (const float *)hidden; pa.m = n; pa.d = L.d; pa.norm_w = m->final_norm; pa.norm_is_bf16 = bf; pa.B = m->B0; pa.ssq = m->ssq0;
-    if ((rc = launch_pack(pa, ctx))) return hip_fail(rc, who);
-    const void *B = m->B0;
-    const float *ssq = m->ssq0;
+    g.W = m->head; g.NT = (L.V + 15) / 16; g.KT = L.kt_d; g.N = L.V; g.K = L.d; g.m = n; g.mode = GEMM_STATIONARY;
+    g.epi = EPI_HEAD; g.head_part = m->head_part;
     if (slot >= 0 && m->T[slot]) {
-        // lightweight head of Sec. 2.1: E = E* T, applied as E* (T n)
+        // lightweight head of Sec. 2.1: E = E* T, applied as E* (T norm(h))
         GemmArgs t;
         memset(&t, 0, sizeof t);
-        t.W = m->T[slot]; t.B = m->B0; t.NT = L.d / 16; t.KT = L.kt_d; t.N = L.d; t.m = n;
-        t.ssq = m->ssq0; t.n_ssq = L.d / 16; t.inv_dim = 1.0f / (float)L.d; t.eps = c.rms_eps;
+        t.W = m->T[slot]; t.NT = L.d / 16; t.KT = L.kt_d; t.N = L.d; t.K = L.d; t.m = n; t.mode = GEMM_STATIONARY;
+        t.x = (const float *)hidden; t.ldx = L.d; t.norm_w = m->final_norm; t.norm_is_bf16 = bf; t.inv_dim = 1.0f / (float)L.d; t.eps = c.rms_eps;
         t.epi = EPI_PACK; t.Bnext = m->B1;
         if ((rc = gemm(m, t, L.d, L.d, ctx))) return hip_fail(rc, who);
-        B = m->B1;
-        ssq = nullptr;
+        g.B = m->B1;
+    } else {
+        g.x = (const float *)hidden; g.ldx = L.d; g.norm_w = m->final_norm; g.norm_is_bf16 = bf; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
     }
-    g.W = m->head; g.B = B; g.NT = (L.V + 15) / 16; g.KT = L.kt_d; g.N = L.V; g.m = n;
-    g.ssq = ssq; g.n_ssq = L.d / 16; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
-    g.epi = EPI_HEAD; g.head_part = m->head_part;
     if ((rc = gemm(m, g, L.V, L.d, ctx))) return hip_fail(rc, who);
     return AD_OK;
 }

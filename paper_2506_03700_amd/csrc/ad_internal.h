@@ -31,29 +31,32 @@ inline size_t packed_bytes(int64_t N, int64_t K, int planes) {
 inline size_t act_packed_bytes(int64_t K) { return (size_t)((K + kTileK - 1) / kTileK) * 1024u; }
 
 enum EpiKind : int { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3, EPI_PACK = 4 };
+enum GemmMode : int { GEMM_STREAMED = 0, GEMM_STATIONARY = 1 };
 
 struct GemmArgs {
     const void *W;        // packed weights
-    const void *B;        // packed activations
     int NT, KT;           // row tiles, k-steps
-    int N;                // valid output rows (EPI_SWIGLU: rows of the interleaved gate/up matrix = 2F)
+    int N, K;             // valid output rows (EPI_SWIGLU: rows of the interleaved gate/up matrix = 2F), valid inputs
     int m;                // tokens
-    const float *ssq;     // [n_ssq][8] partial sums of squares of the un-normalised input, or null (scale 1)
-    int n_ssq;
-    float inv_dim, eps;   // scale_t = rsqrt(sum_t * inv_dim + eps)
+    int mode;             // GemmMode
+    // activations: either fp32 rows x [m][ldx] (stationary mode; multiplied by norm_w and, in the epilogue, by
+    // rsqrt(mean(x^2) + eps) when norm_w is given), or a packed block B
+    const float *x;
+    int ldx;
+    const void *norm_w;
+    int norm_is_bf16;
+    float inv_dim, eps;
+    const void *B;
     int epi;
     // EPI_STORE: out[t*ld + n] = scale_t * acc
-    // EPI_RESID: y = resid[t*ld + n] + acc; out[t*ld + n] = y; optionally pack y*norm_w for the next GEMM
+    // EPI_RESID: out[t*ld + n] = resid[t*ld + n] + acc
     // EPI_SWIGLU: tile rows 0..7 gate, 8..15 up of features tile*8 .. +8; packs silu(gate)*up into Bnext
     // EPI_PACK: packs scale_t * acc into Bnext (used for the exit-head transform T)
-    // EPI_HEAD: per-token argmax / log-sum-exp over all rows, combined across workgroups
+    // EPI_HEAD: per-token argmax / log-sum-exp over all rows; partials per workgroup, folded by a second kernel
     float *out;
     const float *resid;
     int ld;
-    const void *norm_w;   // next norm weights (cfg dtype) or null
-    int norm_is_bf16;
-    void *Bnext;          // packed activations written by the epilogue, or null
-    float *ssq_next;      // [NT][8]
+    void *Bnext;          // packed activations written by the epilogue
     // head
     float *head_part;     // [nwg][8][4] (max, sumexp, argmax as int bits, unused)
     int n_parts;          // workgroups that wrote head_part (set by the launcher)
@@ -65,23 +68,16 @@ struct GemmArgs {
     int verify;
 };
 
-struct PackArgs {
-    const float *x;       // [m][d]
-    int m, d;
-    const void *norm_w;
-    int norm_is_bf16;
-    void *B;              // packed out
-    float *ssq;           // [d/16][8]
-    // rotary table
-    float *rope;          // [m][dh/2][2] (cos, sin) or null
-    int pos0, head_dim;
-    const double *inv_freq;  // [dh/2]
+struct RopeArgs {
+    float *table;         // [n_pos][half][2] (cos, sin)
+    int n_pos, half;
+    double inv_freq[64];  // base^(-2i/dh)
 };
 
 struct AttnArgs {
     const float *qkv;     // [m][ld]: q heads, then k heads, then v heads
     int ld;
-    const float *rope;    // [m][dh/2][2]
+    const float *rope;    // [m][dh/2][2]: rows pos0 .. pos0+m-1 of the cache's rotary table
     void *Kc, *Vc;        // this layer's cache: K [Hkv][stride][dh], V [Hkv][dh][stride]
     int stride;           // positions per cache row block (max_pos rounded up to 64)
     int pos0, m, Hq, Hkv, dh;
@@ -105,7 +101,8 @@ int launch_pack_weights(const void *src, const void *src2, int src_is_bf16, int6
 int launch_copy(const void *src, void *dst, size_t bytes, void *stream);
 int launch_zero(void *dst, size_t bytes, void *stream);
 int launch_embed(const EmbedArgs &, void *stream);
-int launch_pack(const PackArgs &, const LaunchCtx &);
+int launch_rope_table(const RopeArgs &, void *stream);
+int gemm_max_stationary_k(int planes);   // largest d_model the stationary GEMM variants cover
 int launch_gemm(const GemmArgs &, int planes, const LaunchCtx &);   // EPI_HEAD: also launches the vocabulary combine
 int launch_attn(const AttnArgs &, const LaunchCtx &);
 int attn_chunk(int kv_is_bf16, int dh);   // cached positions per attention work item
