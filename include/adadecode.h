@@ -50,7 +50,7 @@ typedef enum { AD_F32 = 0, AD_BF16 = 1 } ad_dtype;
 enum { AD_MAX_EXIT = 8, AD_M_MAX = 8 };
 
 typedef struct {
-    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;   /* d_model % 16 == 0, <= 5120 (fp32: 2048),
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;   /* d_model % 16 == 0 and <= 5120,
                                                                                    head_dim 64 or 128, d_ffn % 8 == 0 */
     float   rope_base, rms_eps;
     int32_t dtype;                       /* ad_dtype: storage of the weights passed in and of the KV cache */

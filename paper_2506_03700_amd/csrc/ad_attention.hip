@@ -85,31 +85,58 @@ __global__ void __launch_bounds__(kAttnThreads) k_attn_mfma(AttnArgs a) {
                 Vg[(size_t)(i + half) * a.stride + p] = v1;
             }
         }
+        // this wavefront's cached block goes in flight first: it does not depend on the queries
+        const int kb0 = c0 + wave * 32;           // first cached position of the block
+        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+        bf16x8 kc[2][KS], vc[DT];
+        if (wave < nbc) {
+#pragma unroll
+            for (int aa = 0; aa < 2; ++aa) {
+                int key = kb0 + 8 * (n >> 2) + 4 * aa + (n & 3);
+                if (key > a.pos0 - 1) key = a.pos0 - 1;     // dead positions are masked below; stay in live memory
+#pragma unroll
+                for (int j = 0; j < KS; ++j) kc[aa][j] = *(const bf16x8 *)(Kg + (size_t)key * DH + j * 32 + gq * 8);
+            }
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) vc[dt] = *(const bf16x8 *)(Vg + (size_t)(dt * 16 + n) * a.stride + kb0 + gq * 8);
+        }
         for (int r0 = 0; r0 < R; r0 += kAttnRowsPerPass) {
             const int nr = (R - r0 < kAttnRowsPerPass) ? R - r0 : kAttnRowsPerPass;
             const int nblk = (nr + 7) / 8;
-            // queries: rotate, scale, split hi/lo, store in B-operand order
-            for (int idx = tid; idx < nblk * 8 * half; idx += kAttnThreads) {
-                const int rr = idx / half, i = idx % half, r = r0 + rr;
-                float q0 = 0.f, q1 = 0.f;
-                if (rr < nr) {
+            // queries: rotate, scale, split hi/lo, store in B-operand order.  Each thread first issues the loads of
+            // all its elements (at most 8 for 32 rows of 128 dims), then does the arithmetic.
+            constexpr int QIT = (kAttnRowsPerPass * half + kAttnThreads - 1) / kAttnThreads;
+            float qx[QIT], qy[QIT], qc[QIT], qs_[QIT];
+#pragma unroll
+            for (int it = 0; it < QIT; ++it) {
+                const int idx = tid + it * kAttnThreads, rr = idx / half, i = idx % half, r = r0 + rr;
+                qx[it] = qy[it] = qc[it] = qs_[it] = 0.f;
+                if (idx < nblk * 8 * half && rr < nr) {
                     const int t = r / G, hq = g * G + r % G;
                     const float *qp = a.qkv + (size_t)t * a.ld + (size_t)hq * DH;
-                    const float c = a.rope[(t * half + i) * 2], sn = a.rope[(t * half + i) * 2 + 1];
-                    const float x = qp[i], y = qp[i + half];
-                    q0 = (x * c - y * sn) * a.scale;
-                    q1 = (x * sn + y * c) * a.scale;
+                    qx[it] = qp[i];
+                    qy[it] = qp[i + half];
+                    qc[it] = a.rope[(t * half + i) * 2];
+                    qs_[it] = a.rope[(t * half + i) * 2 + 1];
                 }
-                const int b = rr >> 3, col = rr & 7;
-                uint16_t hi, lo;
-                int d = i;
-                split_hi_lo(q0, hi, lo);
-                qb16[(((b * KS + (d >> 5)) * 64) + ((d & 31) >> 3) * 16 + col) * 8 + (d & 7)] = hi;
-                qb16[(((b * KS + (d >> 5)) * 64) + ((d & 31) >> 3) * 16 + col + 8) * 8 + (d & 7)] = lo;
-                d = i + half;
-                split_hi_lo(q1, hi, lo);
-                qb16[(((b * KS + (d >> 5)) * 64) + ((d & 31) >> 3) * 16 + col) * 8 + (d & 7)] = hi;
-                qb16[(((b * KS + (d >> 5)) * 64) + ((d & 31) >> 3) * 16 + col + 8) * 8 + (d & 7)] = lo;
+            }
+#pragma unroll
+            for (int it = 0; it < QIT; ++it) {
+                const int idx = tid + it * kAttnThreads, rr = idx / half, i = idx % half;
+                if (idx < nblk * 8 * half) {
+                    const float q0 = (qx[it] * qc[it] - qy[it] * qs_[it]) * a.scale;
+                    const float q1 = (qx[it] * qs_[it] + qy[it] * qc[it]) * a.scale;
+                    const int b = rr >> 3, col = rr & 7;
+                    uint16_t hi, lo;
+                    int d = i;
+                    split_hi_lo(q0, hi, lo);
+                    qb16[(((b * KS + (d >> 5)) * 64) + ((d & 31) >> 3) * 16 + col) * 8 + (d & 7)] = hi;
+                    qb16[(((b * KS + (d >> 5)) * 64) + ((d & 31) >> 3) * 16 + col + 8) * 8 + (d & 7)] = lo;
+                    d = i + half;
+                    split_hi_lo(q1, hi, lo);
+                    qb16[(((b * KS + (d >> 5)) * 64) + ((d & 31) >> 3) * 16 + col) * 8 + (d & 7)] = hi;
+                    qb16[(((b * KS + (d >> 5)) * 64) + ((d & 31) >> 3) * 16 + col + 8) * 8 + (d & 7)] = lo;
+                }
             }
             __syncthreads();
 
@@ -120,21 +147,16 @@ __global__ void __launch_bounds__(kAttnThreads) k_attn_mfma(AttnArgs a) {
                 if (!is_new && wave >= nbc) continue;
                 if (is_new && !(last && wave == w_new)) continue;
                 const int slot = is_new ? 4 : wave;
-                const int kb0 = c0 + wave * 32;           // first cached position of the block
                 bf16x8 kreg[2][KS], vreg[DT];
-                const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
                 if (!is_new) {
 #pragma unroll
-                    for (int aa = 0; aa < 2; ++aa) {
-                        int key = kb0 + 8 * (n >> 2) + 4 * aa + (n & 3);
-                        if (key > a.pos0 - 1) key = a.pos0 - 1;     // dead positions are masked below; stay in live memory
+                    for (int aa = 0; aa < 2; ++aa)
 #pragma unroll
-                        for (int j = 0; j < KS; ++j) kreg[aa][j] = *(const bf16x8 *)(Kg + (size_t)key * DH + j * 32 + gq * 8);
-                    }
+                        for (int j = 0; j < KS; ++j) kreg[aa][j] = kc[aa][j];
                     const bool ragged = kb0 + 32 > a.pos0;
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
-                        bf16x8 v = *(const bf16x8 *)(Vg + (size_t)(dt * 16 + n) * a.stride + kb0 + gq * 8);
+                        bf16x8 v = vc[dt];
                         if (ragged) {
 #pragma unroll
                             for (int e = 0; e < 8; ++e)
@@ -375,26 +397,53 @@ __global__ void __launch_bounds__(kValuThreads) k_attn_valu(AttnArgs a) {
 // ---------------------------------------------------------------------------------------------------
 // fold the splits of every query row, in split order, and pack the result for the Wo GEMM
 // ---------------------------------------------------------------------------------------------------
+// One wavefront per query row: the splits' (max, sum) pairs give the weights exp(max_s - M), then the lanes
+// accumulate the weighted partial outputs, two or one dimension per lane, 8 splits' rows in flight at a time.
 __global__ void __launch_bounds__(256) k_attn_combine(AttnArgs a) {
     const int DH = a.dh, PR = DH + 2;
     const int G = a.Hq / a.Hkv, R = G * a.m;
-    const int total = a.Hkv * R * DH;
-    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x) {
-        const int e = idx % DH, r = (idx / DH) % R, g = idx / (DH * R);
-        const int t = r / G, hq = g * G + r % G;
-        const float *base = a.part + ((size_t)g * a.S * R + r) * PR;
-        const size_t sstride = (size_t)R * PR;
-        float M = -INFINITY;
-        for (int s = 0; s < a.S; ++s) M = fmaxf(M, base[s * sstride + DH]);
-        float den = 0.f, num = 0.f;
-        for (int s = 0; s < a.S; ++s) {
-            const float *pr = base + s * sstride;
-            const float w = (pr[DH] == -INFINITY) ? 0.f : __expf(pr[DH] - M);
-            den += w * pr[DH + 1];
-            num += w * pr[e];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = blockIdx.x * 4 + wave;           // 0 .. Hkv * R
+    if (row >= a.Hkv * R) return;
+    const int g = row / R, r = row % R, t = r / G, hq = g * G + r % G;
+    const float *base = a.part + ((size_t)g * a.S * R + r) * PR;
+    const size_t sstride = (size_t)R * PR;
+    float M = -INFINITY;
+    for (int s = lane; s < a.S; s += 64) M = fmaxf(M, base[s * sstride + DH]);
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+    float den = 0.f, o0 = 0.f, o1 = 0.f;
+    const int e0 = lane, e1 = lane + 64;
+    for (int s0 = 0; s0 < a.S; s0 += 64) {
+        // weights of up to 64 splits, one per lane
+        const int sl = s0 + lane;
+        float w = 0.f, wl = 0.f;
+        if (sl < a.S) {
+            const float pm = base[sl * sstride + DH];
+            w = (pm == -INFINITY) ? 0.f : __expf(pm - M);
+            wl = w * base[sl * sstride + DH + 1];
         }
-        store_act((uint16_t *)a.Bo, hq * DH + e, t, num / den);
+        for (int off = 32; off > 0; off >>= 1) wl += __shfl_xor(wl, off);
+        den += wl;
+        const int ns = (a.S - s0 < 64) ? a.S - s0 : 64;
+        for (int s1 = 0; s1 < ns; s1 += 8) {
+            float v0[8], v1[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int ss = (s1 + k < ns) ? s1 + k : ns - 1;
+                const float *pr = base + (size_t)(s0 + ss) * sstride;
+                v0[k] = pr[e0];
+                v1[k] = (e1 < DH) ? pr[e1] : 0.f;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const float ws = (s1 + k < ns) ? __shfl(w, s1 + k) : 0.f;
+                o0 += ws * v0[k];
+                o1 += ws * v1[k];
+            }
+        }
     }
+    if (e0 < DH) store_act((uint16_t *)a.Bo, hq * DH + e0, t, o0 / den);
+    if (e1 < DH) store_act((uint16_t *)a.Bo, hq * DH + e1, t, o1 / den);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -449,9 +498,8 @@ int launch_attn(const AttnArgs &a, const LaunchCtx &c) {
         else return (int)hipErrorInvalidValue;
     }
     if (rc) return rc;
-    const int total = a.Hq * a.m * a.dh;
-    int grid = (total + 255) / 256;
-    hipLaunchKernelGGL(k_attn_combine, dim3(grid), dim3(256), 0, (hipStream_t)c.stream, a);
+    const int rows = a.Hq * a.m;
+    hipLaunchKernelGGL(k_attn_combine, dim3((rows + 3) / 4), dim3(256), 0, (hipStream_t)c.stream, a);
     return (int)hipGetLastError();
 }
 

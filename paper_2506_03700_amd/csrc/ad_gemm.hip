@@ -4,13 +4,14 @@
 //
 // The contraction is bound by reading W once from HBM (about m flop per byte), so the kernel is organised
 // around the weight stream: W is stored as 1 KiB MFMA A-operand tiles (see ad_internal.h), a workgroup owns
-// a contiguous block of row tiles, and each of its 16 wavefronts streams contiguous pieces with 128-bit
+// a contiguous block of row tiles, and each of its wavefronts streams contiguous pieces with 128-bit
 // loads, two batches in flight.  The MFMA (16x16x32 bf16) is only the cheapest way to multiply a tile by
 // the 2m hi/lo activation columns; it is idle most of the time.
 //
 // Two ways of feeding the activations (the B operand):
 //  * stationary (QKV, gate/up, exit-head transform, LM head: several row tiles per workgroup, K = d):
-//    wavefront w owns a fixed K slice for all the workgroup's tiles and keeps its slice of B in registers.
+//    8 wavefronts per workgroup; wavefront w owns a fixed K slice for all the workgroup's tiles and keeps its
+//    slice of B in registers.
 //    B is built in the prologue straight from the fp32 activations: x * norm_w split into bf16 hi/lo
 //    (the RMSNorm's 1/rms is a per-token scalar, applied in the epilogue), together with the slice's sum
 //    of squares; or it is loaded from a packed block an earlier epilogue wrote.
@@ -27,7 +28,9 @@
 namespace ad {
 
 constexpr int kTilesPerRound = 8;       // stationary mode: row tiles reduced together
-constexpr int kKsMax = 10;              // stationary mode: most k-steps per wavefront (K <= 16 * 10 * 32 = 5120)
+constexpr int kStatWaves = 8;           // stationary mode: wavefronts per workgroup (512 threads, up to 256 registers each)
+constexpr int kStatThreads = kStatWaves * 64;
+constexpr int kKsMax = 20;              // stationary mode: most k-steps per wavefront (K <= 8 * 20 * 32 = 5120)
 
 struct GemmLds {
     // stationary: [tile 0..8)[wave][token 0..8)[row 0..16)      streamed: [slot][col 0..16)[row 0..16)
@@ -39,7 +42,7 @@ struct GemmLds {
     int run_idx[8];
 };
 
-__device__ __forceinline__ int part_start(int tot, int w) { return (int)(((long)tot * w) / kWaves); }
+__device__ __forceinline__ int part_start(int tot, int w, int nw = kWaves) { return (int)(((long)tot * w) / nw); }
 
 // merge (max, sumexp, argmax) pairs; the lower index wins ties
 __device__ __forceinline__ void lse_merge(float &M, float &S, int &I, float m2, float s2, int i2) {
@@ -51,19 +54,19 @@ __device__ __forceinline__ void lse_merge(float &M, float &S, int &I, float m2, 
 }
 
 // ---- epilogue on a reduced round: L.red[T*128 + t*16 + i] holds row (ta+T)*16+i of token t -------------
-__device__ __forceinline__ void epilogue(const GemmArgs &g, GemmLds &L, int ta, int nt, int tid, int lane, int wave) {
+__device__ __forceinline__ void epilogue(const GemmArgs &g, GemmLds &L, int ta, int nt, int tid, int lane, int wave, int nthreads) {
     if (g.epi == EPI_STORE) {
-        for (int idx = tid; idx < nt * 128; idx += kThreads) {
+        for (int idx = tid; idx < nt * 128; idx += nthreads) {
             const int T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15, n = (ta + T) * 16 + i;
             if (t < g.m && n < g.N) g.out[(size_t)t * g.ld + n] = L.scale[t] * L.red[idx];
         }
     } else if (g.epi == EPI_RESID) {
-        for (int idx = tid; idx < nt * 128; idx += kThreads) {
+        for (int idx = tid; idx < nt * 128; idx += nthreads) {
             const int T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15, n = (ta + T) * 16 + i;
             if (t < g.m && n < g.N) g.out[(size_t)t * g.ld + n] = g.resid[(size_t)t * g.ld + n] + L.scale[t] * L.red[idx];
         }
     } else if (g.epi == EPI_SWIGLU) {
-        for (int idx = tid; idx < nt * 128; idx += kThreads) {
+        for (int idx = tid; idx < nt * 128; idx += nthreads) {
             const int T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15, f = (ta + T) * 8 + i;
             if (t < g.m && i < 8 && f * 2 < g.N) {
                 const float gate = L.scale[t] * L.red[idx], up = L.scale[t] * L.red[idx + 8];
@@ -71,13 +74,13 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, GemmLds &L, int ta, 
             }
         }
     } else if (g.epi == EPI_PACK) {
-        for (int idx = tid; idx < nt * 128; idx += kThreads) {
+        for (int idx = tid; idx < nt * 128; idx += nthreads) {
             const int T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15, n = (ta + T) * 16 + i;
             if (t < g.m && n < g.N) store_act((uint16_t *)g.Bnext, n, t, L.scale[t] * L.red[idx]);
         }
     } else {  // EPI_HEAD: running (max, sum of exp, argmax) per token over this workgroup's rows
         if (g.logits) {
-            for (int idx = tid; idx < nt * 128; idx += kThreads) {
+            for (int idx = tid; idx < nt * 128; idx += nthreads) {
                 const int T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15, n = (ta + T) * 16 + i;
                 if (t < g.m && n < g.N) g.logits[(size_t)t * g.N + n] = L.scale[t] * L.red[idx];
             }
@@ -108,98 +111,143 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, GemmLds &L, int ta, 
 }
 
 // ---- stationary mode -------------------------------------------------------------------------------------
-template <int NPL, int KSW>
-__device__ __forceinline__ void load_tile_slice(bf16x8 (&a)[KSW][NPL], const bf16x8 *p, int nks) {
-    if (nks == KSW) {   // the common case: straight-line loads
+// The wavefront's weight stream is a sequence of chunks of CH k-steps: its K slice of tile t0, of tile t0+1, ...
+// (a slice of nks k-steps is NCH = ceil(nks / CH) chunks).  Two chunk buffers alternate, so one chunk is in
+// flight while the other is multiplied.
+template <int NPL, int CH>
+__device__ __forceinline__ void load_chunk(bf16x8 (&a)[CH][NPL], const bf16x8 *p, int n) {
+    if (n == CH) {   // the common case: straight-line loads
 #pragma unroll
-        for (int j = 0; j < KSW; ++j)
+        for (int j = 0; j < CH; ++j)
 #pragma unroll
             for (int q = 0; q < NPL; ++q) a[j][q] = __builtin_nontemporal_load(p + (size_t)(j * NPL + q) * 64);
     } else {
 #pragma unroll
-        for (int j = 0; j < KSW; ++j)
-            if (j < nks) {
+        for (int j = 0; j < CH; ++j)
+            if (j < n) {
 #pragma unroll
                 for (int q = 0; q < NPL; ++q) a[j][q] = __builtin_nontemporal_load(p + (size_t)(j * NPL + q) * 64);
             }
     }
 }
 
-template <int NPL, int KSW>
-__device__ __forceinline__ void mma_tile_slice(const bf16x8 (&a)[KSW][NPL], const bf16x8 (&b)[KSW], int nks, float *slot,
-                                               int lane, int m) {
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    if (nks == KSW) {
+// one fp32 activation slice -> bf16 hi (lanes n < 8) or lo (lanes n >= 8) B operand registers
+__device__ __forceinline__ bf16x8 make_b(const f32x4 &x0, const f32x4 &x1, const float (&w)[8], bool lo_lane, float &ssq) {
+    union { bf16x8 v; uint16_t u[8]; } cv;
 #pragma unroll
-        for (int j = 0; j < KSW; ++j)
-#pragma unroll
-            for (int q = 0; q < NPL; ++q) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j][q], b[j], acc, 0, 0, 0);
-    } else {
-#pragma unroll
-        for (int j = 0; j < KSW; ++j)
-            if (j < nks) {
-#pragma unroll
-                for (int q = 0; q < NPL; ++q) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j][q], b[j], acc, 0, 0, 0);
-            }
+    for (int e = 0; e < 8; ++e) {
+        const float xv = e < 4 ? x0[e] : x1[e - 4];
+        ssq += xv * xv;
+        uint16_t hi, lo;
+        split_hi_lo(xv * w[e], hi, lo);
+        cv.u[e] = lo_lane ? lo : hi;
     }
-    // columns n and n+8 hold the hi and lo partial products of token n
-#pragma unroll
-    for (int c = 0; c < 4; ++c) acc[c] += __shfl_xor(acc[c], 8);
-    const int n = lane & 15;
-    if (n < m) *(f32x4 *)(slot + n * 16 + (lane >> 4) * 4) = acc;
+    return cv.v;
 }
 
-// KSW: most k-steps a wavefront owns (its B slice and one weight-tile slice take 4*KSW registers each).
-// DB: keep the next tile's slice in flight while the current one is multiplied (needs a second buffer).
-template <int NPL, int KSW, bool DB>
+template <int NPL, int CH>
 __device__ void gemm_stationary(const GemmArgs &g, int wg, int nwg, GemmLds &L) {
+    constexpr int NCHMAX = (kKsMax + CH - 1) / CH, KSB = NCHMAX * CH;   // B registers cover whole chunks
+    constexpr int kWaves = kStatWaves, kThreads = kStatThreads;         // this mode's workgroup shape
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, gq = lane >> 4, t_lane = n & 7;
     const int t0 = (int)(((long)g.NT * wg) / nwg), t1 = (int)(((long)g.NT * (wg + 1)) / nwg);
-    const int ks0 = part_start(g.KT, wave), nks = part_start(g.KT, wave + 1) - ks0;
+    const int ks0 = part_start(g.KT, wave, kWaves), nks = part_start(g.KT, wave + 1, kWaves) - ks0;
+    const int nch = (nks + CH - 1) / CH;                 // chunks per tile (0 if this wavefront has no K slice)
+    const int total = (t1 - t0) * nch;                   // chunks in this wavefront's stream
     if (g.epi == EPI_HEAD && tid < 8) {
         L.run_max[tid] = -INFINITY;
         L.run_sum[tid] = 0.f;
         L.run_idx[tid] = 0x7fffffff;
     }
-    // first weight tile goes in flight before anything else
-    bf16x8 a0[KSW][NPL], a1[DB ? KSW : 1][NPL], b[KSW];
-    const bf16x8 *wp = (const bf16x8 *)g.W + ((size_t)t0 * g.KT + ks0) * NPL * 64 + lane;
+    bf16x8 a0[CH][NPL], a1[CH][NPL], b[KSB];
+    const bf16x8 *wbase = (const bf16x8 *)g.W + ((size_t)t0 * g.KT + ks0) * NPL * 64 + lane;
     const size_t tstride = (size_t)g.KT * NPL * 64;
-    if (t0 < t1) load_tile_slice<NPL, KSW>(a0, wp, nks);
+    auto chunk_ptr = [&](int c) { return wbase + (size_t)(c / nch) * tstride + (size_t)(c % nch) * CH * NPL * 64; };
+    auto chunk_len = [&](int c) { const int r = nks - (c % nch) * CH; return r < CH ? r : CH; };
+    // the first two weight chunks go in flight before anything else
+    if (total > 0) load_chunk<NPL, CH>(a0, chunk_ptr(0), chunk_len(0));
+    if (total > 1) load_chunk<NPL, CH>(a1, chunk_ptr(1), chunk_len(1));
 
-    // B slice of this wavefront
+    // B slice of this wavefront.  Its K slice is read in passes of 8 k-steps = 256 inputs: lane l takes inputs
+    // 4l .. 4l+3 of every token (one coalesced 128-bit load per token and pass, all issued up front), multiplies
+    // by the norm weights, splits into bf16 hi/lo and writes them, in B-operand order, into a wavefront-private
+    // strip of LDS from which each lane then reads its operand registers.  The strip aliases the reduction slots,
+    // which are not in use yet.
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    float ssq = 0.f;
+    const bool lane_on = t_lane < g.m;
+    constexpr int NPASS = KSB / 8;
+    // 16-byte units of the strip are permuted (unit u -> u ^ ((u >> 4) & 15)) so that the 8-byte writes of a
+    // wavefront, which all go to the same operand column, spread over the LDS banks
+    uint16_t *strip16 = reinterpret_cast<uint16_t *>(L.slots) + (size_t)wave * 8 * 512;
+    const bf16x8 *strip = reinterpret_cast<const bf16x8 *>(strip16);
+    auto sw = [](int u) { return u ^ ((u >> 4) & 15); };
     if (g.x) {
+        f32x4 xr[NPASS][8], wr[NPASS];
 #pragma unroll
-        for (int j = 0; j < KSW; ++j) {
-            b[j] = zero;
-            const int k = (ks0 + j) * 32 + gq * 8;
-            if (j < nks && t_lane < g.m && k < g.K) {
-                const float *xp = g.x + (size_t)t_lane * g.ldx + k;
-                const f32x4 x0 = *(const f32x4 *)xp, x1 = *(const f32x4 *)(xp + 4);
-                float w[8];
-                load_w8(g.norm_w, g.norm_is_bf16, (size_t)k, w);
-                union { bf16x8 v; uint16_t u[8]; } cv;
+        for (int p = 0; p < NPASS; ++p) {
+            const int k = (ks0 + p * 8) * 32 + lane * 4;
+            const int kc = (k > g.K - 4) ? g.K - 4 : k;              // clamped address, masked result
+            if (p * 8 < nks) {
+                float w8[8];
+                load_w8(g.norm_w, g.norm_is_bf16, (size_t)(kc & ~7), w8);
+                const int o = kc & 4;
+                wr[p] = (f32x4){w8[o], w8[o + 1], w8[o + 2], w8[o + 3]};
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float xv = e < 4 ? x0[e] : x1[e - 4];
-                    ssq += xv * xv;
-                    uint16_t hi, lo;
-                    split_hi_lo(xv * w[e], hi, lo);
-                    cv.u[e] = (n < 8) ? hi : lo;
-                }
-                b[j] = cv.v;
+                for (int t = 0; t < 8; ++t)
+                    if (t < g.m) xr[p][t] = *(const f32x4 *)(g.x + (size_t)t * g.ldx + kc);
             }
         }
-        // sum of squares of this K slice, per token (lanes n < 8 of the four lane groups)
-        ssq += __shfl_xor(ssq, 16);
-        ssq += __shfl_xor(ssq, 32);
-        if (lane < 8) L.ssq_part[wave * 8 + lane] = ssq;
+        float ssq[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+            const int jn = (nks - p * 8 < 8) ? nks - p * 8 : 8;       // k-steps of this pass (<= 0: none)
+            if (jn > 0) {
+                const int k = (ks0 + p * 8) * 32 + lane * 4;
+                const bool k_on = (lane >> 3) < jn && k < g.K;
+                // position of inputs 4l..4l+3 in the operand: k-step l/8, lane group (l%8)/2, elements (l%2)*4..+3
+                const int u0 = (lane >> 3) * 64 + ((lane & 7) >> 1) * 16;     // unit of column 0
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    if (t < g.m) {
+                        union { uint16_t u[4]; uint64_t v; } hi, lo;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float xv = k_on ? xr[p][t][e] : 0.f;
+                            ssq[t] += xv * xv;
+                            split_hi_lo(xv * wr[p][e], hi.u[e], lo.u[e]);
+                        }
+                        *(uint64_t *)(strip16 + sw(u0 + t) * 8 + (lane & 1) * 4) = hi.v;
+                        *(uint64_t *)(strip16 + sw(u0 + 8 + t) * 8 + (lane & 1) * 4) = lo.v;
+                    }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) b[p * 8 + jj] = (lane_on && jj < jn) ? strip[sw(jj * 64 + lane)] : zero;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_wave_barrier();
+            } else {
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) b[p * 8 + jj] = zero;
+            }
+        }
+        // sum of squares of this K slice, per token, over the 64 lanes (fixed butterfly order)
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            if (t < g.m) {
+                float v = ssq[t];
+                for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+                if (lane == 0) L.ssq_part[wave * 8 + t] = v;
+            }
     } else {
 #pragma unroll
-        for (int j = 0; j < KSW; ++j) b[j] = (j < nks && t_lane < g.m) ? ((const bf16x8 *)g.B)[(size_t)(ks0 + j) * 64 + lane] : zero;
+        for (int j = 0; j < KSB; ++j) {
+            int ks = ks0 + j;
+            if (ks > g.KT - 1) ks = g.KT - 1;
+            const bf16x8 v = ((const bf16x8 *)g.B)[(size_t)ks * 64 + lane];
+            b[j] = (lane_on && j < nks) ? v : zero;
+        }
     }
     __syncthreads();
     if (tid < 8) {
@@ -227,31 +275,59 @@ __device__ void gemm_stationary(const GemmArgs &g, int wg, int nwg, GemmLds &L) 
             L.red[idx] = v;
         }
         __syncthreads();
-        epilogue(g, L, ta, nt, tid, lane, wave);
+        epilogue(g, L, ta, nt, tid, lane, wave, kThreads);
         __syncthreads();
     };
-    if constexpr (DB) {
-        for (int t = t0; t < t1; t += 2) {
-            // tile t is in a0 (already in flight); tile t+1 goes into a1, then tile t+2 into a0
-            const int T0 = (t - t0) % kTilesPerRound;
-            if (t + 1 < t1) load_tile_slice<NPL, KSW>(a1, wp + tstride, nks);
-            mma_tile_slice<NPL, KSW>(a0, b, nks, L.slots + ((size_t)T0 * kWaves + wave) * 128, lane, g.m);
-            if (t + 2 < t1) load_tile_slice<NPL, KSW>(a0, wp + 2 * tstride, nks);
-            bool round_end = (t + 1 == t1);
-            if (!round_end) {
-                mma_tile_slice<NPL, KSW>(a1, b, nks, L.slots + ((size_t)(T0 + 1) * kWaves + wave) * 128, lane, g.m);
-                round_end = (T0 + 1 == kTilesPerRound - 1) || (t + 2 >= t1);
+
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    // multiply chunk c (held in `a`) into the tile accumulator; at the end of a tile publish it to the slots
+    auto mma_chunk = [&](const bf16x8 (&a)[CH][NPL], int c) {
+        const int cc = c % nch, len = chunk_len(c);
+#pragma unroll
+        for (int q = 0; q < NCHMAX; ++q) {      // q == cc selects the B registers of this chunk statically
+            if (q == cc) {
+#pragma unroll
+                for (int j = 0; j < CH; ++j)
+                    if (j < len) {
+#pragma unroll
+                        for (int pl = 0; pl < NPL; ++pl) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j][pl], b[q * CH + j], acc, 0, 0, 0);
+                    }
             }
-            wp += 2 * tstride;
-            if (round_end) finish_round((t + 2 < t1) ? t + 2 : t1);
+        }
+        if (cc == nch - 1) {
+            // columns n and n+8 hold the hi and lo partial products of token n
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] += __shfl_xor(acc[e], 8);
+            const int T = (c / nch) % kTilesPerRound;
+            if (n < g.m) *(f32x4 *)(L.slots + ((size_t)T * kWaves + wave) * 128 + n * 16 + gq * 4) = acc;
+            acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    if (nch == 0) {
+        // no K slice (more wavefronts than k-steps): contribute zeros and keep the barriers aligned
+        for (int t = t0; t < t1; ++t) {
+            const int T = (t - t0) % kTilesPerRound;
+            if (n < g.m) *(f32x4 *)(L.slots + ((size_t)T * kWaves + wave) * 128 + n * 16 + gq * 4) = acc;
+            if (T == kTilesPerRound - 1 || t + 1 == t1) finish_round(t + 1);
         }
     } else {
-        for (int t = t0; t < t1; ++t) {
-            const int T0 = (t - t0) % kTilesPerRound;
-            mma_tile_slice<NPL, KSW>(a0, b, nks, L.slots + ((size_t)T0 * kWaves + wave) * 128, lane, g.m);
-            wp += tstride;
-            if (t + 1 < t1) load_tile_slice<NPL, KSW>(a0, wp, nks);
-            if (T0 == kTilesPerRound - 1 || t + 1 == t1) finish_round(t + 1);
+        auto tile_done = [&](int c) {
+            // a round ends when the tile that chunk c completes is the last of its round or of the workgroup
+            if (c % nch == nch - 1) {
+                const int t = t0 + c / nch;
+                if ((t - t0) % kTilesPerRound == kTilesPerRound - 1 || t + 1 == t1) finish_round(t + 1);
+            }
+        };
+        for (int c = 0; c < total; c += 2) {
+            // chunks c and c+1 are in a0 and a1 (in flight or landed); refill each buffer as soon as it is consumed
+            mma_chunk(a0, c);
+            if (c + 2 < total) load_chunk<NPL, CH>(a0, chunk_ptr(c + 2), chunk_len(c + 2));
+            tile_done(c);
+            if (c + 1 < total) {
+                mma_chunk(a1, c + 1);
+                if (c + 3 < total) load_chunk<NPL, CH>(a1, chunk_ptr(c + 3), chunk_len(c + 3));
+                tile_done(c + 1);
+            }
         }
     }
     if (g.epi == EPI_HEAD && tid < g.m) {
@@ -340,21 +416,17 @@ __device__ void gemm_streamed(const GemmArgs &g, int wg, int nwg, GemmLds &L) {
             L.red[idx] = v;
         }
         __syncthreads();
-        epilogue(g, L, ta, nt, tid, lane, wave);
+        epilogue(g, L, ta, nt, tid, lane, wave, kThreads);
         __syncthreads();
     }
 }
 
-enum { GEMM_STATIONARY_8 = 1, GEMM_STATIONARY_WIDE = 2 };   // kernel variants of the stationary mode
-
 template <int NPL, int MODE>
-__global__ void __launch_bounds__(kThreads) k_gemm(GemmArgs g) {
+__global__ void __launch_bounds__(MODE == GEMM_STATIONARY ? kStatThreads : kThreads) k_gemm(GemmArgs g) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     GemmLds &L = *reinterpret_cast<GemmLds *>(lds_raw);
-    if constexpr (MODE == GEMM_STATIONARY_8)
-        gemm_stationary<NPL, 8, true>(g, blockIdx.x, gridDim.x, L);
-    else if constexpr (MODE == GEMM_STATIONARY_WIDE)
-        gemm_stationary<NPL, (NPL == 1 ? kKsMax : 4), false>(g, blockIdx.x, gridDim.x, L);
+    if constexpr (MODE == GEMM_STATIONARY)
+        gemm_stationary<NPL, (NPL == 1 ? 8 : 2)>(g, blockIdx.x, gridDim.x, L);
     else
         gemm_streamed<NPL, (NPL == 1 ? 4 : 2)>(g, blockIdx.x, gridDim.x, L);
 }
@@ -404,26 +476,20 @@ static int launch_one(const GemmArgs &g, int grid, hipStream_t s) {
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_gemm<NPL, MODE>), dim3(grid), dim3(kThreads), sizeof(GemmLds), s, g);
+    hipLaunchKernelGGL((k_gemm<NPL, MODE>), dim3(grid), dim3(MODE == GEMM_STATIONARY ? kStatThreads : kThreads), sizeof(GemmLds), s, g);
     return (int)hipGetLastError();
 }
 
 int launch_gemm(const GemmArgs &g, int planes, const LaunchCtx &c) {
-    int grid = c.n_wg < g.NT ? c.n_wg : g.NT;
+    // equal numbers of row tiles per workgroup: with per = ceil(NT / n_wg) tiles each, ceil(NT / per) workgroups
+    const int per = (g.NT + c.n_wg - 1) / c.n_wg;
+    int grid = (g.NT + per - 1) / (per < 1 ? 1 : per);
     if (grid < 1) grid = 1;
     hipStream_t s = (hipStream_t)c.stream;
     int rc;
     if (g.mode == GEMM_STATIONARY) {
-        // k-steps per wavefront: up to 8 runs double-buffered; bf16 up to 10 and fp32 up to 4 single-buffered
-        const int ksw = (g.KT + kWaves - 1) / kWaves;
-        if (planes == 1) {
-            if (ksw <= 8) rc = launch_one<1, GEMM_STATIONARY_8>(g, grid, s);
-            else if (ksw <= kKsMax) rc = launch_one<1, GEMM_STATIONARY_WIDE>(g, grid, s);
-            else return (int)hipErrorInvalidValue;
-        } else {
-            if (ksw <= 4) rc = launch_one<3, GEMM_STATIONARY_WIDE>(g, grid, s);
-            else return (int)hipErrorInvalidValue;
-        }
+        if ((g.KT + kStatWaves - 1) / kStatWaves > kKsMax || g.K < 8) return (int)hipErrorInvalidValue;
+        rc = planes == 1 ? launch_one<1, GEMM_STATIONARY>(g, grid, s) : launch_one<3, GEMM_STATIONARY>(g, grid, s);
     } else {
         rc = planes == 1 ? launch_one<1, GEMM_STREAMED>(g, grid, s) : launch_one<3, GEMM_STREAMED>(g, grid, s);
     }
@@ -437,6 +503,6 @@ int launch_gemm(const GemmArgs &g, int planes, const LaunchCtx &c) {
     return rc;
 }
 
-int gemm_max_stationary_k(int planes) { return (planes == 1 ? kKsMax : 4) * kWaves * 32; }
+int gemm_max_stationary_k(int) { return kKsMax * kStatWaves * 32; }
 
 }  // namespace ad

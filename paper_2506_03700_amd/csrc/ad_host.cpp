@@ -68,7 +68,7 @@ bool config_ok(const ad_config *c, const char **why) {
         if (i && c->exit_layers[i] <= c->exit_layers[i - 1]) { *why = "exit layers must ascend"; return false; }
     }
     if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) { *why = "bad rope_base / rms_eps"; return false; }
-    if (c->d_model > gemm_max_stationary_k(c->dtype == AD_BF16 ? 1 : 3)) { *why = "d_model too large (bf16: up to 5120, fp32: up to 2048)"; return false; }
+    if (c->d_model > gemm_max_stationary_k(c->dtype == AD_BF16 ? 1 : 3)) { *why = "d_model above 5120 is not supported"; return false; }
     return true;
 }
 
