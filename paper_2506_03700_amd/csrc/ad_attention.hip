@@ -196,8 +196,8 @@ __global__ void __launch_bounds__(kAttnThreads) k_attn_mfma(AttnArgs a) {
                     float sc[8];
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
-                        sc[c] = s0[c] + __shfl_xor(s0[c], 8);
-                        sc[4 + c] = s1[c] + __shfl_xor(s1[c], 8);
+                        sc[c] = add_lane_xor8(s0[c]);
+                        sc[4 + c] = add_lane_xor8(s1[c]);
                     }
                     const int rr = b * 8 + (n & 7), t_row = (r0 + rr) / G;
                     float mx = -INFINITY;
@@ -223,13 +223,17 @@ __global__ void __launch_bounds__(kAttnThreads) k_attn_mfma(AttnArgs a) {
                     sum += __shfl_xor(sum, 16);
                     sum += __shfl_xor(sum, 32);
                     float *prow = L.part + ((size_t)slot * kAttnRowsPerPass + rr) * PL;
+                    f32x4 o[DT];
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
-                        f32x4 o = {0.f, 0.f, 0.f, 0.f};
-                        o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vreg[dt], pb.v, o, 0, 0, 0);
+                        o[dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                        o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vreg[dt], pb.v, o[dt], 0, 0, 0);
+                    }
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) o[c] += __shfl_xor(o[c], 8);
-                        if (n < 8 && rr < nr) *(f32x4 *)(prow + dt * 16 + gq * 4) = o;
+                    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) o[dt][c] = add_lane_xor8(o[dt][c]);
+                        if (n < 8 && rr < nr) *(f32x4 *)(prow + dt * 16 + gq * 4) = o[dt];
                     }
                     if (n < 8 && gq == 0 && rr < nr) {
                         prow[DH] = mx;
@@ -238,27 +242,45 @@ __global__ void __launch_bounds__(kAttnThreads) k_attn_mfma(AttnArgs a) {
                 }
             }
             __syncthreads();
-            // fold this item's (up to 5) block partials in block order and publish one partial per row
+            // fold this item's (up to 5) block partials in block order and publish one partial per row:
+            // first the weights exp(max_p - M) of each row's blocks, then the weighted sums, all loads up front
+            float *wts = reinterpret_cast<float *>(L.qb);       // [row][8]: weights of the 5 slots, M, sum (queries are done)
+            if (tid < nr) {
+                float mp[kAttnSlots], M = -INFINITY;
+#pragma unroll
+                for (int p = 0; p < kAttnSlots; ++p) {
+                    const bool on = p < 4 ? p < nbc : last;
+                    mp[p] = on ? L.part[((size_t)p * kAttnRowsPerPass + tid) * PL + DH] : -INFINITY;
+                    M = fmaxf(M, mp[p]);
+                }
+                float den = 0.f;
+#pragma unroll
+                for (int p = 0; p < kAttnSlots; ++p) {
+                    const float w = (mp[p] == -INFINITY) ? 0.f : __expf(mp[p] - M);
+                    wts[tid * 8 + p] = w;
+                    if (w != 0.f) den += w * L.part[((size_t)p * kAttnRowsPerPass + tid) * PL + DH + 1];
+                }
+                wts[tid * 8 + 5] = M;
+                wts[tid * 8 + 6] = den;
+            }
+            __syncthreads();
             for (int idx = tid; idx < nr * DH; idx += kAttnThreads) {
                 const int rr = idx / DH, e = idx % DH;
-                float M = -INFINITY;
+                float v[kAttnSlots], w[kAttnSlots];
+#pragma unroll
                 for (int p = 0; p < kAttnSlots; ++p) {
-                    if (p < 4 ? p >= nbc : !last) continue;
-                    M = fmaxf(M, L.part[((size_t)p * kAttnRowsPerPass + rr) * PL + DH]);
+                    w[p] = wts[rr * 8 + p];
+                    v[p] = L.part[((size_t)p * kAttnRowsPerPass + rr) * PL + e];    // slots without data have weight 0
                 }
-                float den = 0.f, num = 0.f;
-                for (int p = 0; p < kAttnSlots; ++p) {
-                    if (p < 4 ? p >= nbc : !last) continue;
-                    const float *pr = L.part + ((size_t)p * kAttnRowsPerPass + rr) * PL;
-                    const float w = (pr[DH] == -INFINITY) ? 0.f : __expf(pr[DH] - M);
-                    den += w * pr[DH + 1];
-                    num += w * pr[e];
-                }
+                float num = 0.f;
+#pragma unroll
+                for (int p = 0; p < kAttnSlots; ++p)
+                    if (w[p] != 0.f) num += w[p] * v[p];
                 float *out = a.part + (((size_t)g * a.S + s) * R + (r0 + rr)) * PR;
                 out[e] = num;
                 if (e == 0) {
-                    out[DH] = M;
-                    out[DH + 1] = den;
+                    out[DH] = wts[rr * 8 + 5];
+                    out[DH + 1] = wts[rr * 8 + 6];
                 }
             }
             __syncthreads();

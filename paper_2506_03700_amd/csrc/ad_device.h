@@ -53,6 +53,13 @@ __device__ __forceinline__ void load_w8(const void *p, int is_bf16, size_t k, fl
     }
 }
 
+// v + (v of the lane 8 places away within its group of 16 lanes): the hi and lo columns of an MFMA result.
+// A DPP row rotation by 8, so it costs one VALU instruction and no LDS traffic.
+__device__ __forceinline__ float add_lane_xor8(float v) {
+    const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128 /* row_ror:8 */, 0xf, 0xf, false);
+    return v + __int_as_float(o);
+}
+
 // index (in bf16 elements) of input k of column col in a packed activation block
 __device__ __forceinline__ size_t act_index(int k, int col) {
     return ((size_t)((k >> 5) * 4 + ((k & 31) >> 3)) * 16 + col) * 8 + (k & 7);

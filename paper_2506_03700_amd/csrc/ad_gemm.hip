@@ -297,7 +297,7 @@ __device__ void gemm_stationary(const GemmArgs &g, int wg, int nwg, GemmLds &L) 
         if (cc == nch - 1) {
             // columns n and n+8 hold the hi and lo partial products of token n
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] += __shfl_xor(acc[e], 8);
+            for (int e = 0; e < 4; ++e) acc[e] = add_lane_xor8(acc[e]);
             const int T = (c / nch) % kTilesPerRound;
             if (n < g.m) *(f32x4 *)(L.slots + ((size_t)T * kWaves + wave) * 128 + n * 16 + gq * 4) = acc;
             acc = (f32x4){0.f, 0.f, 0.f, 0.f};
