@@ -90,12 +90,24 @@ def main():
     tokens_per_s = args.steps * gen_len / dt
     log(f"[bench] {args.steps} x {gen_len} tokens in {dt:.3f}s -> {tokens_per_s:.1f} tok/s; stats {stats}")
 
+    # HBM traffic per launch: algorithmic bytes x the measured ratio (rocprofv3 FETCH_SIZE + WRITE_SIZE of the four
+    # GEMM launches of a layer step, calibrated on a copy of known size; see the file named in traffic_source)
+    traffic_ratio, traffic_src = None, os.path.join("profiles", "layer_step_8b_ctx4096_hbm_traffic.md")
+    try:
+        for line in open(os.path.join(ROOT, traffic_src)):
+            if line.startswith("traffic_ratio_gemm"):
+                traffic_ratio = float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
     avg_ms = prof["sampled_ms"] / max(1, prof["samples"])
     avg_bytes = prof["sampled_bytes"] / max(1, prof["samples"])
     achieved = avg_bytes / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
-    roofline = {"bound": "hbm", "kernel": "k_gemm<1,8> (weight-streaming skinny GEMM, all projections + vocabulary pass)",
+    roofline = {"bound": "hbm", "kernel": "ad::k_gemm (weight-streaming skinny GEMM: every projection of the layer step and the "
+                                          "vocabulary pass; instantiations k_gemm<1,1> stationary and k_gemm<1,0> streamed)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "avg_launch_us": round(avg_ms * 1e3, 2), "avg_bytes_per_launch": int(avg_bytes),
+                "traffic": None if traffic_ratio is None else int(avg_bytes * traffic_ratio),
+                "traffic_source": None if traffic_ratio is None else f"{traffic_src}: measured HBM bytes / algorithmic bytes = {traffic_ratio}",
+                "avg_launch_us": round(avg_ms * 1e3, 2), "avg_bytes_per_launch": int(avg_bytes),
                 "launches": prof["launches"], "sampled": prof["samples"]}
     decode_bytes = stats["bytes_algorithmic"]
     e2e = {"algorithmic_GB_per_step": round(decode_bytes / 1e9, 3),
@@ -155,7 +167,7 @@ def main():
     cpu = None
     if not args.skip_cpu:
         from oracle import oracle as orc
-        n_prompt, n_new = 9, 8
+        n_prompt, n_new = 17, 64          # about 10-15 s of oracle time on the 8B shape
         o = orc.Oracle(shape, w, max_pos=64)
         t0 = time.perf_counter()
         ot, ost, _ = o.generate_ada(prompt[:n_prompt], n_new, shape.gamma, cap)
