@@ -40,6 +40,15 @@ static inline double weight_at(const void *w, int32_t wdtype, size_t i) {
     return wdtype == ORC_F32 ? (double)((const float *)w)[i] : bf16_value(((const uint16_t *)w)[i]);
 }
 
+/* A value as a bf16 cache stores it: to fp32, then round-to-nearest-even to 8 significand bits. */
+static inline double round_to_bf16(double x) {
+    union { uint32_t u; float f; } c;
+    c.f = (float)x;
+    c.u += 0x7FFFu + ((c.u >> 16) & 1u);
+    c.u &= 0xFFFF0000u;
+    return (double)c.f;
+}
+
 /* sum_i w[off+i] * x[i] */
 static double dot_w(const void *w, int32_t wdtype, size_t off, const double *x, int32_t n) {
     double acc = 0.0;
@@ -219,6 +228,11 @@ int orc_layer_step(const orc_model *model, orc_kv *kv, int32_t layer, double *hi
     for (int32_t r = 0; r < m; ++r) {
         for (int32_t h = 0; h < hq; ++h) orc_rope(q + (size_t)r * dq + (size_t)h * dh, dh, pos[r], c->rope_base);
         for (int32_t h = 0; h < hkv; ++h) orc_rope(kk + (size_t)r * dkv + (size_t)h * dh, dh, pos[r], c->rope_base);
+        if (c->kv_dtype == ORC_BF16)   /* the cache's storage format: quantise what is stored */
+            for (int32_t e = 0; e < dkv; ++e) {
+                kk[(size_t)r * dkv + e] = round_to_bf16(kk[(size_t)r * dkv + e]);
+                vv[(size_t)r * dkv + e] = round_to_bf16(vv[(size_t)r * dkv + e]);
+            }
         memcpy(K + (size_t)pos[r] * dkv, kk + (size_t)r * dkv, sizeof(double) * (size_t)dkv);
         memcpy(V + (size_t)pos[r] * dkv, vv + (size_t)r * dkv, sizeof(double) * (size_t)dkv);
     }

@@ -8,7 +8,9 @@
  * product: only tests, the smoke check and the benchmark's CPU-baseline leg use it.
  *
  * Arithmetic: every value is a double; weights are read as stored (fp32, or bf16 bit patterns widened
- * exactly) and never rounded again.  Dot products may be summed in any order (the compiler is allowed
+ * exactly) and never rounded again.  The one storage format that is part of a workload's definition, a bf16
+ * KV cache, is modelled as such: entries are quantised to bf16 when they are stored (kv_dtype), and every
+ * later read sees the stored value.  Dot products may be summed in any order (the compiler is allowed
  * to vectorise them); nothing else is reordered, blocked or fused.
  *
  * Pins (tests/test_oracle_*.py): whole-sequence causal forward written with library matmul/softmax,
@@ -36,6 +38,10 @@ typedef struct {
     int32_t wdtype;                       /* ORC_F32 or ORC_BF16: storage of every weight tensor */
     int32_t n_exit;
     int32_t exit_layers[ORC_MAX_EXIT];    /* 1-based, ascending, each < n_layers */
+    int32_t kv_dtype;                     /* storage format of the KV cache: ORC_F32 keeps the computed values,
+                                             ORC_BF16 rounds every stored K (after the rotary embedding) and V entry to
+                                             bf16, round-to-nearest-even, as a bf16 cache does; attention then reads
+                                             the stored values */
 } orc_config;
 
 /* All matrices are [out_features, in_features] row-major. */

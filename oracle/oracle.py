@@ -21,7 +21,7 @@ class Config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
                 ("rope_base", C.c_double), ("rms_eps", C.c_double), ("wdtype", C.c_int32),
-                ("n_exit", C.c_int32), ("exit_layers", C.c_int32 * MAX_EXIT)]
+                ("n_exit", C.c_int32), ("exit_layers", C.c_int32 * MAX_EXIT), ("kv_dtype", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -146,6 +146,7 @@ class Oracle:
                      shape.vocab, shape.rope_base, shape.rms_eps, shape.dtype, len(shape.exit_layers))
         for i, l in enumerate(shape.exit_layers):
             cfg.exit_layers[i] = l
+        cfg.kv_dtype = shape.dtype        # a bf16 workload keeps a bf16 KV cache
         want = np.float32 if shape.dtype == 0 else np.uint16
         for k, v in weights.items():
             assert v.dtype == want and v.flags["C_CONTIGUOUS"], k

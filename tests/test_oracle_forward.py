@@ -45,6 +45,8 @@ def library_forward(shape, w, tokens, T_index=None):
         k = (a @ _t(w[p + "wk"]).T).view(T, s.n_kv_heads, s.head_dim)
         v = (a @ _t(w[p + "wv"]).T).view(T, s.n_kv_heads, s.head_dim)
         q, k = _rope_complex(q, s.rope_base), _rope_complex(k, s.rope_base)
+        if s.dtype == synth.BF16:      # a bf16 workload stores K and V in a bf16 cache (library rounding, RNE)
+            k, v = k.float().bfloat16().double(), v.float().bfloat16().double()
         Ks.append(k)
         Vs.append(v)
         rep = s.n_q_heads // s.n_kv_heads
