@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-micro", action="store_true")
     ap.add_argument("--skip-forced", action="store_true")
+    ap.add_argument("--layer-mode", default="kernels", choices=["fused", "kernels"],
+                    help="layer step as one kernel per phase (default) or as one persistent kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no sharding, no collectives); run with --gpus 1")
@@ -72,6 +74,8 @@ def main():
     g = binding.Model(shape, w, max_pos=max_pos)
     log(f"[bench] model on device in {time.time() - t0:.1f}s")
     prompt = synth.make_prompt(shape, 0, n=prompt_len)
+    fused = args.layer_mode == "fused" and shape.dtype == synth.BF16
+    g.ad_set_layer_mode(binding.AD_LAYER_FUSED if fused else binding.AD_LAYER_KERNELS)
 
     def run(**kw):
         return g.ad_generate(prompt, gen_len, shape.gamma, cap, want_events=False, **kw)
@@ -79,7 +83,7 @@ def main():
     for _ in range(args.warmup):
         run()
     torch.cuda.synchronize()
-    g.ad_profile_start(period=7, max_samples=16384)
+    g.ad_profile_start(binding.AD_PROF_LAYER if fused else binding.AD_PROF_GEMM, period=7, max_samples=16384)
     t0 = time.perf_counter()
     stats = None
     for _ in range(args.steps):
@@ -93,17 +97,20 @@ def main():
     # HBM traffic per launch: algorithmic bytes x the measured ratio (rocprofv3 FETCH_SIZE + WRITE_SIZE of the four
     # GEMM launches of a layer step, calibrated on a copy of known size; see the file named in traffic_source)
     traffic_ratio, traffic_src = None, os.path.join("profiles", "layer_step_8b_ctx4096_hbm_traffic.md")
+    ratio_key = "traffic_ratio_layer_fused" if fused else "traffic_ratio_gemm"
     try:
         for line in open(os.path.join(ROOT, traffic_src)):
-            if line.startswith("traffic_ratio_gemm"):
+            if line.startswith(ratio_key):
                 traffic_ratio = float(line.split("=")[1].split()[0])
     except OSError:
         pass
     avg_ms = prof["sampled_ms"] / max(1, prof["samples"])
     avg_bytes = prof["sampled_bytes"] / max(1, prof["samples"])
     achieved = avg_bytes / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
-    roofline = {"bound": "hbm", "kernel": "ad::k_gemm (weight-streaming skinny GEMM: every projection of the layer step and the "
-                                          "vocabulary pass; instantiations k_gemm<1,1> stationary and k_gemm<1,0> streamed)",
+    kernel = ("ad::k_layer_fused (one decoder-layer step over the call's m rows as one persistent kernel: QKV, attention, "
+              "Wo, gate/up, down; bytes = the layer's weights + KV rows read and written)") if fused else \
+             ("ad::k_gemm (weight-streaming skinny GEMM: every projection of the layer step and the vocabulary pass)")
+    roofline = {"bound": "hbm", "kernel": kernel,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": None if traffic_ratio is None else int(avg_bytes * traffic_ratio),
                 "traffic_source": None if traffic_ratio is None else f"{traffic_src}: measured HBM bytes / algorithmic bytes = {traffic_ratio}",

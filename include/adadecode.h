@@ -109,6 +109,14 @@ ad_status ad_embed(const ad_model *, const int32_t *tokens, int32_t m, void *hid
 ad_status ad_layer_step(const ad_model *, ad_kv *, int32_t layer, void *hidden, const int32_t *pos, int32_t m,
                         void *stream);
 
+/* How ad_layer_step runs.  AD_LAYER_KERNELS (the default): one kernel per phase (QKV, attention, fold, Wo,
+ * gate/up, down).  AD_LAYER_FUSED (bf16 models only): one persistent kernel with one workgroup per compute unit
+ * and grid barriers between the phases; it needs the device to itself while it runs (no other kernel of this
+ * process may occupy compute units at the same time, or a barrier wait can time out; the call after such a
+ * time-out returns AD_EDEVICE).  Both modes compute the same function; results may differ in the last bits. */
+enum { AD_LAYER_KERNELS = 0, AD_LAYER_FUSED = 1 };
+ad_status ad_set_layer_mode(ad_model *, int32_t mode);
+
 /* Eq. 1 at temperature 0 for the exit head at `layer` (which must be one of exit_layers; layer ==
  * n_layers selects the final head): token = argmax_t z_t (lowest id among equals), conf = softmax
  * probability of that token, with z = E* T norm(hidden_row).  hidden_row: dev [d] fp32.
@@ -160,15 +168,24 @@ ad_status ad_generate(const ad_model *, ad_kv *, const int32_t *prompt, int32_t 
                       int64_t *n_events, void *stream);
 
 /* ---- measurement ------------------------------------------------------------------------------------
- * Samples the library's weight-streaming kernel (the kernel that runs every projection of the layer step
- * and the vocabulary pass of Eq. 1 / Eq. 2): every `period`-th launch is bracketed by a pair of events on
- * the launch stream.  ad_profile_stop synchronises, and reports the number of launches seen, the number
- * sampled, the summed duration of the sampled launches and the weight bytes those launches had to read
- * (rows x inputs x element size of the matrix, the algorithmic figure), and the same byte count over all
- * launches.  At most max_samples launches are sampled (bounded event pool, 1..65536). */
-ad_status ad_profile_start(ad_model *, int32_t period, int32_t max_samples);
+ * Samples one of the library's two big kernels: AD_PROF_GEMM, the weight-streaming GEMM kernel (the vocabulary
+ * pass of Eq. 1 / Eq. 2, and every projection of the layer step in AD_LAYER_KERNELS mode), or AD_PROF_LAYER,
+ * the fused layer-step kernel (AD_LAYER_FUSED mode).  Every `period`-th launch of that kind is bracketed by a
+ * pair of events on the launch stream.  ad_profile_stop synchronises, and reports the number of launches
+ * seen, the number sampled, the summed duration of the sampled launches and the bytes those launches had to
+ * move (GEMM: rows x inputs x element size of the matrix; layer step: its weights, the KV rows read and the KV
+ * rows written -- the algorithmic figures), and the same byte count over all launches.  At most max_samples
+ * launches are sampled (bounded event pool, 1..65536). */
+enum { AD_PROF_GEMM = 0, AD_PROF_LAYER = 1 };
+ad_status ad_profile_start(ad_model *, int32_t kind, int32_t period, int32_t max_samples);
 ad_status ad_profile_stop(ad_model *, int64_t *n_launches, int64_t *n_samples, double *sampled_ms, int64_t *sampled_bytes,
                           int64_t *total_bytes);
+
+/* Phase trace of the fused layer-step kernel: while `ticks` (dev, [n_workgroups][n_stamps] int64) is set, every
+ * fused launch overwrites it with each workgroup's wall-clock ticks (100 MHz) at the kernel's start, before and
+ * after each of its five grid barriers, and at its end.  ticks == NULL stops it.  The two counts are returned
+ * through the pointers (either may be NULL); bytes is the size of the buffer. */
+ad_status ad_layer_trace(ad_model *, void *ticks, size_t bytes, int32_t *n_workgroups, int32_t *n_stamps);
 
 const char *ad_last_error(void);   /* thread-local, never NULL */
 const char *ad_version(void);

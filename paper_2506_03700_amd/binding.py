@@ -20,10 +20,12 @@ AD_OK, AD_EINVAL, AD_ERANGE, AD_ESTATE, AD_EDEVICE, AD_ENOMEM = range(6)
 AD_F32, AD_BF16 = 0, 1
 AD_MAX_EXIT, AD_M_MAX = 8, 8
 EV_LAYER_STEP, EV_HEAD, EV_VERIFY, EV_VERIFY_ROW = 1, 2, 3, 4
+AD_LAYER_KERNELS, AD_LAYER_FUSED = 0, 1
+AD_PROF_GEMM, AD_PROF_LAYER = 0, 1
 
 EXPORTS = ["ad_workspace_bytes", "ad_model_create", "ad_model_destroy", "ad_kv_bytes", "ad_kv_create", "ad_kv_destroy",
-           "ad_kv_len", "ad_kv_set_len", "ad_kv_truncate", "ad_embed", "ad_layer_step", "ad_exit_head", "ad_verify",
-           "ad_head_logits", "ad_generate", "ad_profile_start", "ad_profile_stop", "ad_last_error", "ad_version"]
+           "ad_kv_len", "ad_kv_set_len", "ad_kv_truncate", "ad_embed", "ad_layer_step", "ad_set_layer_mode", "ad_exit_head", "ad_verify",
+           "ad_head_logits", "ad_generate", "ad_layer_trace", "ad_profile_start", "ad_profile_stop", "ad_last_error", "ad_version"]
 
 
 class Config(C.Structure):
@@ -96,7 +98,9 @@ def lib() -> C.CDLL:
         L.ad_verify.argtypes = [P, P, P, i32, P, P, P, P]
         L.ad_head_logits.argtypes = [P, i32, P, i32, P, P]
         L.ad_generate.argtypes = [P, P, P, i32, C.POINTER(GenParams), P, P, C.POINTER(Stats), P, C.c_int64, P, P]
-        L.ad_profile_start.argtypes = [P, i32, i32]
+        L.ad_profile_start.argtypes = [P, i32, i32, i32]
+        L.ad_set_layer_mode.argtypes = [P, i32]
+        L.ad_layer_trace.argtypes = [P, P, C.c_size_t, P, P]
         L.ad_profile_stop.argtypes = [P, P, P, P, P, P]
         L.ad_last_error.restype = C.c_char_p
         L.ad_version.restype = C.c_char_p
@@ -128,7 +132,8 @@ def _stream_ptr(torch):
 class Model:
     """ad_model + ad_kv over torch device buffers.  Method names follow the C entry points."""
 
-    def __init__(self, shape, weights: Dict[str, np.ndarray], max_pos: int, m_max: int = AD_M_MAX, device: str = "cuda:0"):
+    def __init__(self, shape, weights: Dict[str, np.ndarray], max_pos: int, m_max: int = AD_M_MAX, device: str = "cuda:0",
+                 layer_mode: Optional[int] = None):
         import torch
         self.torch = torch
         self.shape = shape
@@ -175,6 +180,8 @@ class Model:
         self.kv_storage = torch.zeros(kv_bytes, dtype=torch.uint8, device=self.device)
         _check(self.L.ad_kv_create(self.model, C.c_void_p(self.kv_storage.data_ptr()), kv_bytes, max_pos, _stream_ptr(torch), C.byref(self.kv)))
         self._pinned = torch.zeros(64, dtype=torch.int32).pin_memory()
+        if layer_mode is not None:
+            self.ad_set_layer_mode(layer_mode)
 
     def close(self) -> None:
         if getattr(self, "kv", None):
@@ -304,8 +311,24 @@ class Model:
         return out[:n.value].copy(), st.as_dict(), ev[:min(nev.value, len(ev))].copy() if want_events else None
 
 
-    def ad_profile_start(self, period: int = 1, max_samples: int = 65536) -> None:
-        _check(self.L.ad_profile_start(self.model, period, max_samples))
+    def ad_set_layer_mode(self, mode: int) -> None:
+        _check(self.L.ad_set_layer_mode(self.model, mode))
+
+    def ad_layer_trace(self, on: bool = True):
+        """Returns the device tensor [workgroups, stamps] (int64 ticks of the 100 MHz wall clock) that every fused
+        layer-step launch overwrites from now on, or None after switching the trace off."""
+        torch = self.torch
+        nwg, ns = C.c_int32(), C.c_int32()
+        _check(self.L.ad_layer_trace(self.model, None, 0, C.byref(nwg), C.byref(ns)))
+        if not on:
+            self._trace = None
+            return None
+        self._trace = torch.zeros((nwg.value, ns.value), dtype=torch.int64, device="cuda:0")
+        _check(self.L.ad_layer_trace(self.model, self._trace.data_ptr(), self._trace.numel() * 8, None, None))
+        return self._trace
+
+    def ad_profile_start(self, kind: int = AD_PROF_GEMM, period: int = 1, max_samples: int = 65536) -> None:
+        _check(self.L.ad_profile_start(self.model, kind, period, max_samples))
 
     def ad_profile_stop(self) -> dict:
         nl, ns, sb, tb, ms = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64(), C.c_double()

@@ -8,6 +8,7 @@ namespace ad {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 // ---------------------------------------------------------------------------------------------------
@@ -60,16 +61,16 @@ __device__ __forceinline__ float add_lane_xor8(float v) {
     return v + __int_as_float(o);
 }
 
-// index (in bf16 elements) of input k of column col in a packed activation block
-__device__ __forceinline__ size_t act_index(int k, int col) {
-    return ((size_t)((k >> 5) * 4 + ((k & 31) >> 3)) * 16 + col) * 8 + (k & 7);
+// index (in bf16 elements) of input k of column col (token col & 7, hi/lo part col >> 3) in a packed activation
+// block of KT k-steps (see ad_internal.h)
+__device__ __forceinline__ size_t act_index(int k, int col, int KT) {
+    return ((((size_t)(col & 7) * KT + (k >> 5)) * 2 + (col >> 3)) * 4 + ((k & 31) >> 3)) * 8 + (k & 7);
 }
 
-__device__ __forceinline__ void store_act(uint16_t *B, int k, int t, float v) {
-    uint16_t hi, lo;
-    split_hi_lo(v, hi, lo);
-    B[act_index(k, t)] = hi;
-    B[act_index(k, 8 + t)] = lo;
+// index (in 16-byte units) of the MFMA B operand register of lane `lane` for k-step ks of such a block
+__device__ __forceinline__ size_t act_operand_index(int ks, int lane, int KT) {
+    const int n = lane & 15;
+    return (((size_t)(n & 7) * KT + ks) * 2 + (n >> 3)) * 4 + (lane >> 4);
 }
 
 }  // namespace ad

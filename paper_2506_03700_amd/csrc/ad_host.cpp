@@ -104,6 +104,7 @@ void make_layout(const ad_config &c, Layout &L) {
     s += align_up((size_t)8 * L.nqkv * 4);                     // qkv
     s += 2 * align_up((size_t)8 * L.d * 4);                    // x1, rows
     s += align_up((size_t)4096 * 8 * 4 * 4);                   // head partials (up to 4096 workgroups)
+    s += align_up((size_t)kBarrierWords * 4);                  // grid-barrier counters of the fused layer step
     L.scratch_bytes = s;
     L.total = off + s;
 }
@@ -112,6 +113,7 @@ void make_layout(const ad_config &c, Layout &L) {
 
 struct Profile {
     bool on = false;
+    int32_t kind = AD_PROF_GEMM;
     int32_t period = 1, max_samples = 0;
     int64_t launches = 0, total_bytes = 0;
     std::vector<void *> start, stop;
@@ -132,6 +134,12 @@ struct ad_model {
     // pinned host results for ad_generate
     int32_t *pin;         // [0..8) tok, [8] n_accept, [9] next, [16..24) row argmax
     float *pin_conf;      // [8]
+    // fused layer step: mode, barrier counters (device), barriers completed so far, abort word (pinned host)
+    int32_t layer_mode;
+    unsigned *bar_ctr;
+    mutable unsigned bar_round;
+    unsigned *bar_abort;
+    long long *layer_trace;   // device buffer for the fused kernel's phase timestamps, or null
 };
 
 struct ad_kv {
@@ -232,9 +240,15 @@ ad_status ad_model_create(const ad_config *cfg, const ad_layer_weights *layers, 
     m->x1 = (float *)take((size_t)8 * L.d * 4);
     m->rows = (float *)take((size_t)8 * L.d * 4);
     m->head_part = (float *)take((size_t)4096 * 8 * 4 * 4);
+    m->bar_ctr = (unsigned *)take((size_t)kBarrierWords * 4);     // zeroed with the rest of the scratch above
+    m->bar_round = 0;
     m->pin = (int32_t *)pinned_alloc(4096);
     if (!m->pin) { delete m; return (ad_status)fail(AD_ENOMEM, "ad_model_create: pinned allocation failed"); }
     m->pin_conf = (float *)(m->pin + 32);
+    m->bar_abort = (unsigned *)(m->pin + 64);
+    *m->bar_abort = 0;
+    m->layer_mode = AD_LAYER_KERNELS;
+    m->layer_trace = nullptr;
     AD_TRY(stream_sync(stream), "model creation");
 #undef AD_TRY
     *out = m;
@@ -328,21 +342,26 @@ ad_status ad_kv_truncate(ad_kv *kv, int32_t new_len) {
 
 // ---- steps -----------------------------------------------------------------------------------------
 
+// Counts a launch of the profiled kind; returns true if it is to be sampled (the start event is then recorded and
+// the caller records p.stop.back() after the launch).
+static bool profile_begin(Profile &p, int32_t kind, int64_t bytes, void *stream) {
+    if (!p.on || p.kind != kind) return false;
+    const bool sample = (p.launches % p.period == 0) && (int32_t)p.bytes.size() < p.max_samples;
+    ++p.launches;
+    p.total_bytes += bytes;
+    if (!sample) return false;
+    void *a = event_create(), *b = event_create();
+    if (!a || !b) { event_destroy(a); event_destroy(b); return false; }
+    p.start.push_back(a); p.stop.push_back(b); p.bytes.push_back(bytes);
+    (void)event_record(a, stream);
+    return true;
+}
+
 // Launches the weight-streaming kernel; when profiling is on, every period-th launch is timed with events.
 static int gemm(const ad_model *m, const GemmArgs &g, int64_t rows, int64_t cols, const LaunchCtx &ctx) {
     Profile &p = m->prof;
     const int64_t bytes = rows * cols * (int64_t)m->lay.elem;
-    bool sample = false;
-    if (p.on) {
-        sample = (p.launches % p.period == 0) && (int32_t)p.bytes.size() < p.max_samples;
-        ++p.launches;
-        p.total_bytes += bytes;
-    }
-    if (sample) {
-        void *a = event_create(), *b = event_create();
-        if (!a || !b) { event_destroy(a); event_destroy(b); sample = false; }
-        else { p.start.push_back(a); p.stop.push_back(b); p.bytes.push_back(bytes); (void)event_record(a, ctx.stream); }
-    }
+    const bool sample = profile_begin(p, AD_PROF_GEMM, bytes, ctx.stream);
     const int rc = launch_gemm(g, m->lay.planes, ctx);
     if (sample) (void)event_record(p.stop.back(), ctx.stream);
     return rc;
@@ -359,6 +378,19 @@ ad_status ad_embed(const ad_model *m, const int32_t *tokens, int32_t n, void *hi
     }
     int rc = launch_embed(a, stream);
     return rc ? (ad_status)hip_fail(rc, "ad_embed") : AD_OK;
+}
+
+// The fused layer step's grid barrier gave up in an earlier launch (it never should: the grid is co-resident):
+// report it once, and put the counters back in order for later calls.
+static int fused_health(const ad_model *m, void *stream) {
+    if (*(volatile unsigned *)m->bar_abort == 0) return AD_OK;
+    int rc = stream_sync(stream);
+    if (!rc) rc = launch_zero(m->bar_ctr, (size_t)kBarrierWords * 4, stream);
+    if (!rc) rc = stream_sync(stream);
+    *(volatile unsigned *)m->bar_abort = 0;
+    m->bar_round = 0;
+    if (rc) return hip_fail(rc, "fused layer step: resetting the grid barrier");
+    return fail(AD_EDEVICE, "fused layer step: a grid barrier timed out in an earlier call; its result and the KV cache rows it appended are invalid");
 }
 
 static int64_t layer_step_bytes(const ad_config &c, int32_t ctx, int32_t m) {
@@ -386,12 +418,11 @@ ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidde
     const int bf = c.dtype == AD_BF16;
     int rc;
     // 1. q, k, v = W (RMSNorm(x)): the norm is fused into the GEMM (B operand built from x in its prologue)
-    GemmArgs g;
-    memset(&g, 0, sizeof g);
-    g.W = lp.wqkv; g.NT = L.nqkv / 16; g.KT = L.kt_d; g.N = L.nqkv; g.K = L.d; g.m = n; g.mode = GEMM_STATIONARY;
-    g.x = (const float *)hidden; g.ldx = L.d; g.norm_w = lp.attn_norm; g.norm_is_bf16 = bf; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
-    g.epi = EPI_STORE; g.out = m->qkv; g.ld = L.nqkv;
-    if ((rc = gemm(m, g, L.nqkv, L.d, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: qkv");
+    GemmArgs gq;
+    memset(&gq, 0, sizeof gq);
+    gq.W = lp.wqkv; gq.NT = L.nqkv / 16; gq.KT = L.kt_d; gq.N = L.nqkv; gq.K = L.d; gq.m = n; gq.mode = GEMM_STATIONARY;
+    gq.x = (const float *)hidden; gq.ldx = L.d; gq.norm_w = lp.attn_norm; gq.norm_is_bf16 = bf; gq.inv_dim = 1.0f / (float)L.d; gq.eps = c.rms_eps;
+    gq.epi = EPI_STORE; gq.out = m->qkv; gq.ld = L.nqkv;
     // 2. rotary embedding, KV append, attention (partials + combine)
     AttnArgs a;
     memset(&a, 0, sizeof a);
@@ -400,24 +431,46 @@ ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidde
     a.stride = kv->stride; a.pos0 = pos[0]; a.m = n; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = L.dh;
     a.C = attn_chunk(bf, L.dh);
     a.S = pos[0] > 0 ? (pos[0] + a.C - 1) / a.C : 1;
-    a.part = kv->part; a.Bo = m->Bo; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_is_bf16 = bf;
-    if ((rc = launch_attn(a, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: attention");
+    a.part = kv->part; a.Bo = m->Bo; a.Bo_KT = L.kt_q; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_is_bf16 = bf;
     // 3. x' = x + Wo o
-    memset(&g, 0, sizeof g);
-    g.W = lp.wo; g.B = m->Bo; g.NT = L.d / 16; g.KT = L.kt_q; g.N = L.d; g.K = L.dq; g.m = n; g.mode = GEMM_STREAMED;
-    g.epi = EPI_RESID; g.resid = (const float *)hidden; g.out = m->x1; g.ld = L.d;
-    if ((rc = gemm(m, g, L.d, L.dq, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: wo");
+    GemmArgs go;
+    memset(&go, 0, sizeof go);
+    go.W = lp.wo; go.B = m->Bo; go.NT = L.d / 16; go.KT = L.kt_q; go.N = L.d; go.K = L.dq; go.m = n; go.mode = GEMM_STREAMED;
+    go.epi = EPI_RESID; go.resid = (const float *)hidden; go.out = m->x1; go.ld = L.d;
     // 4. g = silu(Wg b) * (Wu b), b = RMSNorm(x') fused as in step 1
-    memset(&g, 0, sizeof g);
-    g.W = lp.wgu; g.NT = (2 * L.f) / 16; g.KT = L.kt_d; g.N = 2 * L.f; g.K = L.d; g.m = n; g.mode = GEMM_STATIONARY;
-    g.x = m->x1; g.ldx = L.d; g.norm_w = lp.ffn_norm; g.norm_is_bf16 = bf; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
-    g.epi = EPI_SWIGLU; g.Bnext = m->Bg;
-    if ((rc = gemm(m, g, 2 * (int64_t)L.f, L.d, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: gate/up");
+    GemmArgs gg;
+    memset(&gg, 0, sizeof gg);
+    gg.W = lp.wgu; gg.NT = (2 * L.f) / 16; gg.KT = L.kt_d; gg.N = 2 * L.f; gg.K = L.d; gg.m = n; gg.mode = GEMM_STATIONARY;
+    gg.x = m->x1; gg.ldx = L.d; gg.norm_w = lp.ffn_norm; gg.norm_is_bf16 = bf; gg.inv_dim = 1.0f / (float)L.d; gg.eps = c.rms_eps;
+    gg.epi = EPI_SWIGLU; gg.Bnext = m->Bg; gg.Bnext_KT = L.kt_f;
     // 5. y = x' + Wd g
-    memset(&g, 0, sizeof g);
-    g.W = lp.wd; g.B = m->Bg; g.NT = L.d / 16; g.KT = L.kt_f; g.N = L.d; g.K = L.f; g.m = n; g.mode = GEMM_STREAMED;
-    g.epi = EPI_RESID; g.resid = m->x1; g.out = (float *)hidden; g.ld = L.d;
-    if ((rc = gemm(m, g, L.d, L.f, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: down");
+    GemmArgs gd;
+    memset(&gd, 0, sizeof gd);
+    gd.W = lp.wd; gd.B = m->Bg; gd.NT = L.d / 16; gd.KT = L.kt_f; gd.N = L.d; gd.K = L.f; gd.m = n; gd.mode = GEMM_STREAMED;
+    gd.epi = EPI_RESID; gd.resid = m->x1; gd.out = (float *)hidden; gd.ld = L.d;
+
+    if (m->layer_mode == AD_LAYER_FUSED) {
+        // all five steps in one persistent kernel
+        if ((rc = fused_health(m, stream))) return (ad_status)rc;
+        FusedArgs f;
+        f.qkv = gq; f.wo = go; f.gu = gg; f.down = gd; f.attn = a;
+        f.nwg_qkv = fused_phase_workgroups(gq.NT, m->n_wg);
+        f.nwg_wo = fused_phase_workgroups(go.NT, m->n_wg);
+        f.nwg_gu = fused_phase_workgroups(gg.NT, m->n_wg);
+        f.nwg_down = fused_phase_workgroups(gd.NT, m->n_wg);
+        f.ctr = m->bar_ctr; f.round0 = m->bar_round; f.abort_flag = m->bar_abort; f.trace = m->layer_trace;
+        const bool sample = profile_begin(m->prof, AD_PROF_LAYER, layer_step_bytes(c, pos[0], n), stream);
+        rc = launch_layer_fused(f, ctx);
+        if (sample) (void)event_record(m->prof.stop.back(), stream);
+        if (rc) return (ad_status)hip_fail(rc, "ad_layer_step: fused kernel");
+        m->bar_round += kFusedBarriers;
+    } else {
+        if ((rc = gemm(m, gq, L.nqkv, L.d, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: qkv");
+        if ((rc = launch_attn(a, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: attention");
+        if ((rc = gemm(m, go, L.d, L.dq, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: wo");
+        if ((rc = gemm(m, gg, 2 * (int64_t)L.f, L.d, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: gate/up");
+        if ((rc = gemm(m, gd, L.d, L.f, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: down");
+    }
     kv->len[layer - 1] += n;
     return AD_OK;
 }
@@ -443,7 +496,7 @@ static int run_head(const ad_model *m, int32_t layer, const void *hidden, int32_
         memset(&t, 0, sizeof t);
         t.W = m->T[slot]; t.NT = L.d / 16; t.KT = L.kt_d; t.N = L.d; t.K = L.d; t.m = n; t.mode = GEMM_STATIONARY;
         t.x = (const float *)hidden; t.ldx = L.d; t.norm_w = m->final_norm; t.norm_is_bf16 = bf; t.inv_dim = 1.0f / (float)L.d; t.eps = c.rms_eps;
-        t.epi = EPI_PACK; t.Bnext = m->B1;
+        t.epi = EPI_PACK; t.Bnext = m->B1; t.Bnext_KT = L.kt_d;
         if ((rc = gemm(m, t, L.d, L.d, ctx))) return hip_fail(rc, who);
         g.B = m->B1;
     } else {
@@ -492,10 +545,29 @@ static void profile_clear(Profile &p) {
     p.launches = 0; p.total_bytes = 0; p.on = false;
 }
 
-ad_status ad_profile_start(ad_model *m, int32_t period, int32_t max_samples) {
+ad_status ad_set_layer_mode(ad_model *m, int32_t mode) {
+    if (!m) return (ad_status)fail(AD_EINVAL, "ad_set_layer_mode: null model");
+    if (mode != AD_LAYER_KERNELS && mode != AD_LAYER_FUSED) return (ad_status)fail(AD_EINVAL, "ad_set_layer_mode: unknown mode %d", mode);
+    if (mode == AD_LAYER_FUSED && m->cfg.dtype != AD_BF16) return (ad_status)fail(AD_ESTATE, "ad_set_layer_mode: the fused layer step needs a bf16 model");
+    m->layer_mode = mode;
+    return AD_OK;
+}
+
+ad_status ad_layer_trace(ad_model *m, void *ticks, size_t bytes, int32_t *n_workgroups, int32_t *n_stamps) {
+    if (!m) return (ad_status)fail(AD_EINVAL, "ad_layer_trace: null model");
+    if (n_workgroups) *n_workgroups = m->n_wg;
+    if (n_stamps) *n_stamps = kFusedTraceStamps;
+    if (ticks && bytes < (size_t)m->n_wg * kFusedTraceStamps * 8) return (ad_status)fail(AD_ENOMEM, "ad_layer_trace: buffer too small");
+    m->layer_trace = (long long *)ticks;
+    return AD_OK;
+}
+
+ad_status ad_profile_start(ad_model *m, int32_t kind, int32_t period, int32_t max_samples) {
     if (!m) return (ad_status)fail(AD_EINVAL, "ad_profile_start: null model");
+    if (kind != AD_PROF_GEMM && kind != AD_PROF_LAYER) return (ad_status)fail(AD_EINVAL, "ad_profile_start: unknown kind %d", kind);
     if (period < 1 || max_samples < 1 || max_samples > 65536) return (ad_status)fail(AD_ERANGE, "ad_profile_start: period >= 1 and 1 <= max_samples <= 65536");
     profile_clear(m->prof);
+    m->prof.kind = kind;
     m->prof.period = period;
     m->prof.max_samples = max_samples;
     m->prof.on = true;
@@ -558,6 +630,7 @@ struct GpuBackend : Backend {
         int rc = ad_exit_head(m, layer, row(r), m->pin, m->pin_conf, stream);
         if (rc != AD_OK) return rc;
         if ((rc = stream_sync(stream))) return hip_fail(rc, "ad_generate: exit head");
+        if ((rc = fused_health(m, stream))) return rc;
         *token = m->pin[0];
         *conf = m->pin_conf[0];
         const int64_t s = m->cfg.dtype == AD_BF16 ? 2 : 4;
@@ -568,6 +641,7 @@ struct GpuBackend : Backend {
         int rc = ad_verify(m, row(0), draft, n, m->pin + 8, m->pin + 9, m->pin + 16, stream);
         if (rc != AD_OK) return rc;
         if ((rc = stream_sync(stream))) return hip_fail(rc, "ad_generate: verify");
+        if ((rc = fused_health(m, stream))) return rc;
         *n_accept = m->pin[8];
         *next = m->pin[9];
         for (int i = 0; i < n; ++i) row_argmax[i] = m->pin[16 + i];
@@ -600,6 +674,7 @@ ad_status ad_generate(const ad_model *m, ad_kv *kv, const int32_t *prompt, int32
     int rc = run_algorithm1(be, sc, *gp, prompt, n_prompt, out_tokens, n_out, stats, events, max_events, n_events);
     if (stats) stats->bytes_algorithmic = be.bytes;
     if (rc == AD_OK && (rc = stream_sync(stream))) return (ad_status)hip_fail(rc, "ad_generate");
+    if (rc == AD_OK) rc = fused_health(m, stream);
     return (ad_status)rc;
 }
 

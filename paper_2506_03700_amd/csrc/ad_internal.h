@@ -14,10 +14,12 @@ namespace ad {
 // bf16 weights have one plane; fp32 weights are split exactly into three bf16 planes (W = p0 + p1 + p2).
 // Rows >= N and inputs >= K are zero.
 //
-// Activation block [m <= 8 tokens, K] -> per k-step 64 lanes x 8 bf16 (1 KiB): lane l holds column
-// (l & 15) and inputs ks*32 + (l >> 4)*8 .. +8; columns 0..7 are the tokens' bf16 "hi" parts and columns
-// 8..15 their "lo" parts (x = hi + lo to 16 mantissa bits), so one MFMA yields both partial products and
-// the activations keep near-fp32 precision.  This is the MFMA's B operand.
+// Activation block [m <= 8 tokens, K]: the MFMA's B operand has 16 columns; columns 0..7 are the tokens' bf16
+// "hi" parts and columns 8..15 their "lo" parts (x = hi + lo to 16 mantissa bits), so one MFMA yields both
+// partial products and the activations keep near-fp32 precision.  Lane l of the operand of k-step ks holds
+// column (l & 15) and inputs ks*32 + (l >> 4)*8 .. +8.  In memory the block is ordered
+// [token][k-step][hi, lo][lane group l >> 4][8 inputs]: the 128 bytes a token contributes to a k-step are one
+// cache line, and a call with m tokens touches m lines per k-step (KT * 1 KiB for a full block).
 constexpr int kTileRows = 16;
 constexpr int kTileK = 32;
 constexpr int kThreads = 1024;   // one workgroup per CU, 16 wavefronts
@@ -57,6 +59,7 @@ struct GemmArgs {
     const float *resid;
     int ld;
     void *Bnext;          // packed activations written by the epilogue
+    int Bnext_KT;         // k-steps of that block (the K of the GEMM that will read it, in units of 32)
     // head
     float *head_part;     // [nwg][8][4] (max, sumexp, argmax as int bits, unused)
     int n_parts;          // workgroups that wrote head_part (set by the launcher)
@@ -84,9 +87,25 @@ struct AttnArgs {
     int C, S;             // chunk (positions per work item), splits
     float *part;          // [Hkv][S][R][dh+2]
     void *Bo;             // packed attention output for the Wo GEMM
+    int Bo_KT;            // k-steps of that block (n_q_heads * head_dim / 32)
     float scale;
     int kv_is_bf16;
 };
+
+// One decoder-layer step as a single persistent kernel (bf16 models): the four GEMMs and the attention phase
+// with their usual arguments, the number of workgroups that own row tiles in each GEMM, and the grid barrier.
+struct FusedArgs {
+    GemmArgs qkv, wo, gu, down;
+    AttnArgs attn;
+    int nwg_qkv, nwg_wo, nwg_gu, nwg_down;
+    unsigned *ctr;          // barrier counters: kBarrierWords zero-initialised words, owned by the model
+    unsigned round0;        // barriers completed by earlier launches on these counters
+    unsigned *abort_flag;   // pinned host word, set when a barrier wait timed out
+    long long *trace;       // null, or [workgroups][kFusedTraceStamps] wall-clock ticks (100 MHz) at the phase boundaries
+};
+constexpr int kFusedTraceStamps = 12;      // start, before and after each of the 5 barriers, end
+constexpr int kBarrierWords = 32 * 9;      // one 128-byte line for the global counter and for each of 8 groups
+constexpr int kFusedBarriers = 5;          // barriers per launch
 
 struct EmbedArgs {
     const void *table; int is_bf16; int d; int m; int32_t tok[8]; float *out;
@@ -105,6 +124,8 @@ int launch_rope_table(const RopeArgs &, void *stream);
 int gemm_max_stationary_k(int planes);   // largest d_model the stationary GEMM variants cover
 int launch_gemm(const GemmArgs &, int planes, const LaunchCtx &);   // EPI_HEAD: also launches the vocabulary combine
 int launch_attn(const AttnArgs &, const LaunchCtx &);
+int launch_layer_fused(const FusedArgs &, const LaunchCtx &);   // n_wg must not exceed the number of compute units
+int fused_phase_workgroups(int n_tiles, int n_wg);               // workgroups that own row tiles of a GEMM phase
 int attn_chunk(int kv_is_bf16, int dh);   // cached positions per attention work item
 int device_info(int *n_cu);
 const char *hip_error_text(int code);

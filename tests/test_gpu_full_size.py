@@ -57,15 +57,16 @@ def _assert_same_or_near_tie(g, prompt, t_ada, t_ref):
     return i
 
 
-@pytest.mark.parametrize("name,n_prompt,n_new", [("8b", 48, 20), ("13b", 32, 12)])
-def test_full_model_against_oracle_and_greedy_property(name, n_prompt, n_new):
+@pytest.mark.parametrize("name,n_prompt,n_new,mode", [("8b", 48, 20, 0), ("8b", 48, 20, 1), ("13b", 32, 12, 0)],
+                         ids=["8b-kernels", "8b-fused", "13b-kernels"])
+def test_full_model_against_oracle_and_greedy_property(name, n_prompt, n_new, mode):
     import torch
     from paper_2506_03700_amd import binding as ad
     shape = synth.SHAPES[name]
     print(f"case {name}: generating weights", flush=True)
     w = synth.make_weights(shape, seed=0)
     max_pos = shape.prompt_len + shape.gen_len + 8
-    g = ad.Model(shape, w, max_pos=max_pos)
+    g = ad.Model(shape, w, max_pos=max_pos, layer_mode=mode)    # 0: one kernel per phase, 1: fused persistent kernel
     prompt = synth.make_prompt(shape, 0)
 
     # (a) against the oracle, shorter run, natural threshold and a forced schedule with scripted wrong drafts
@@ -126,7 +127,7 @@ def test_long_context_forced_schedule_property():
     shape = synth.LLAMA8B_LONG.with_(n_layers=8, exit_layers=(2, 4, 6), vocab=16384)
     w = synth.make_weights(shape, seed=0)
     n_prompt, n_new = 1024, 1536
-    g = ad.Model(shape, w, max_pos=n_prompt + n_new + 8)
+    g = ad.Model(shape, w, max_pos=n_prompt + n_new + 8, layer_mode=ad.AD_LAYER_FUSED)
     prompt = synth.make_prompt(shape, 0, n=n_prompt)
     sched = synth.make_forced_schedule(shape, 0, n_prompt + n_new + 8)
     print("case 8b-long (8 layers): forced schedule vs greedy", flush=True)

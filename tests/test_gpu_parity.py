@@ -37,21 +37,28 @@ def gpu_kv(model, layer, n):
     return model.kv_read(layer, n)
 
 
+def with_modes(shapes):
+    """(shape, layer mode) cases: bf16 models run the layer step both as one kernel per phase (0) and as the
+    fused persistent kernel (1); fp32 models have the per-phase kernels only."""
+    return [pytest.param(s, m, id=f"{s.name}-{'fused' if m else 'kernels'}")
+            for s in shapes for m in ((0, 1) if s.dtype == synth.BF16 else (0,))]
+
+
 UNTIED = synth.TINY.with_(name="tiny-untied", tied_head=False, vocab=512, exit_layers=(1, 2, 3))
 ODD = synth.TINY.with_(name="tiny-odd", n_q_heads=6, n_kv_heads=2, head_dim=64, d_model=208, d_ffn=200, vocab=301,
                        n_layers=3, exit_layers=(1,), rope_base=500000.0)
 
 
-@pytest.mark.parametrize("shape", [synth.TINY, synth.TINY_BF16, synth.TINY_GQA, ODD, ODD.with_(name="tiny-odd-bf16", dtype=synth.BF16)],
-                         ids=lambda s: s.name)
-def test_layer_steps_ragged_small_models(ad, shape):
+@pytest.mark.parametrize("shape,mode", with_modes([synth.TINY, synth.TINY_BF16, synth.TINY_GQA, ODD,
+                                                    ODD.with_(name="tiny-odd-bf16", dtype=synth.BF16)]))
+def test_layer_steps_ragged_small_models(ad, shape, mode):
     import torch
-    print(f"case {shape.name}", flush=True)
+    print(f"case {shape.name} layer mode {mode}", flush=True)
     w = synth.make_weights(shape, seed=11, norm_jitter=0.2)
     T = 45
     toks = synth.make_prompt(shape, seed=5, n=T)
     o = orc.Oracle(shape, w, max_pos=64)
-    g = ad.Model(shape, w, max_pos=64)
+    g = ad.Model(shape, w, max_pos=64, layer_mode=mode)
     tol = TOL[shape.dtype]
     start = 0
     for m in [1, 3, 8, 1, 5, 2, 7, 4, 6, 8]:
@@ -85,20 +92,23 @@ def test_layer_steps_ragged_small_models(ad, shape):
     g.close()
 
 
-@pytest.mark.parametrize("shape,ctx", [(synth.LLAMA8B_LAYER, 4096), (synth.LLAMA13B.with_(name="13b-layer", n_layers=1, exit_layers=(), vocab=256), 1000)],
-                         ids=["8b-layer", "13b-layer"])
-def test_layer_step_full_width_shapes(ad, shape, ctx):
+L13 = synth.LLAMA13B.with_(name="13b-layer", n_layers=1, exit_layers=(), vocab=256)
+
+
+@pytest.mark.parametrize("shape,ctx,mode", [(synth.LLAMA8B_LAYER, 4096, 0), (synth.LLAMA8B_LAYER, 4096, 1), (L13, 1000, 0), (L13, 1000, 1)],
+                         ids=["8b-layer-kernels", "8b-layer-fused", "13b-layer-kernels", "13b-layer-fused"])
+def test_layer_step_full_width_shapes(ad, shape, ctx, mode):
     """The single-layer microbenchmark workload: prefilled N(0,1) cache, N(0,1) hidden rows, m in {1,2,3,4,6,8}
     at positions ctx .. ctx+m-1, cache length reset before each call."""
     import torch
     w = synth.make_weights(shape, seed=0)
     o = orc.Oracle(shape, w, max_pos=ctx + 8)
-    g = ad.Model(shape, w, max_pos=ctx + 8)
+    g = ad.Model(shape, w, max_pos=ctx + 8, layer_mode=mode)
     k, v = synth.make_kv_prefill(shape, 0, 0, ctx)
     o.kv_write(1, 0, k.reshape(ctx, -1), v.reshape(ctx, -1))
     g.kv_fill(1, k, v)
     for call, m in enumerate([1, 2, 3, 4, 6, 8, 8, 1]):
-        print(f"case {shape.name} m={m} call={call}", flush=True)
+        print(f"case {shape.name} layer mode {mode} m={m} call={call}", flush=True)
         o.kv_set_len(1, ctx)
         g.kv_set_len(1, ctx)
         h = synth.make_hidden(shape, seed=100 + call, m=m)
@@ -171,19 +181,18 @@ def compare_runs(shape, g, o, prompt, max_new, gamma, cap, **kw):
     return cmp(g, o, prompt, max_new, gamma, cap, TOL[shape.dtype], **kw)[0]
 
 
-@pytest.mark.parametrize("shape", [synth.TINY, UNTIED, synth.TINY_GQA, UNTIED.with_(name="tiny-untied-bf16", dtype=synth.BF16)],
-                         ids=lambda s: s.name)
-def test_generate_matches_oracle_decisions(ad, shape):
+@pytest.mark.parametrize("shape,mode", with_modes([synth.TINY, UNTIED, synth.TINY_GQA, UNTIED.with_(name="tiny-untied-bf16", dtype=synth.BF16)]))
+def test_generate_matches_oracle_decisions(ad, shape, mode):
     w = synth.make_weights(shape, seed=0)
     max_pos = 160
     o = orc.Oracle(shape, w, max_pos=max_pos)
-    g = ad.Model(shape, w, max_pos=max_pos)
+    g = ad.Model(shape, w, max_pos=max_pos, layer_mode=mode)
     p = synth.make_prompt(shape, 0)
     greedy, margins = o.generate_greedy(p, 64)
     # the workload as stated (gamma 0.9), then thresholds at which exits actually happen, then forced schedules
     total = 0
     for gamma, cap in [(0.9, 7), (1.0, 5), (0.0, 5), (0.0045, 7), (0.05, 3)]:
-        print(f"case {shape.name} gamma={gamma} cap={cap}", flush=True)
+        print(f"case {shape.name} layer mode {mode} gamma={gamma} cap={cap}", flush=True)
         total += compare_runs(shape, g, o, p, 64, gamma, cap)
     for seed in (1, 2):
         k = len(shape.exit_layers)
@@ -200,16 +209,16 @@ def test_generate_matches_oracle_decisions(ad, shape):
     g.close()
 
 
-@pytest.mark.parametrize("shape", [synth.MINI8B, synth.MINI13B], ids=lambda s: s.name)
-def test_generate_full_width_reduced_depth(ad, shape):
+@pytest.mark.parametrize("shape,mode", with_modes([synth.MINI8B, synth.MINI13B]))
+def test_generate_full_width_reduced_depth(ad, shape, mode):
     """8B- and 13B-shaped layers (real d, heads, FFN), 4 layers and a reduced vocabulary so that the oracle
     finishes in seconds; forced schedules exercise ragged catch-up, scripted drafts force rejections."""
     w = synth.make_weights(shape, seed=0)
     max_pos = 64
     o = orc.Oracle(shape, w, max_pos=max_pos)
-    g = ad.Model(shape, w, max_pos=max_pos)
+    g = ad.Model(shape, w, max_pos=max_pos, layer_mode=mode)
     p = synth.make_prompt(shape, 0)
-    print(f"case {shape.name} natural", flush=True)
+    print(f"case {shape.name} layer mode {mode} natural", flush=True)
     compare_runs(shape, g, o, p, shape.gen_len, 0.9, 7)
     forced = synth.make_forced_schedule(shape, 1, max_pos, probs=[0.25, 0.25, 0.25])
     print(f"case {shape.name} forced", flush=True)
@@ -269,6 +278,13 @@ def test_abi_error_paths(ad):
     with pytest.raises(ad.AdError) as e:
         g.ad_generate([1, 2, 3], 4, 0.9, 4)        # cap needs more rows than m_max
     assert e.value.status == ad.AD_ERANGE
+    with pytest.raises(ad.AdError) as e:
+        g.ad_set_layer_mode(ad.AD_LAYER_FUSED)     # the fused layer step exists for bf16 models only
+    assert e.value.status == ad.AD_ESTATE
+    with pytest.raises(ad.AdError) as e:
+        g.ad_set_layer_mode(7)
+    assert e.value.status == ad.AD_EINVAL
+    g.ad_set_layer_mode(ad.AD_LAYER_KERNELS)
     g.close()
 
 
