@@ -23,9 +23,10 @@
 namespace ad {
 
 // ---------------------------------------------------------------------------------------------------
-// bf16 cache: MFMA kernel (device code in ad_attention_device.h), 4 wavefronts per work item
+// bf16 cache: MFMA kernel (device code in ad_attention_device.h), 8 wavefronts per work item: two per block of
+// 32 cached positions, which share the blocks of 8 query rows between them
 // ---------------------------------------------------------------------------------------------------
-constexpr int kAttnThreads = 256;
+constexpr int kAttnThreads = 512;
 
 template <int DH>
 __global__ void __launch_bounds__(kAttnThreads) k_attn_mfma(AttnArgs a) {

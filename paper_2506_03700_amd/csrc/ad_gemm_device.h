@@ -271,57 +271,47 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
     const bf16x8 *strip = reinterpret_cast<const bf16x8 *>(strip16);
     auto sw = [](int u) { return u ^ ((u >> 4) & 15); };
     if (g.x) {
-        // A pass is done in two stages of four tokens; the loads of the next stage are issued before a stage is
-        // converted, so two stages' worth of loads are in flight.
-        f32x4 xr[2][4], wr[2];
-        auto load_stage = [&](f32x4 (&xp)[4], f32x4 &wp, int st) {
-            const int p = st >> 1, th = (st & 1) * 4;
+        // two passes' worth of loads are in flight: those of pass p + 1 are issued before pass p is converted
+        f32x4 xr[2][8], wr[2];
+        auto load_pass = [&](f32x4 (&xp)[8], f32x4 &wp, int p) {
             const int k = (ks0 + p * 8) * 32 + lane * 4;
             const int kc = (k > g.K - 4) ? g.K - 4 : k;              // clamped address, masked result
-            if (p * 8 < nks && th < g.m) {
+            if (p * 8 < nks) {
                 float w8[8];
                 load_w8(g.norm_w, g.norm_is_bf16, (size_t)(kc & ~7), w8);
                 const int o = kc & 4;
                 wp = (f32x4){w8[o], w8[o + 1], w8[o + 2], w8[o + 3]};
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    if (th + t < g.m) xp[t] = Io::ld4(g.x + (size_t)(th + t) * g.ldx + kc);
+                for (int t = 0; t < 8; ++t)
+                    if (t < g.m) xp[t] = Io::ld4(g.x + (size_t)t * g.ldx + kc);
             }
         };
-        load_stage(xr[0], wr[0], 0);
+        load_pass(xr[0], wr[0], 0);
         float ssq[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
+            if (p + 1 < NPASS) load_pass(xr[(p + 1) & 1], wr[(p + 1) & 1], p + 1);
+            const f32x4 (&xp)[8] = xr[p & 1];
+            const f32x4 wp = wr[p & 1];
             const int jn = (nks - p * 8 < 8) ? nks - p * 8 : 8;       // k-steps of this pass (<= 0: none)
-            const int k = (ks0 + p * 8) * 32 + lane * 4;
-            const bool k_on = (lane >> 3) < jn && k < g.K;
-            // position of inputs 4l..4l+3 in the operand: k-step l/8, lane group (l%8)/2, elements (l%2)*4..+3
-            const int u0 = (lane >> 3) * 64 + ((lane & 7) >> 1) * 16;     // unit of column 0
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                const int st = p * 2 + hf;
-                if (st + 1 < NPASS * 2) load_stage(xr[(st + 1) & 1], wr[(st + 1) & 1], st + 1);
-                const f32x4 (&xp)[4] = xr[st & 1];
-                const f32x4 wp = wr[st & 1];
-                if (jn > 0) {
-#pragma unroll
-                    for (int tt = 0; tt < 4; ++tt) {
-                        const int t = hf * 4 + tt;
-                        if (t < g.m) {
-                            union { uint16_t u[4]; uint64_t v; } hi, lo;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const float xv = k_on ? xp[tt][e] : 0.f;
-                                ssq[t] += xv * xv;
-                                split_hi_lo(xv * wp[e], hi.u[e], lo.u[e]);
-                            }
-                            *(uint64_t *)(strip16 + sw(u0 + t) * 8 + (lane & 1) * 4) = hi.v;
-                            *(uint64_t *)(strip16 + sw(u0 + 8 + t) * 8 + (lane & 1) * 4) = lo.v;
-                        }
-                    }
-                }
-            }
             if (jn > 0) {
+                const int k = (ks0 + p * 8) * 32 + lane * 4;
+                const bool k_on = (lane >> 3) < jn && k < g.K;
+                // position of inputs 4l..4l+3 in the operand: k-step l/8, lane group (l%8)/2, elements (l%2)*4..+3
+                const int u0 = (lane >> 3) * 64 + ((lane & 7) >> 1) * 16;     // unit of column 0
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    if (t < g.m) {
+                        union { uint16_t u[4]; uint64_t v; } hi, lo;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float xv = k_on ? xp[t][e] : 0.f;
+                            ssq[t] += xv * xv;
+                            split_hi_lo(xv * wp[e], hi.u[e], lo.u[e]);
+                        }
+                        *(uint64_t *)(strip16 + sw(u0 + t) * 8 + (lane & 1) * 4) = hi.v;
+                        *(uint64_t *)(strip16 + sw(u0 + 8 + t) * 8 + (lane & 1) * 4) = lo.v;
+                    }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
