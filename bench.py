@@ -175,7 +175,7 @@ def main():
     if not args.skip_cpu:
         from oracle import oracle as orc
         n_prompt, n_new = 17, 64          # about 10-15 s of oracle time on the 8B shape
-        o = orc.Oracle(shape, w, max_pos=64)
+        o = orc.Oracle(shape, w, max_pos=n_prompt + n_new + 8)
         t0 = time.perf_counter()
         ot, ost, _ = o.generate_ada(prompt[:n_prompt], n_new, shape.gamma, cap)
         cdt = time.perf_counter() - t0

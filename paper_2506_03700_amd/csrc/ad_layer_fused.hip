@@ -2,10 +2,9 @@
 // persistent kernel for bf16 models: one workgroup of 8 wavefronts per compute unit runs the six phases
 //   QKV projection (RMSNorm fused) | attention items | fold of the splits | Wo + residual |
 //   gate/up (RMSNorm fused) + SwiGLU | down + residual
-// separated by five grid barriers.  Compared with one kernel per phase this removes the launch gaps and, more
-// importantly, lets every workgroup put the first weight batches of the next phase in flight *before* it waits
-// at the barrier (weights do not depend on the previous phase), so the HBM stream hardly stops at a phase
-// boundary.
+// separated by five grid barriers.  Compared with one kernel per phase this removes the launch gaps and lets every
+// workgroup put the first weight batches of the next phase in flight *while* it waits at the barrier (weights do
+// not depend on the previous phase), so the HBM stream hardly stops at a phase boundary.
 //
 // Data handed from one phase to the next (q/k/v rows, attention partials, packed activations, x') is written
 // and read with relaxed agent-scope atomics (see IoAgent): the stores go through to memory, a wavefront waits
@@ -40,10 +39,16 @@ struct GridBarrier {
     // Returns false (to every thread of the workgroup) if the wait timed out or another workgroup gave up.
     // acquire: also invalidate this compute unit's L1 and this XCD's stale L2 lines, so that ordinary loads after
     // the barrier see what other workgroups stored (write-through) before it.
-    __device__ __forceinline__ bool sync(bool acquire = false) {
+    // pre: issues the next phase's first weight loads.  It runs after the workgroup has counted itself in (issuing
+    // loads to a region nobody has touched yet can stall a wavefront for microseconds, which must not delay the
+    // other workgroups) and while wavefront 0 waits for the grid; wavefront 0 issues its own share after the wait,
+    // because its polling loads would queue behind them.
+    template <class Pre>
+    __device__ __forceinline__ bool sync(bool acquire, Pre pre) {
         __builtin_amdgcn_s_waitcnt(0);     // this wavefront's stores have completed
         __syncthreads();
         ++round;
+        if (threadIdx.x >= 64) pre();
         if (threadIdx.x == 0) {
             const unsigned nwg = gridDim.x, g = blockIdx.x & 7, n_groups = nwg < 8 ? nwg : 8, per = (nwg - g + 7) >> 3;
             const unsigned old = __hip_atomic_fetch_add(ctr + 32 * (1 + g), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -63,6 +68,7 @@ struct GridBarrier {
             if (acquire) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         }
         __syncthreads();
+        if (threadIdx.x < 64) pre();
         return *ok != 0;
     }
 };
@@ -99,42 +105,39 @@ __global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f) {
     s_qkv.prefetch();
     AttnKv<DH> kv;
     auto pre_attn = [&]() { attn_load_kv<DH, kFusedThreads>(f.attn, wg, kv); };   // the cached K/V block of the first item
-    if (wg < f.nwg_qkv) gemm_stationary<1, CH, NCHMAX, IoAgent, EPI_STORE>(f.qkv, s_qkv, L.gemm, pre_attn);
-    else pre_attn();
+    if (wg < f.nwg_qkv) gemm_stationary<1, CH, NCHMAX, IoAgent, EPI_STORE>(f.qkv, s_qkv, L.gemm, NoTail());
     stamp();
-    if (!bar.sync()) return;
+    if (!bar.sync(false, pre_attn)) return;
     stamp();
 
     // ---- 2. rotary embedding, KV append, attention partials ------------------------------------------------
     attn_mfma_items<DH, kFusedThreads, IoAgent>(f.attn, L.attn, wg, nwg, kv, true);
     stamp();
-    if (!bar.sync()) return;
+    if (!bar.sync(false, NoTail())) return;
     stamp();
 
     // ---- 3. fold the splits of each query row (one wavefront per row), packed for Wo -------------------------
     for (int row = wave * nwg + wg; row < f.attn.Hq * f.attn.m; row += NW * nwg) attn_combine_row<IoAgent>(f.attn, row);
     s_wo.init(f.wo, wg, f.nwg_wo);
-    s_wo.prefetch(f.wo);
+    auto pre_wo = [&]() { s_wo.prefetch(f.wo); };
     stamp();
-    if (!bar.sync(true)) return;
+    if (!bar.sync(true, pre_wo)) return;
     stamp();
 
     // ---- 4. x' = x + Wo o ------------------------------------------------------------------------------------
     s_gu.init(f.gu, wg, f.nwg_gu);
     auto pre_gu = [&]() { s_gu.prefetch(); };
-    if (wg < f.nwg_wo) gemm_streamed<1, U, NW, IoAcquired, EPI_RESID, true>(f.wo, s_wo, L.gemm, pre_gu);
-    else pre_gu();
+    if (wg < f.nwg_wo) gemm_streamed<1, U, NW, IoAcquired, EPI_RESID, true>(f.wo, s_wo, L.gemm, NoTail());
     stamp();
-    if (!bar.sync(true)) return;
+    if (!bar.sync(true, pre_gu)) return;
     stamp();
 
     // ---- 5. g = silu(Wg b) * (Wu b), b = RMSNorm(x') -----------------------------------------------------------
     s_down.init(f.down, wg, f.nwg_down);
     auto pre_down = [&]() { s_down.prefetch(f.down); };
-    if (wg < f.nwg_gu) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_SWIGLU>(f.gu, s_gu, L.gemm, pre_down);
-    else pre_down();
+    if (wg < f.nwg_gu) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_SWIGLU>(f.gu, s_gu, L.gemm, NoTail());
     stamp();
-    if (!bar.sync(true)) return;
+    if (!bar.sync(true, pre_down)) return;
     stamp();
 
     // ---- 6. y = x' + Wd g ----------------------------------------------------------------------------------------
