@@ -333,12 +333,21 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
                 if (lane == 0) L.ssq_part[wave * 8 + t] = v;
             }
     } else {
+        // B was packed by an earlier epilogue: only the lanes of the call's tokens load
 #pragma unroll
         for (int j = 0; j < KSB; ++j) {
-            int ks = ks0 + j;
-            if (ks > g.KT - 1) ks = g.KT - 1;
-            const bf16x8 v = Io::ldb((const bf16x8 *)g.B + act_operand_index(ks, lane, g.KT));
-            b[j] = (lane_on && j < nks) ? v : zero;
+            b[j] = zero;
+            if (lane_on && j < nks) b[j] = Io::ldb((const bf16x8 *)g.B + act_operand_index(ks0 + j, lane, g.KT));
+        }
+        if (g.ssq_in) {
+            // the producer left per-tile sums of squares: wavefront t adds up token t's, in tile order per lane and
+            // then across the lanes (fixed order)
+            const int t = wave;
+            float v = 0.f;
+            if (t < g.m)
+                for (int i = lane; i < g.ssq_tiles; i += 64) v += Io::ld(g.ssq_in + (size_t)i * 8 + t);
+            for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+            if (lane == 0) L.ssq_part[t] = v;
         }
     }
     __syncthreads();
@@ -348,6 +357,8 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
             s = 0.f;
             for (int w = 0; w < kWaves; ++w) s += L.ssq_part[w * 8 + tid];
             s = 1.0f / sqrtf(s * g.inv_dim + g.eps);
+        } else if (!g.x && g.ssq_in) {
+            s = 1.0f / sqrtf(L.ssq_part[tid] * g.inv_dim + g.eps);
         }
         L.scale[tid] = s;
     }
@@ -586,7 +597,20 @@ __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NP
 #pragma unroll
             for (int j = 0; j < RP; ++j) {
                 const int idx = tid + j * NTHREADS, T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15, n = (ta + T) * 16 + i;
-                if (idx < nt * 128 && t < g.m && n < g.N) Io::st(g.out + (size_t)t * g.ld + n, rpre[j] + L.red[idx]);
+                const bool on = idx < nt * 128 && t < g.m && n < g.N;
+                const float y = on ? rpre[j] + L.red[idx] : 0.f;
+                if (on) Io::st(g.out + (size_t)t * g.ld + n, y);
+                if (g.Bnext) {
+                    // input of the next GEMM: y * norm weight, packed; and this tile's share of sum(y^2) per token
+                    // (the 16 outputs of a (tile, token) pair sit in 16 neighbouring lanes)
+                    if (on) store_act_io<Io>((uint16_t *)g.Bnext, g.Bnext_KT, n, t, y * load_w(g.next_norm_w, g.next_norm_is_bf16, (size_t)n));
+                    float q = y * y;
+                    q += __shfl_xor(q, 8);
+                    q += __shfl_xor(q, 4);
+                    q += __shfl_xor(q, 2);
+                    q += __shfl_xor(q, 1);
+                    if (i == 0 && idx < nt * 128 && t < g.m) Io::st(g.ssq_out + (size_t)(ta + T) * 8 + t, q);
+                }
             }
         } else {
             epilogue<Io, EPI>(g, L, ta, nt, tid, lane, wave, NTHREADS);

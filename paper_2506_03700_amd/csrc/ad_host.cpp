@@ -101,6 +101,8 @@ void make_layout(const ad_config &c, Layout &L) {
     s += align_up(act_packed_bytes(L.d));                      // B1 (exit-head transform output)
     s += align_up(act_packed_bytes(L.dq));                     // Bo (attention output)
     s += align_up(act_packed_bytes(L.f));                      // Bg (SwiGLU output)
+    s += align_up(act_packed_bytes(L.d));                      // Bx (x' * ffn norm weight, packed by the Wo epilogue)
+    s += align_up((size_t)(L.d / 16) * 8 * 4);                 // per-tile sums of squares of x'
     s += align_up((size_t)8 * L.nqkv * 4);                     // qkv
     s += 2 * align_up((size_t)8 * L.d * 4);                    // x1, rows
     s += align_up((size_t)4096 * 8 * 4 * 4);                   // head partials (up to 4096 workgroups)
@@ -129,7 +131,8 @@ struct ad_model {
     std::vector<LayerPacked> layers;
     char *embed, *final_norm, *head, *T[AD_MAX_EXIT];
     // scratch
-    char *B1, *Bo, *Bg;
+    char *B1, *Bo, *Bg, *Bx;
+    float *ssq;
     float *qkv, *x1, *rows, *head_part;
     // pinned host results for ad_generate
     int32_t *pin;         // [0..8) tok, [8] n_accept, [9] next, [16..24) row argmax
@@ -236,6 +239,8 @@ ad_status ad_model_create(const ad_config *cfg, const ad_layer_weights *layers, 
     m->B1 = take(act_packed_bytes(L.d));
     m->Bo = take(act_packed_bytes(L.dq));
     m->Bg = take(act_packed_bytes(L.f));
+    m->Bx = take(act_packed_bytes(L.d));
+    m->ssq = (float *)take((size_t)(L.d / 16) * 8 * 4);
     m->qkv = (float *)take((size_t)8 * L.nqkv * 4);
     m->x1 = (float *)take((size_t)8 * L.d * 4);
     m->rows = (float *)take((size_t)8 * L.d * 4);
@@ -437,11 +442,13 @@ ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidde
     memset(&go, 0, sizeof go);
     go.W = lp.wo; go.B = m->Bo; go.NT = L.d / 16; go.KT = L.kt_q; go.N = L.d; go.K = L.dq; go.m = n; go.mode = GEMM_STREAMED;
     go.epi = EPI_RESID; go.resid = (const float *)hidden; go.out = m->x1; go.ld = L.d;
+    // ... and the Wo epilogue already prepares the gate/up GEMM's input: x' * ffn norm weight packed, sum(x'^2) per tile
+    go.Bnext = m->Bx; go.Bnext_KT = L.kt_d; go.next_norm_w = lp.ffn_norm; go.next_norm_is_bf16 = bf; go.ssq_out = m->ssq;
     // 4. g = silu(Wg b) * (Wu b), b = RMSNorm(x') fused as in step 1
     GemmArgs gg;
     memset(&gg, 0, sizeof gg);
     gg.W = lp.wgu; gg.NT = (2 * L.f) / 16; gg.KT = L.kt_d; gg.N = 2 * L.f; gg.K = L.d; gg.m = n; gg.mode = GEMM_STATIONARY;
-    gg.x = m->x1; gg.ldx = L.d; gg.norm_w = lp.ffn_norm; gg.norm_is_bf16 = bf; gg.inv_dim = 1.0f / (float)L.d; gg.eps = c.rms_eps;
+    gg.B = m->Bx; gg.ssq_in = m->ssq; gg.ssq_tiles = go.NT; gg.inv_dim = 1.0f / (float)L.d; gg.eps = c.rms_eps;
     gg.epi = EPI_SWIGLU; gg.Bnext = m->Bg; gg.Bnext_KT = L.kt_f;
     // 5. y = x' + Wd g
     GemmArgs gd;

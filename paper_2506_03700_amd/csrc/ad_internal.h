@@ -60,6 +60,15 @@ struct GemmArgs {
     int ld;
     void *Bnext;          // packed activations written by the epilogue
     int Bnext_KT;         // k-steps of that block (the K of the GEMM that will read it, in units of 32)
+    // EPI_RESID in streamed mode, optional (Bnext non-null): the epilogue also prepares the next GEMM's input, which is
+    // RMSNorm(out): it packs out * next_norm_w into Bnext and writes the sum of squares of its 16 outputs per token
+    // to ssq_out[tile][token].  The consumer (stationary mode, B = that block, ssq_in = those partials, ssq_tiles
+    // of them) only has to load its operand registers and add the partials up for the 1/rms factor.
+    const void *next_norm_w;
+    int next_norm_is_bf16;
+    float *ssq_out;
+    const float *ssq_in;
+    int ssq_tiles;
     // head
     float *head_part;     // [nwg][8][4] (max, sumexp, argmax as int bits, unused)
     int n_parts;          // workgroups that wrote head_part (set by the launcher)
