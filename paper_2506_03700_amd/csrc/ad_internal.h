@@ -24,7 +24,6 @@ constexpr int kTileRows = 16;
 constexpr int kTileK = 32;
 constexpr int kThreads = 1024;   // one workgroup per CU, 16 wavefronts
 constexpr int kWaves = kThreads / 64;
-constexpr int kMaxTilesPerRound = 32;
 
 inline size_t packed_bytes(int64_t N, int64_t K, int planes) {
     const int64_t nt = (N + kTileRows - 1) / kTileRows, kt = (K + kTileK - 1) / kTileK;
