@@ -36,8 +36,19 @@ static inline double bf16_value(uint16_t bits) {
     return (double)c.f;
 }
 
+/* IEEE half precision (1 sign, 5 exponent, 10 fraction bits) widened exactly */
+static inline double f16_value(uint16_t bits) {
+    const int sign = bits >> 15, e = (bits >> 10) & 31, f = bits & 1023;
+    double v;
+    if (e == 0) v = ldexp((double)f, -24);                     /* zero and subnormals: f * 2^-24 */
+    else if (e == 31) v = f ? NAN : INFINITY;
+    else v = ldexp((double)(1024 + f), e - 25);                /* (1 + f/1024) * 2^(e-15) */
+    return sign ? -v : v;
+}
+
 static inline double weight_at(const void *w, int32_t wdtype, size_t i) {
-    return wdtype == ORC_F32 ? (double)((const float *)w)[i] : bf16_value(((const uint16_t *)w)[i]);
+    if (wdtype == ORC_F32) return (double)((const float *)w)[i];
+    return wdtype == ORC_BF16 ? bf16_value(((const uint16_t *)w)[i]) : f16_value(((const uint16_t *)w)[i]);
 }
 
 /* A value as a bf16 cache stores it: to fp32, then round-to-nearest-even to 8 significand bits. */
@@ -49,6 +60,19 @@ static inline double round_to_bf16(double x) {
     return (double)c.f;
 }
 
+/* A value as an fp16 cache stores it: to fp32, then round-to-nearest-even to half precision (11 significand
+ * bits above 2^-14, multiples of 2^-24 below; finite inputs far below the half-precision maximum). */
+static inline double round_to_f16(double x) {
+    const float f = (float)x;
+    const double a = fabs((double)f);
+    if (a == 0.0) return (double)f;
+    int e;
+    (void)frexp(a, &e);                                         /* a = frac * 2^e, frac in [0.5, 1) */
+    const int q = (e - 1 < -14 ? -14 : e - 1) - 10;             /* exponent of the last kept bit */
+    const double r = ldexp(nearbyint(ldexp(a, -q)), q);         /* nearbyint: ties to even (default mode) */
+    return f < 0 ? -r : r;
+}
+
 /* sum_i w[off+i] * x[i] */
 static double dot_w(const void *w, int32_t wdtype, size_t off, const double *x, int32_t n) {
     double acc = 0.0;
@@ -56,10 +80,13 @@ static double dot_w(const void *w, int32_t wdtype, size_t off, const double *x, 
         const float *p = (const float *)w + off;
 #pragma omp simd reduction(+ : acc)
         for (int32_t i = 0; i < n; ++i) acc += (double)p[i] * x[i];
-    } else {
+    } else if (wdtype == ORC_BF16) {
         const uint16_t *p = (const uint16_t *)w + off;
 #pragma omp simd reduction(+ : acc)
         for (int32_t i = 0; i < n; ++i) acc += bf16_value(p[i]) * x[i];
+    } else {
+        const uint16_t *p = (const uint16_t *)w + off;
+        for (int32_t i = 0; i < n; ++i) acc += f16_value(p[i]) * x[i];
     }
     return acc;
 }
@@ -232,6 +259,11 @@ int orc_layer_step(const orc_model *model, orc_kv *kv, int32_t layer, double *hi
             for (int32_t e = 0; e < dkv; ++e) {
                 kk[(size_t)r * dkv + e] = round_to_bf16(kk[(size_t)r * dkv + e]);
                 vv[(size_t)r * dkv + e] = round_to_bf16(vv[(size_t)r * dkv + e]);
+            }
+        else if (c->kv_dtype == ORC_F16)
+            for (int32_t e = 0; e < dkv; ++e) {
+                kk[(size_t)r * dkv + e] = round_to_f16(kk[(size_t)r * dkv + e]);
+                vv[(size_t)r * dkv + e] = round_to_f16(vv[(size_t)r * dkv + e]);
             }
         memcpy(K + (size_t)pos[r] * dkv, kk + (size_t)r * dkv, sizeof(double) * (size_t)dkv);
         memcpy(V + (size_t)pos[r] * dkv, vv + (size_t)r * dkv, sizeof(double) * (size_t)dkv);

@@ -7,9 +7,9 @@
  * It shares no code with the HIP path and must never be linked into, imported by or called from the
  * product: only tests, the smoke check and the benchmark's CPU-baseline leg use it.
  *
- * Arithmetic: every value is a double; weights are read as stored (fp32, or bf16 bit patterns widened
- * exactly) and never rounded again.  The one storage format that is part of a workload's definition, a bf16
- * KV cache, is modelled as such: entries are quantised to bf16 when they are stored (kv_dtype), and every
+ * Arithmetic: every value is a double; weights are read as stored (fp32, or bf16 / fp16 bit patterns widened
+ * exactly) and never rounded again.  The one storage format that is part of a workload's definition, a 16-bit
+ * KV cache, is modelled as such: entries are quantised to its type when they are stored (kv_dtype), and every
  * later read sees the stored value.  Dot products may be summed in any order (the compiler is allowed
  * to vectorise them); nothing else is reordered, blocked or fused.
  *
@@ -29,19 +29,19 @@
 extern "C" {
 #endif
 
-enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2 };   /* fp32, bf16 bit patterns, IEEE half precision */
 enum { ORC_MAX_EXIT = 8 };
 
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
     double  rope_base, rms_eps;
-    int32_t wdtype;                       /* ORC_F32 or ORC_BF16: storage of every weight tensor */
+    int32_t wdtype;                       /* ORC_F32, ORC_BF16 or ORC_F16: storage of every weight tensor */
     int32_t n_exit;
     int32_t exit_layers[ORC_MAX_EXIT];    /* 1-based, ascending, each < n_layers */
     int32_t kv_dtype;                     /* storage format of the KV cache: ORC_F32 keeps the computed values,
-                                             ORC_BF16 rounds every stored K (after the rotary embedding) and V entry to
-                                             bf16, round-to-nearest-even, as a bf16 cache does; attention then reads
-                                             the stored values */
+                                             ORC_BF16 / ORC_F16 round every stored K (after the rotary embedding) and
+                                             V entry to that type, round-to-nearest-even, as a 16-bit cache does;
+                                             attention then reads the stored values */
 } orc_config;
 
 /* All matrices are [out_features, in_features] row-major. */

@@ -114,9 +114,10 @@ def _i32(a) -> np.ndarray:
 def rmsnorm(x, w: np.ndarray, eps: float) -> np.ndarray:
     x = _f64(x)
     w = np.ascontiguousarray(w)
-    assert w.dtype in (np.float32, np.uint16)
+    assert w.dtype in (np.float32, np.uint16, np.float16)
     out = np.empty_like(x)
-    lib().orc_rmsnorm(x.ctypes.data, w.ctypes.data, 0 if w.dtype == np.float32 else 1, x.size, eps, out.ctypes.data)
+    lib().orc_rmsnorm(x.ctypes.data, w.ctypes.data, {np.dtype(np.float32): 0, np.dtype(np.uint16): 1, np.dtype(np.float16): 2}[w.dtype],
+                      x.size, eps, out.ctypes.data)
     return out
 
 
@@ -146,8 +147,8 @@ class Oracle:
                      shape.vocab, shape.rope_base, shape.rms_eps, shape.dtype, len(shape.exit_layers))
         for i, l in enumerate(shape.exit_layers):
             cfg.exit_layers[i] = l
-        cfg.kv_dtype = shape.dtype        # a bf16 workload keeps a bf16 KV cache
-        want = np.float32 if shape.dtype == 0 else np.uint16
+        cfg.kv_dtype = shape.dtype        # a 16-bit workload keeps a KV cache of its type
+        want = (np.float32, np.uint16, np.float16)[shape.dtype]
         for k, v in weights.items():
             assert v.dtype == want and v.flags["C_CONTIGUOUS"], k
         layers = (LayerWeights * shape.n_layers)()

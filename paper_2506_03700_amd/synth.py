@@ -2,8 +2,9 @@
 
 This module is data only. It serves both the CPU oracle (tests) and the HIP library (tests, bench,
 smoke) with the *same* buffers, and contains none of the method's arithmetic: no norm, no attention,
-no head, no scheduling.  The only numeric helper is the storage rounding of fp32 values to bf16 bit
-patterns (round-to-nearest-even), which is how the bf16 workloads' weights are defined.
+no head, no scheduling.  The only numeric helpers are the storage roundings of fp32 values to bf16 bit
+patterns and to IEEE half precision (both round-to-nearest-even), which is how the 16-bit workloads'
+weights are defined.
 
 The workloads stand in for the paper's models (Llama-3.1-8B-Instruct, CodeLlama-13B-Instruct; Sec. 3
 "Experimental setup", Table 4 for the LM-head shapes) which are not available here: Llama-shaped
@@ -21,6 +22,7 @@ import numpy as np
 
 F32 = 0
 BF16 = 1
+F16 = 2     # IEEE half precision, the inference precision the paper reports (Sec. 4.2)
 
 
 @dataclasses.dataclass(frozen=True)
@@ -35,7 +37,7 @@ class ModelShape:
     vocab: int
     rope_base: float
     exit_layers: Tuple[int, ...]      # 1-based layer indices that carry an exit head, each < n_layers
-    dtype: int                        # F32 or BF16 (storage type of weights and of the GPU KV cache)
+    dtype: int                        # F32, BF16 or F16 (storage type of weights and of the KV cache)
     tied_head: bool                   # LM head shares the embedding matrix
     rms_eps: float = 1e-5
     gamma: float = 0.9
@@ -55,7 +57,7 @@ class ModelShape:
         return (self.d_q + 2 * self.d_kv) * d + d * self.d_q + 3 * d * f
 
     def elem_bytes(self) -> int:
-        return 2 if self.dtype == BF16 else 4
+        return 4 if self.dtype == F32 else 2
 
     def with_(self, **kw) -> "ModelShape":
         return dataclasses.replace(self, **kw)
@@ -75,6 +77,7 @@ LLAMA8B_LONG = LLAMA8B.with_(name="8b-long", prompt_len=1024, gen_len=8192)
 # Reduced-depth variants used where the full model would make a CPU comparison take too long; the
 # per-layer shapes (what every kernel sees) are unchanged.
 TINY_BF16 = TINY.with_(name="tiny-bf16", dtype=BF16)
+TINY_F16 = TINY.with_(name="tiny-f16", dtype=F16)
 TINY_GQA = TINY.with_(name="tiny-gqa", n_q_heads=4, n_kv_heads=2, n_layers=6, exit_layers=(2, 4))
 MINI8B = LLAMA8B.with_(name="8b-mini", n_layers=4, exit_layers=(1, 2, 3), vocab=8192,
                        prompt_len=24, gen_len=24)
@@ -92,6 +95,16 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     return ((u + bias) >> np.uint32(16)).astype(np.uint16)
 
 
+def store_as(x: np.ndarray, dtype: int) -> np.ndarray:
+    """fp32 values in the storage type of a workload: fp32 as is, bf16 as uint16 bit patterns, fp16 as numpy
+    float16 (numpy's conversion rounds to nearest even)."""
+    if dtype == F32:
+        return np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == BF16:
+        return f32_to_bf16_bits(x)
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16)
+
+
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
@@ -104,20 +117,18 @@ def _tensor_seed(seed: int, name: str) -> np.random.Generator:
 def _normal(seed: int, name: str, shape: Sequence[int], std: float, dtype: int) -> np.ndarray:
     rng = _tensor_seed(seed, name)
     n = int(np.prod(shape))
-    out = np.empty(n, dtype=np.float32 if dtype == F32 else np.uint16)
+    out = np.empty(n, dtype={F32: np.float32, BF16: np.uint16, F16: np.float16}[dtype])
     step = 1 << 24
     for s in range(0, n, step):        # chunked so that the fp32 temporary stays small
         e = min(n, s + step)
         blk = rng.standard_normal(e - s, dtype=np.float32)
         blk *= np.float32(std)
-        out[s:e] = blk if dtype == F32 else f32_to_bf16_bits(blk)
+        out[s:e] = store_as(blk, dtype)
     return out.reshape(shape)
 
 
 def _ones(shape: Sequence[int], dtype: int) -> np.ndarray:
-    if dtype == F32:
-        return np.ones(shape, dtype=np.float32)
-    return np.full(shape, 0x3F80, dtype=np.uint16)
+    return store_as(np.ones(shape, dtype=np.float32), dtype)
 
 
 def make_weights(shape: ModelShape, seed: int = 0, *, with_T: bool = False, T_std: float = 0.01,
@@ -153,7 +164,7 @@ def make_weights(shape: ModelShape, seed: int = 0, *, with_T: bool = False, T_st
         if norm_jitter == 0.0:
             return _ones((d,), dt)
         v = 1.0 + norm_jitter * _tensor_seed(seed, name).standard_normal(d).astype(np.float32)
-        return v.astype(np.float32) if dt == F32 else f32_to_bf16_bits(v)
+        return store_as(v, dt)
 
     out["final_norm"] = norm_w("final_norm")
     for l in range(shape.n_layers):
@@ -163,7 +174,7 @@ def make_weights(shape: ModelShape, seed: int = 0, *, with_T: bool = False, T_st
         for i, _ in enumerate(shape.exit_layers):
             t = T_std * _tensor_seed(seed, f"exit_T.{i}").standard_normal((d, d)).astype(np.float32)
             t += np.eye(d, dtype=np.float32)
-            out[f"exit_T.{i}"] = t if dt == F32 else f32_to_bf16_bits(t)
+            out[f"exit_T.{i}"] = store_as(t, dt)
     return out
 
 
@@ -180,15 +191,15 @@ def make_hidden(shape: ModelShape, seed: int, m: int) -> np.ndarray:
 def make_kv_prefill(shape: ModelShape, seed: int, layer: int, n_pos: int) -> Tuple[np.ndarray, np.ndarray]:
     """K and V values for positions [0, n_pos) of one layer, each [n_pos, n_kv_heads, head_dim], N(0,1).
 
-    For a BF16 shape the values are already rounded to bf16 (returned as fp32 holding bf16-exact
-    numbers) so that a bf16 cache and the oracle's cache start from identical numbers.
+    For a 16-bit shape the values are already rounded to the cache's type (returned as fp32 holding exactly
+    representable numbers) so that the GPU cache and the oracle's cache start from identical numbers.
     """
     shp = (n_pos, shape.n_kv_heads, shape.head_dim)
     k = _tensor_seed(seed, f"kv.{layer}.k").standard_normal(shp, dtype=np.float32)
     v = _tensor_seed(seed, f"kv.{layer}.v").standard_normal(shp, dtype=np.float32)
-    if shape.dtype == BF16:
-        k = bf16_bits_to_f32(f32_to_bf16_bits(k))
-        v = bf16_bits_to_f32(f32_to_bf16_bits(v))
+    if shape.dtype != F32:
+        k = as_f32(store_as(k, shape.dtype))
+        v = as_f32(store_as(v, shape.dtype))
     return k, v
 
 
@@ -211,4 +222,4 @@ def make_forced_schedule(shape: ModelShape, seed: int, n_pos: int,
 
 def as_f32(w: np.ndarray) -> np.ndarray:
     """The real values a stored tensor represents (fp32 array), whatever its storage type."""
-    return bf16_bits_to_f32(w) if w.dtype == np.uint16 else w.astype(np.float32, copy=False)
+    return bf16_bits_to_f32(w) if w.dtype == np.uint16 else w.astype(np.float32, copy=False)   # float16 widens exactly

@@ -164,3 +164,20 @@ def test_bf16_rounding_helper():
     # ties go to even: 1 + 2^-8 -> 1, 1 + 3*2^-8 -> 1 + 2^-6
     np.testing.assert_array_equal(b[:4], np.array([1.0, 1.0, 1.0 + 2 ** -7, 1.0 + 2 ** -6], dtype=np.float32))
     assert abs(b[4] + 0.3) < 0.3 * 2 ** -8
+
+
+def test_fp16_weights_are_read_exactly():
+    # every kind of half-precision value (zero, subnormals, the smallest normal, the largest finite value, both
+    # signs) must come out of the oracle as numpy's own exact widening: x = ones has rms 1, so rmsnorm returns w
+    rng = np.random.default_rng(0)
+    w = (rng.standard_normal(2048) * 3).astype(np.float16)
+    w[:10] = np.array([0.0, -0.0, 6e-8, -6e-8, 5.96e-8, 6.1e-5, 6.104e-5, 65504, -65504, 1e-7], dtype=np.float16)
+    out = orc.rmsnorm(np.ones(w.size), w, 0.0)
+    np.testing.assert_array_equal(out, w.astype(np.float64))
+
+
+def test_fp16_storage_helper_rounds_to_nearest_even():
+    # 1 + 2^-11 is a tie between 1 and 1 + 2^-10 -> 1 (even); 1 + 3*2^-11 is a tie -> 1 + 2^-9
+    x = np.array([1.0 + 2 ** -11, 1.0 + 3 * 2 ** -11, 1.0 + 2 ** -10, 2.0 ** -25, 3 * 2.0 ** -25], dtype=np.float32)
+    h = synth.as_f32(synth.store_as(x, synth.F16))
+    np.testing.assert_array_equal(h, np.array([1.0, 1.0 + 2 ** -9, 1.0 + 2 ** -10, 0.0, 2.0 ** -23], dtype=np.float32))

@@ -47,6 +47,8 @@ def library_forward(shape, w, tokens, T_index=None):
         q, k = _rope_complex(q, s.rope_base), _rope_complex(k, s.rope_base)
         if s.dtype == synth.BF16:      # a bf16 workload stores K and V in a bf16 cache (library rounding, RNE)
             k, v = k.float().bfloat16().double(), v.float().bfloat16().double()
+        elif s.dtype == synth.F16:     # likewise an fp16 workload (the paper's inference precision, Sec. 4.2)
+            k, v = k.float().half().double(), v.float().half().double()
         Ks.append(k)
         Vs.append(v)
         rep = s.n_q_heads // s.n_kv_heads
@@ -62,7 +64,7 @@ def library_forward(shape, w, tokens, T_index=None):
     return hs, Ks, Vs, n @ _t(w["lm_head"]).T
 
 
-SHAPES = [synth.TINY, synth.TINY_BF16, synth.TINY_GQA,
+SHAPES = [synth.TINY, synth.TINY_BF16, synth.TINY_F16, synth.TINY_GQA.with_(name="tiny-gqa-f16", dtype=synth.F16), synth.TINY_GQA,
           synth.TINY.with_(name="tiny-odd", n_q_heads=6, n_kv_heads=2, head_dim=32, d_model=96, d_ffn=200, vocab=301,
                            n_layers=3, rope_base=500000.0)]
 
