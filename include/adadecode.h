@@ -45,7 +45,7 @@ typedef enum {
     AD_ENOMEM = 5    /* workspace / storage too small */
 } ad_status;
 
-typedef enum { AD_F32 = 0, AD_BF16 = 1 } ad_dtype;
+typedef enum { AD_F32 = 0, AD_BF16 = 1, AD_F16 = 2 } ad_dtype;
 
 enum { AD_MAX_EXIT = 8, AD_M_MAX = 8 };
 
@@ -53,7 +53,9 @@ typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;   /* d_model % 16 == 0 and <= 5120,
                                                                                    head_dim 64 or 128, d_ffn % 8 == 0 */
     float   rope_base, rms_eps;
-    int32_t dtype;                       /* ad_dtype: storage of the weights passed in and of the KV cache */
+    int32_t dtype;                       /* ad_dtype: storage of the weights passed in and of the KV cache.  AD_F16 is
+                                            IEEE half precision, the precision the paper's models run in (Sec. 4.2);
+                                            hidden states are fp32 at the boundary for every dtype */
     int32_t n_exit;                      /* number of exit heads */
     int32_t exit_layers[AD_MAX_EXIT];    /* 1-based, ascending, each < n_layers (Sec. 2.1: heads at chosen layers) */
     int32_t m_max;                       /* largest number of rows per call, 1..AD_M_MAX */

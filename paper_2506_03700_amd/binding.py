@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libadadecode.so")
 SCHED_TEST_LIB_PATH = os.path.join(HERE, "libad_sched_test.so")
 
 AD_OK, AD_EINVAL, AD_ERANGE, AD_ESTATE, AD_EDEVICE, AD_ENOMEM = range(6)
-AD_F32, AD_BF16 = 0, 1
+AD_F32, AD_BF16, AD_F16 = 0, 1, 2
 AD_MAX_EXIT, AD_M_MAX = 8, 8
 EV_LAYER_STEP, EV_HEAD, EV_VERIFY, EV_VERIFY_ROW = 1, 2, 3, 4
 AD_LAYER_KERNELS, AD_LAYER_FUSED = 0, 1
@@ -221,7 +221,7 @@ class Model:
         """(K, V): K as [layer][kv head][position][head_dim], V as [layer][kv head][head_dim][position]
         (the library stores V transposed), positions 0..stride, of the storage dtype."""
         s, torch = self.shape, self.torch
-        dt = torch.bfloat16 if s.dtype == AD_BF16 else torch.float32
+        dt = {AD_F32: torch.float32, AD_BF16: torch.bfloat16, AD_F16: torch.float16}[s.dtype]
         half = s.n_kv_heads * self.kv_stride * s.head_dim
         flat = self.kv_storage[: s.n_layers * 2 * half * s.elem_bytes()].view(dt).view(s.n_layers, 2, half)
         k = flat[:, 0].view(s.n_layers, s.n_kv_heads, self.kv_stride, s.head_dim)

@@ -28,11 +28,11 @@ namespace ad {
 // ---------------------------------------------------------------------------------------------------
 constexpr int kAttnThreads = 512;
 
-template <int DH>
+template <int DH, bool F16>
 __global__ void __launch_bounds__(kAttnThreads) k_attn_mfma(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     AttnKv<DH> kv;
-    attn_mfma_items<DH, kAttnThreads, IoPlain>(a, *reinterpret_cast<AttnMfmaLds<DH> *>(lds_raw), blockIdx.x, gridDim.x, kv, false);
+    attn_mfma_items<DH, kAttnThreads, IoPlain, F16>(a, *reinterpret_cast<AttnMfmaLds<DH> *>(lds_raw), blockIdx.x, gridDim.x, kv, false);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -168,7 +168,9 @@ __global__ void __launch_bounds__(kValuThreads) k_attn_valu(AttnArgs a) {
 // ---------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_attn_combine(AttnArgs a) {
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row < a.Hq * a.m) attn_combine_row<IoPlain>(a, row);
+    if (row >= a.Hq * a.m) return;
+    if (a.kv_elem == ELEM_F16) attn_combine_row<IoPlain, true>(a, row);
+    else attn_combine_row<IoPlain, false>(a, row);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -179,7 +181,7 @@ constexpr size_t valu_lds_bytes(size_t kv_elem, int dh) {
            2 * (size_t)valu_max_keys(kv_elem, dh) * (dh + 16 / kv_elem) * kv_elem;
 }
 
-int attn_chunk(int kv_is_bf16, int dh) { return kv_is_bf16 ? 128 : valu_max_keys(4, dh) - 8; }
+int attn_chunk(int kv_elem, int dh) { return kv_elem != kElemF32 ? 128 : valu_max_keys(4, dh) - 8; }
 
 template <typename KVT, int DH>
 static int launch_valu(const AttnArgs &a, const LaunchCtx &c) {
@@ -196,26 +198,30 @@ static int launch_valu(const AttnArgs &a, const LaunchCtx &c) {
     return (int)hipGetLastError();
 }
 
-template <int DH>
+template <int DH, bool F16>
 static int launch_mfma(const AttnArgs &a, const LaunchCtx &c) {
     const size_t lds = sizeof(AttnMfmaLds<DH>);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_attn_mfma<DH>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void *)k_attn_mfma<DH, F16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
     int grid = a.Hkv * a.S;
     if (grid > 8 * c.n_wg) grid = 8 * c.n_wg;
-    hipLaunchKernelGGL((k_attn_mfma<DH>), dim3(grid), dim3(kAttnThreads), lds, (hipStream_t)c.stream, a);
+    hipLaunchKernelGGL((k_attn_mfma<DH, F16>), dim3(grid), dim3(kAttnThreads), lds, (hipStream_t)c.stream, a);
     return (int)hipGetLastError();
 }
 
 int launch_attn(const AttnArgs &a, const LaunchCtx &c) {
     int rc;
-    if (a.kv_is_bf16) {
-        if (a.dh == 128) rc = launch_mfma<128>(a, c);
-        else if (a.dh == 64) rc = launch_mfma<64>(a, c);
+    if (a.kv_elem == kElemBF16) {
+        if (a.dh == 128) rc = launch_mfma<128, false>(a, c);
+        else if (a.dh == 64) rc = launch_mfma<64, false>(a, c);
+        else return (int)hipErrorInvalidValue;
+    } else if (a.kv_elem == kElemF16) {
+        if (a.dh == 128) rc = launch_mfma<128, true>(a, c);
+        else if (a.dh == 64) rc = launch_mfma<64, true>(a, c);
         else return (int)hipErrorInvalidValue;
     } else {
         if (a.dh == 128) rc = launch_valu<float, 128>(a, c);

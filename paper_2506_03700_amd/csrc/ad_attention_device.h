@@ -72,7 +72,8 @@ __device__ __forceinline__ void attn_load_kv(const AttnArgs &a, int item, AttnKv
 
 // `kv`: register block for the cached K/V; if `preloaded`, it already holds (or has in flight) the block of the
 // first item, wg.
-template <int DH, int NTHREADS, class Io>
+// F16: the cache, and the 16-bit halves of the queries and probabilities, are fp16 (else bf16).
+template <int DH, int NTHREADS, class Io, bool F16>
 __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<DH> &L, int wg, int nwg, AttnKv<DH> &kv, bool preloaded) {
     constexpr int KS = DH / 32, DT = DH / 16, half = DH / 2, PR = DH + 2, PL = DH + 4;
     constexpr int NRH = NTHREADS / 256;      // wavefronts per key block
@@ -99,8 +100,8 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
                 const float *vp = kp + (size_t)a.Hkv * DH;
                 const float c = a.rope[(t * half + i) * 2], sn = a.rope[(t * half + i) * 2 + 1];
                 const float x = Io::ld(kp + i), y = Io::ld(kp + i + half);
-                const uint16_t k0 = f32_to_bf16_bits(x * c - y * sn), k1 = f32_to_bf16_bits(x * sn + y * c);
-                const uint16_t v0 = f32_to_bf16_bits(Io::ld(vp + i)), v1 = f32_to_bf16_bits(Io::ld(vp + i + half));
+                const uint16_t k0 = f32_to_16<F16>(x * c - y * sn), k1 = f32_to_16<F16>(x * sn + y * c);
+                const uint16_t v0 = f32_to_16<F16>(Io::ld(vp + i)), v1 = f32_to_16<F16>(Io::ld(vp + i + half));
                 L.knew[t * DH + i] = k0;
                 L.knew[t * DH + i + half] = k1;
                 L.vnew[t * DH + i] = v0;
@@ -147,11 +148,11 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
                     const int b = rr >> 3, col = rr & 7;
                     uint16_t hi, lo;
                     int d = i;
-                    split_hi_lo(q0, hi, lo);
+                    split_hi_lo<F16>(q0, hi, lo);
                     qb16[(((b * KS + (d >> 5)) * 64) + ((d & 31) >> 3) * 16 + col) * 8 + (d & 7)] = hi;
                     qb16[(((b * KS + (d >> 5)) * 64) + ((d & 31) >> 3) * 16 + col + 8) * 8 + (d & 7)] = lo;
                     d = i + half;
-                    split_hi_lo(q1, hi, lo);
+                    split_hi_lo<F16>(q1, hi, lo);
                     qb16[(((b * KS + (d >> 5)) * 64) + ((d & 31) >> 3) * 16 + col) * 8 + (d & 7)] = hi;
                     qb16[(((b * KS + (d >> 5)) * 64) + ((d & 31) >> 3) * 16 + col + 8) * 8 + (d & 7)] = lo;
                 }
@@ -196,13 +197,16 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
                         vreg[dt] = cv.v;
                     }
                 }
+                // Half precision has a narrow exponent range: probabilities below 2^-14 of their block's maximum would
+                // be subnormal.  They enter the MFMA scaled by 2^10 (exact), and the products are scaled back.
+                constexpr float kPScale = F16 ? 1024.0f : 1.0f;
                 for (int b = rh; b < nblk; b += NRH) {
                     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int j = 0; j < KS; ++j) {
                         const bf16x8 q = L.qb[(b * KS + j) * 64 + lane];
-                        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[0][j], q, s0, 0, 0, 0);
-                        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[1][j], q, s1, 0, 0, 0);
+                        s0 = mma16<F16>(kreg[0][j], q, s0);
+                        s1 = mma16<F16>(kreg[1][j], q, s1);
                     }
                     // lane (n, gq) now holds, for query row b*8 + (n & 7), the keys gq*8 + 0..3 (s0) and
                     // gq*8 + 4..7 (s1) of the block: hi part in columns 0..7, lo part in columns 8..15
@@ -230,7 +234,7 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
                         const float p = (sc[c] == -INFINITY) ? 0.f : __expf(sc[c] - mx);
                         sum += p;
                         uint16_t hi, lo;
-                        split_hi_lo(p, hi, lo);
+                        split_hi_lo<F16>(p * kPScale, hi, lo);
                         pb.u[c] = (n < 8) ? hi : lo;
                     }
                     sum += __shfl_xor(sum, 16);
@@ -240,12 +244,12 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
                         o[dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-                        o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vreg[dt], pb.v, o[dt], 0, 0, 0);
+                        o[dt] = mma16<F16>(vreg[dt], pb.v, o[dt]);
                     }
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) o[dt][c] = add_lane_xor8(o[dt][c]);
+                        for (int c = 0; c < 4; ++c) o[dt][c] = add_lane_xor8(o[dt][c]) * (1.0f / kPScale);
                         if (n < 8 && rr < nr) *(f32x4 *)(prow + dt * 16 + gq * 4) = o[dt];
                     }
                     if (n < 8 && gq == 0 && rr < nr) {
@@ -307,7 +311,7 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
 // One wavefront per query row: the splits' (max, sum) pairs give the weights exp(max_s - M), then the lanes
 // accumulate the weighted partial outputs in split order, two dimensions per lane, 32 splits' rows in flight at a
 // time (at most 64 splits, i.e. one round trip to memory, for contexts up to 8192).
-template <class Io>
+template <class Io, bool F16>
 __device__ __forceinline__ void attn_combine_row(const AttnArgs &a, int row /* 0 .. Hkv * R */) {
     constexpr int NB = 32;                             // splits whose rows are in flight together
     const int DH = a.dh, PR = DH + 2, S = a.S;
@@ -360,8 +364,8 @@ __device__ __forceinline__ void attn_combine_row(const AttnArgs &a, int row /* 0
         }
     }
     if (e_on) {
-        store_act_io<Io>((uint16_t *)a.Bo, a.Bo_KT, hq * DH + e, t, o0 / den);
-        store_act_io<Io>((uint16_t *)a.Bo, a.Bo_KT, hq * DH + e + 1, t, o1 / den);
+        store_act_io<Io, F16>((uint16_t *)a.Bo, a.Bo_KT, hq * DH + e, t, o0 / den);
+        store_act_io<Io, F16>((uint16_t *)a.Bo, a.Bo_KT, hq * DH + e + 1, t, o1 / den);
     }
 }
 

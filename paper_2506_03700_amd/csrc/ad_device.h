@@ -6,7 +6,8 @@
 
 namespace ad {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;   // also carries 8 fp16 values (see mma16)
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
@@ -23,26 +24,62 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
     return (uint16_t)(u >> 16);
 }
 
+// IEEE half precision <-> fp32 (the conversion instruction rounds to nearest even)
+__device__ __forceinline__ float f16_bits_to_f32(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float x) { return __builtin_bit_cast(uint16_t, (_Float16)x); }
+
+// Element kinds of stored tensors (weights, norm vectors, embedding table, KV cache).  16-bit activations use
+// the same type as the weights they meet in an MFMA: bf16 for fp32 and bf16 models, fp16 for fp16 models.
+enum ElemKind : int { ELEM_F32 = 0, ELEM_BF16 = 1, ELEM_F16 = 2 };
+
+// x = hi + lo with hi, lo in the 16-bit type (F16: half precision, else bf16)
+template <bool F16>
 __device__ __forceinline__ void split_hi_lo(float x, uint16_t &hi, uint16_t &lo) {
-    hi = f32_to_bf16_bits(x);
-    lo = f32_to_bf16_bits(x - bf16_bits_to_f32(hi));
+    if constexpr (F16) {
+        hi = f32_to_f16_bits(x);
+        lo = f32_to_f16_bits(x - f16_bits_to_f32(hi));
+    } else {
+        hi = f32_to_bf16_bits(x);
+        lo = f32_to_bf16_bits(x - bf16_bits_to_f32(hi));
+    }
 }
 
-__device__ __forceinline__ float load_w(const void *p, int is_bf16, size_t i) {
-    return is_bf16 ? bf16_bits_to_f32(((const uint16_t *)p)[i]) : ((const float *)p)[i];
+template <bool F16>
+__device__ __forceinline__ uint16_t f32_to_16(float x) { return F16 ? f32_to_f16_bits(x) : f32_to_bf16_bits(x); }
+
+// D += A (16 rows x 32) * B (32 x 16 columns), 16-bit operands of the model's type, fp32 accumulation
+template <bool F16>
+__device__ __forceinline__ f32x4 mma16(const bf16x8 &a, const bf16x8 &b, const f32x4 &c) {
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float load_w(const void *p, int elem, size_t i) {
+    if (elem == ELEM_F32) return ((const float *)p)[i];
+    const uint16_t b = ((const uint16_t *)p)[i];
+    return elem == ELEM_BF16 ? bf16_bits_to_f32(b) : f16_bits_to_f32(b);
 }
 
 // eight consecutive weights starting at element k (k a multiple of 8); a null vector means all ones
-__device__ __forceinline__ void load_w8(const void *p, int is_bf16, size_t k, float (&w)[8]) {
+__device__ __forceinline__ void load_w8(const void *p, int elem, size_t k, float (&w)[8]) {
     if (!p) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) w[e] = 1.0f;
-    } else if (is_bf16) {
+    } else if (elem == ELEM_BF16) {
         const u32x4 v = *(const u32x4 *)((const uint16_t *)p + k);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             w[2 * e] = __uint_as_float(v[e] << 16);
             w[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
+        }
+    } else if (elem == ELEM_F16) {
+        const u32x4 v = *(const u32x4 *)((const uint16_t *)p + k);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            w[2 * e] = f16_bits_to_f32((uint16_t)(v[e] & 0xffffu));
+            w[2 * e + 1] = f16_bits_to_f32((uint16_t)(v[e] >> 16));
         }
     } else {
         const f32x4 v0 = *(const f32x4 *)((const float *)p + k), v1 = *(const f32x4 *)((const float *)p + k + 4);

@@ -11,7 +11,7 @@
 namespace ad {
 
 // NCHMAX (stationary mode): chunks of k-steps per tile and wavefront that the B registers cover
-template <int NPL, int MODE, int NCHMAX>
+template <int NPL, int MODE, int NCHMAX, bool F16>
 __global__ void __launch_bounds__(MODE == GEMM_STATIONARY ? kStatThreads : kThreads) k_gemm(GemmArgs g) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     GemmLds &L = *reinterpret_cast<GemmLds *>(lds_raw);
@@ -20,13 +20,13 @@ __global__ void __launch_bounds__(MODE == GEMM_STATIONARY ? kStatThreads : kThre
         StatStream<NPL, CH> S;
         S.init(g, blockIdx.x, gridDim.x);
         S.prefetch();
-        gemm_stationary<NPL, CH, NCHMAX, IoPlain, -1>(g, S, L, NoTail());
+        gemm_stationary<NPL, CH, NCHMAX, IoPlain, -1, F16>(g, S, L, NoTail());
     } else {
         constexpr int U = NPL == 1 ? 4 : 2;
         StreamStream<NPL, U, kWaves> S;
         S.init(g, blockIdx.x, gridDim.x);
         S.prefetch(g);
-        gemm_streamed<NPL, U, kWaves, IoPlain, -1, false>(g, S, L, NoTail());
+        gemm_streamed<NPL, U, kWaves, IoPlain, -1, false, F16>(g, S, L, NoTail());
     }
 }
 
@@ -67,15 +67,15 @@ __global__ void __launch_bounds__(512) k_head_combine(GemmArgs g) {
     }
 }
 
-template <int NPL, int MODE, int NCHMAX>
+template <int NPL, int MODE, int NCHMAX, bool F16 = false>
 static int launch_one(const GemmArgs &g, int grid, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_gemm<NPL, MODE, NCHMAX>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(GemmLds));
+        hipError_t e = hipFuncSetAttribute((const void *)k_gemm<NPL, MODE, NCHMAX, F16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(GemmLds));
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_gemm<NPL, MODE, NCHMAX>), dim3(grid), dim3(MODE == GEMM_STATIONARY ? kStatThreads : kThreads), sizeof(GemmLds), s, g);
+    hipLaunchKernelGGL((k_gemm<NPL, MODE, NCHMAX, F16>), dim3(grid), dim3(MODE == GEMM_STATIONARY ? kStatThreads : kThreads), sizeof(GemmLds), s, g);
     return (int)hipGetLastError();
 }
 
@@ -85,14 +85,18 @@ int launch_gemm(const GemmArgs &g, int planes, const LaunchCtx &c) {
     int grid = (g.NT + per - 1) / (per < 1 ? 1 : per);
     if (grid < 1) grid = 1;
     hipStream_t s = (hipStream_t)c.stream;
+    const bool f16 = g.elem == kElemF16;
+    if ((planes == 1) != (g.elem != kElemF32)) return (int)hipErrorInvalidValue;     // fp32 weights are three bf16 planes
     int rc;
     if (g.mode == GEMM_STATIONARY) {
         if ((g.KT + kStatWaves - 1) / kStatWaves > kKsMax || g.K < 8) return (int)hipErrorInvalidValue;
         const int nks = (g.KT + kStatWaves - 1) / kStatWaves;     // most k-steps of a wavefront
-        if (planes == 1) rc = nks <= 16 ? launch_one<1, GEMM_STATIONARY, 2>(g, grid, s) : launch_one<1, GEMM_STATIONARY, 3>(g, grid, s);
-        else rc = launch_one<3, GEMM_STATIONARY, kKsMax / 2>(g, grid, s);
+        if (planes != 1) rc = launch_one<3, GEMM_STATIONARY, kKsMax / 2>(g, grid, s);
+        else if (f16) rc = nks <= 16 ? launch_one<1, GEMM_STATIONARY, 2, true>(g, grid, s) : launch_one<1, GEMM_STATIONARY, 3, true>(g, grid, s);
+        else rc = nks <= 16 ? launch_one<1, GEMM_STATIONARY, 2>(g, grid, s) : launch_one<1, GEMM_STATIONARY, 3>(g, grid, s);
     } else {
-        rc = planes == 1 ? launch_one<1, GEMM_STREAMED, 0>(g, grid, s) : launch_one<3, GEMM_STREAMED, 0>(g, grid, s);
+        if (planes != 1) rc = launch_one<3, GEMM_STREAMED, 0>(g, grid, s);
+        else rc = f16 ? launch_one<1, GEMM_STREAMED, 0, true>(g, grid, s) : launch_one<1, GEMM_STREAMED, 0>(g, grid, s);
     }
     if (rc) return rc;
     if (g.epi == EPI_HEAD) {

@@ -94,10 +94,10 @@ struct IoAcquired : IoAgent {
     static __device__ __forceinline__ bf16x8 ldb(const bf16x8 *p) { return *p; }
 };
 
-template <class Io>
+template <class Io, bool F16>
 __device__ __forceinline__ void store_act_io(uint16_t *B, int KT, int k, int t, float v) {
     uint16_t hi, lo;
-    split_hi_lo(v, hi, lo);
+    split_hi_lo<F16>(v, hi, lo);
     Io::st16(B + act_index(k, t, KT), hi);
     Io::st16(B + act_index(k, 8 + t, KT), lo);
 }
@@ -119,7 +119,7 @@ __device__ __forceinline__ void lse_merge(float &M, float &S, int &I, float m2, 
 
 // ---- epilogue on a reduced round: L.red[T*128 + t*16 + i] holds row (ta+T)*16+i of token t -------------
 // EPI: the epilogue kind when it is known at compile time, or -1 to take g.epi.
-template <class Io, int EPI = -1>
+template <class Io, int EPI, bool F16>
 __device__ __forceinline__ void epilogue(const GemmArgs &g, GemmLds &L, int ta, int nt, int tid, int lane, int wave, int nthreads) {
     const int epi = EPI >= 0 ? EPI : g.epi;
     if (epi == EPI_STORE) {
@@ -137,13 +137,13 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, GemmLds &L, int ta, 
             const int T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15, f = (ta + T) * 8 + i;
             if (t < g.m && i < 8 && f * 2 < g.N) {
                 const float gate = L.scale[t] * L.red[idx], up = L.scale[t] * L.red[idx + 8];
-                store_act_io<Io>((uint16_t *)g.Bnext, g.Bnext_KT, f, t, gate / (1.0f + __expf(-gate)) * up);
+                store_act_io<Io, F16>((uint16_t *)g.Bnext, g.Bnext_KT, f, t, gate / (1.0f + __expf(-gate)) * up);
             }
         }
     } else if (epi == EPI_PACK) {
         for (int idx = tid; idx < nt * 128; idx += nthreads) {
             const int T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15, n = (ta + T) * 16 + i;
-            if (t < g.m && n < g.N) store_act_io<Io>((uint16_t *)g.Bnext, g.Bnext_KT, n, t, L.scale[t] * L.red[idx]);
+            if (t < g.m && n < g.N) store_act_io<Io, F16>((uint16_t *)g.Bnext, g.Bnext_KT, n, t, L.scale[t] * L.red[idx]);
         }
     } else {  // EPI_HEAD: running (max, sum of exp, argmax) per token over this workgroup's rows
         if (g.logits) {
@@ -242,7 +242,8 @@ struct StatStream {
 
 // `tail` runs once, after the workgroup's last MFMA and before its last reduction and epilogue.
 // NCHMAX: most chunks per tile and wavefront this instance covers (the B slice takes NCHMAX * CH registers x 4).
-template <int NPL, int CH, int NCHMAX, class Io, int EPI, class Tail>
+// F16: the weights and the 16-bit halves of the activations are fp16 (else bf16).
+template <int NPL, int CH, int NCHMAX, class Io, int EPI, bool F16, class Tail>
 __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NPL, CH> &S, GemmLds &L, Tail tail) {
     constexpr int KSB = NCHMAX * CH;   // B registers cover whole chunks
     constexpr int kWaves = kStatWaves, kThreads = kStatThreads;         // this mode's workgroup shape
@@ -278,7 +279,7 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
             const int kc = (k > g.K - 4) ? g.K - 4 : k;              // clamped address, masked result
             if (p * 8 < nks) {
                 float w8[8];
-                load_w8(g.norm_w, g.norm_is_bf16, (size_t)(kc & ~7), w8);
+                load_w8(g.norm_w, g.norm_elem, (size_t)(kc & ~7), w8);
                 const int o = kc & 4;
                 wp = (f32x4){w8[o], w8[o + 1], w8[o + 2], w8[o + 3]};
 #pragma unroll
@@ -307,7 +308,7 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
                         for (int e = 0; e < 4; ++e) {
                             const float xv = k_on ? xp[t][e] : 0.f;
                             ssq[t] += xv * xv;
-                            split_hi_lo(xv * wp[e], hi.u[e], lo.u[e]);
+                            split_hi_lo<F16>(xv * wp[e], hi.u[e], lo.u[e]);
                         }
                         *(uint64_t *)(strip16 + sw(u0 + t) * 8 + (lane & 1) * 4) = hi.v;
                         *(uint64_t *)(strip16 + sw(u0 + 8 + t) * 8 + (lane & 1) * 4) = lo.v;
@@ -378,7 +379,7 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
             L.red[idx] = v;
         }
         __syncthreads();
-        epilogue<Io, EPI>(g, L, ta, nt, tid, lane, wave, kThreads);
+        epilogue<Io, EPI, F16>(g, L, ta, nt, tid, lane, wave, kThreads);
         __syncthreads();
     };
 
@@ -393,7 +394,7 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
                 for (int j = 0; j < CH; ++j)
                     if (j < len) {
 #pragma unroll
-                        for (int pl = 0; pl < NPL; ++pl) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j][pl], b[q * CH + j], acc, 0, 0, 0);
+                        for (int pl = 0; pl < NPL; ++pl) acc = mma16<F16>(a[j][pl], b[q * CH + j], acc);
                     }
             }
         }
@@ -492,7 +493,7 @@ struct StreamStream {
 
 // ONE_ROUND: the caller guarantees at most 8 row tiles per workgroup (then there is no loop over rounds, and the
 // tail runs with the stream's buffers dead).
-template <int NPL, int U, int NW, class Io, int EPI, bool ONE_ROUND, class Tail>
+template <int NPL, int U, int NW, class Io, int EPI, bool ONE_ROUND, bool F16, class Tail>
 __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NPL, U, NW> &S, GemmLds &L, Tail tail) {
     constexpr int NTHREADS = NW * 64;
     constexpr int RP = (kTilesPerRound * 128 + NTHREADS - 1) / NTHREADS;   // residual entries per thread and round
@@ -527,7 +528,7 @@ __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NP
             for (int j = 0; j < U; ++j)
                 if (x + j < xb) {
 #pragma unroll
-                    for (int q = 0; q < NPL; ++q) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j][q], b[j], acc, 0, 0, 0);
+                    for (int q = 0; q < NPL; ++q) acc = mma16<F16>(a[j][q], b[j], acc);
                     if (++ks == KT) {
                         *(f32x4 *)(L.slots + (wave + tile) * 256 + (lane & 15) * 16 + (lane >> 4) * 4) = acc;
                         acc = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -603,7 +604,7 @@ __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NP
                 if (g.Bnext) {
                     // input of the next GEMM: y * norm weight, packed; and this tile's share of sum(y^2) per token
                     // (the 16 outputs of a (tile, token) pair sit in 16 neighbouring lanes)
-                    if (on) store_act_io<Io>((uint16_t *)g.Bnext, g.Bnext_KT, n, t, y * load_w(g.next_norm_w, g.next_norm_is_bf16, (size_t)n));
+                    if (on) store_act_io<Io, F16>((uint16_t *)g.Bnext, g.Bnext_KT, n, t, y * load_w(g.next_norm_w, g.next_norm_elem, (size_t)n));
                     float q = y * y;
                     q += __shfl_xor(q, 8);
                     q += __shfl_xor(q, 4);
@@ -613,7 +614,7 @@ __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NP
                 }
             }
         } else {
-            epilogue<Io, EPI>(g, L, ta, nt, tid, lane, wave, NTHREADS);
+            epilogue<Io, EPI, F16>(g, L, ta, nt, tid, lane, wave, NTHREADS);
         }
         __syncthreads();
     }

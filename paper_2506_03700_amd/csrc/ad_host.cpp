@@ -52,6 +52,10 @@ struct Layout {
     size_t total;
 };
 
+// The public dtype codes and the kernels' element kinds are the same numbers.
+static_assert(AD_F32 == kElemF32 && AD_BF16 == kElemBF16 && AD_F16 == kElemF16, "dtype codes");
+static inline int elem_kind(const ad_config &c) { return c.dtype; }
+
 bool config_ok(const ad_config *c, const char **why) {
     *why = "";
     if (!c) { *why = "null config"; return false; }
@@ -60,7 +64,7 @@ bool config_ok(const ad_config *c, const char **why) {
     if (c->d_ffn % 8) { *why = "d_ffn must be a multiple of 8"; return false; }
     if (c->head_dim != 64 && c->head_dim != 128) { *why = "head_dim must be 64 or 128"; return false; }
     if (c->n_q_heads % c->n_kv_heads) { *why = "n_q_heads must be a multiple of n_kv_heads"; return false; }
-    if (c->dtype != AD_F32 && c->dtype != AD_BF16) { *why = "unknown dtype"; return false; }
+    if (c->dtype != AD_F32 && c->dtype != AD_BF16 && c->dtype != AD_F16) { *why = "unknown dtype"; return false; }
     if (c->m_max < 1 || c->m_max > AD_M_MAX) { *why = "m_max must be in 1..8"; return false; }
     if (c->n_exit < 0 || c->n_exit > AD_MAX_EXIT) { *why = "n_exit out of range"; return false; }
     for (int i = 0; i < c->n_exit; ++i) {
@@ -68,13 +72,13 @@ bool config_ok(const ad_config *c, const char **why) {
         if (i && c->exit_layers[i] <= c->exit_layers[i - 1]) { *why = "exit layers must ascend"; return false; }
     }
     if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) { *why = "bad rope_base / rms_eps"; return false; }
-    if (c->d_model > gemm_max_stationary_k(c->dtype == AD_BF16 ? 1 : 3)) { *why = "d_model above 5120 is not supported"; return false; }
+    if (c->d_model > gemm_max_stationary_k(c->dtype == AD_F32 ? 3 : 1)) { *why = "d_model above 5120 is not supported"; return false; }
     return true;
 }
 
 void make_layout(const ad_config &c, Layout &L) {
-    L.elem = c.dtype == AD_BF16 ? 2 : 4;
-    L.planes = c.dtype == AD_BF16 ? 1 : 3;
+    L.elem = c.dtype == AD_F32 ? 4 : 2;
+    L.planes = c.dtype == AD_F32 ? 3 : 1;
     L.d = c.d_model; L.dh = c.head_dim; L.dq = c.n_q_heads * c.head_dim; L.dkv = c.n_kv_heads * c.head_dim;
     L.nqkv = L.dq + 2 * L.dkv; L.f = c.d_ffn; L.V = c.vocab;
     L.kt_d = (L.d + 31) / 32; L.kt_q = (L.dq + 31) / 32; L.kt_f = (L.f + 31) / 32;
@@ -194,7 +198,7 @@ ad_status ad_model_create(const ad_config *cfg, const ad_layer_weights *layers, 
     if (rc) { delete m; return (ad_status)hip_fail(rc, "device query"); }
     m->n_wg = n_cu;
     m->ws = (char *)workspace;
-    const int bf = cfg->dtype == AD_BF16;
+    const int bf = elem_kind(*cfg);
     const size_t tile_kb = (size_t)L.planes * 1024u;
 
 #define AD_TRY(expr, what) do { int rc_ = (expr); if (rc_) { delete m; return (ad_status)hip_fail(rc_, what); } } while (0)
@@ -277,7 +281,7 @@ static size_t rope_table_bytes(const ad_config &c, int32_t max_pos) {
 }
 
 static size_t attn_part_bytes(const ad_config &c, int32_t max_pos) {
-    const int C = attn_chunk(c.dtype == AD_BF16, c.head_dim);
+    const int C = attn_chunk(elem_kind(c), c.head_dim);
     const size_t S = (size_t)(max_pos + C - 1) / C + 1;
     return align_up((size_t)c.n_q_heads * 8 * S * (c.head_dim + 2) * 4);
 }
@@ -285,7 +289,7 @@ static size_t attn_part_bytes(const ad_config &c, int32_t max_pos) {
 size_t ad_kv_bytes(const ad_config *cfg, int32_t max_pos) {
     const char *why;
     if (!config_ok(cfg, &why) || max_pos < 1) { fail(AD_EINVAL, "ad_kv_bytes: %s", max_pos < 1 ? "max_pos < 1" : why); return 0; }
-    const size_t elem = cfg->dtype == AD_BF16 ? 2 : 4;
+    const size_t elem = cfg->dtype == AD_F32 ? 4 : 2;
     const size_t stride = ((size_t)max_pos + 63) / 64 * 64;
     const size_t cache = (size_t)cfg->n_layers * 2 * cfg->n_kv_heads * stride * cfg->head_dim * elem;
     return align_up(cache) + attn_part_bytes(*cfg, max_pos) + rope_table_bytes(*cfg, max_pos);
@@ -299,7 +303,7 @@ ad_status ad_kv_create(const ad_model *model, void *kv_storage, size_t kv_storag
     ad_kv *kv = new (std::nothrow) ad_kv();
     if (!kv) return (ad_status)fail(AD_ENOMEM, "ad_kv_create: out of host memory");
     const ad_config &c = model->cfg;
-    const size_t elem = c.dtype == AD_BF16 ? 2 : 4;
+    const size_t elem = c.dtype == AD_F32 ? 4 : 2;
     kv->model = model;
     kv->storage = (char *)kv_storage;
     kv->stride = (max_pos + 63) / 64 * 64;
@@ -376,7 +380,7 @@ ad_status ad_embed(const ad_model *m, const int32_t *tokens, int32_t n, void *hi
     if (!m || !tokens || !hidden) return (ad_status)fail(AD_EINVAL, "ad_embed: null argument");
     if (n < 1 || n > m->cfg.m_max) return (ad_status)fail(AD_ERANGE, "ad_embed: m = %d outside 1..%d", n, m->cfg.m_max);
     EmbedArgs a;
-    a.table = m->embed; a.is_bf16 = m->cfg.dtype == AD_BF16; a.d = m->cfg.d_model; a.m = n; a.out = (float *)hidden;
+    a.table = m->embed; a.elem = elem_kind(m->cfg); a.d = m->cfg.d_model; a.m = n; a.out = (float *)hidden;
     for (int i = 0; i < n; ++i) {
         if (tokens[i] < 0 || tokens[i] >= m->cfg.vocab) return (ad_status)fail(AD_ERANGE, "ad_embed: token %d outside the vocabulary", tokens[i]);
         a.tok[i] = tokens[i];
@@ -399,7 +403,7 @@ static int fused_health(const ad_model *m, void *stream) {
 }
 
 static int64_t layer_step_bytes(const ad_config &c, int32_t ctx, int32_t m) {
-    const int64_t s = c.dtype == AD_BF16 ? 2 : 4;
+    const int64_t s = c.dtype == AD_F32 ? 4 : 2;
     const int64_t dq = (int64_t)c.n_q_heads * c.head_dim, dkv = (int64_t)c.n_kv_heads * c.head_dim, d = c.d_model, f = c.d_ffn;
     const int64_t w = ((dq + 2 * dkv) * d + d * dq + 3 * d * f) * s;
     return w + 2 * dkv * s * ((int64_t)ctx + m) + 2 * dkv * s * m;
@@ -420,13 +424,14 @@ ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidde
     const Layout &L = m->lay;
     const LayerPacked &lp = m->layers[layer - 1];
     const LaunchCtx ctx{stream, m->n_wg};
-    const int bf = c.dtype == AD_BF16;
+    const int bf = elem_kind(c);
     int rc;
     // 1. q, k, v = W (RMSNorm(x)): the norm is fused into the GEMM (B operand built from x in its prologue)
     GemmArgs gq;
     memset(&gq, 0, sizeof gq);
+    gq.elem = bf;
     gq.W = lp.wqkv; gq.NT = L.nqkv / 16; gq.KT = L.kt_d; gq.N = L.nqkv; gq.K = L.d; gq.m = n; gq.mode = GEMM_STATIONARY;
-    gq.x = (const float *)hidden; gq.ldx = L.d; gq.norm_w = lp.attn_norm; gq.norm_is_bf16 = bf; gq.inv_dim = 1.0f / (float)L.d; gq.eps = c.rms_eps;
+    gq.x = (const float *)hidden; gq.ldx = L.d; gq.norm_w = lp.attn_norm; gq.norm_elem = bf; gq.inv_dim = 1.0f / (float)L.d; gq.eps = c.rms_eps;
     gq.epi = EPI_STORE; gq.out = m->qkv; gq.ld = L.nqkv;
     // 2. rotary embedding, KV append, attention (partials + combine)
     AttnArgs a;
@@ -436,23 +441,26 @@ ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidde
     a.stride = kv->stride; a.pos0 = pos[0]; a.m = n; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = L.dh;
     a.C = attn_chunk(bf, L.dh);
     a.S = pos[0] > 0 ? (pos[0] + a.C - 1) / a.C : 1;
-    a.part = kv->part; a.Bo = m->Bo; a.Bo_KT = L.kt_q; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_is_bf16 = bf;
+    a.part = kv->part; a.Bo = m->Bo; a.Bo_KT = L.kt_q; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_elem = bf;
     // 3. x' = x + Wo o
     GemmArgs go;
     memset(&go, 0, sizeof go);
+    go.elem = bf;
     go.W = lp.wo; go.B = m->Bo; go.NT = L.d / 16; go.KT = L.kt_q; go.N = L.d; go.K = L.dq; go.m = n; go.mode = GEMM_STREAMED;
     go.epi = EPI_RESID; go.resid = (const float *)hidden; go.out = m->x1; go.ld = L.d;
     // ... and the Wo epilogue already prepares the gate/up GEMM's input: x' * ffn norm weight packed, sum(x'^2) per tile
-    go.Bnext = m->Bx; go.Bnext_KT = L.kt_d; go.next_norm_w = lp.ffn_norm; go.next_norm_is_bf16 = bf; go.ssq_out = m->ssq;
+    go.Bnext = m->Bx; go.Bnext_KT = L.kt_d; go.next_norm_w = lp.ffn_norm; go.next_norm_elem = bf; go.ssq_out = m->ssq;
     // 4. g = silu(Wg b) * (Wu b), b = RMSNorm(x') fused as in step 1
     GemmArgs gg;
     memset(&gg, 0, sizeof gg);
+    gg.elem = bf;
     gg.W = lp.wgu; gg.NT = (2 * L.f) / 16; gg.KT = L.kt_d; gg.N = 2 * L.f; gg.K = L.d; gg.m = n; gg.mode = GEMM_STATIONARY;
     gg.B = m->Bx; gg.ssq_in = m->ssq; gg.ssq_tiles = go.NT; gg.inv_dim = 1.0f / (float)L.d; gg.eps = c.rms_eps;
     gg.epi = EPI_SWIGLU; gg.Bnext = m->Bg; gg.Bnext_KT = L.kt_f;
     // 5. y = x' + Wd g
     GemmArgs gd;
     memset(&gd, 0, sizeof gd);
+    gd.elem = bf;
     gd.W = lp.wd; gd.B = m->Bg; gd.NT = L.d / 16; gd.KT = L.kt_f; gd.N = L.d; gd.K = L.f; gd.m = n; gd.mode = GEMM_STREAMED;
     gd.epi = EPI_RESID; gd.resid = m->x1; gd.out = (float *)hidden; gd.ld = L.d;
 
@@ -493,21 +501,23 @@ static int run_head(const ad_model *m, int32_t layer, const void *hidden, int32_
     }
     const Layout &L = m->lay;
     const LaunchCtx ctx{stream, m->n_wg};
-    const int bf = c.dtype == AD_BF16;
+    const int bf = elem_kind(c);
     int rc;
+    g.elem = bf;
     g.W = m->head; g.NT = (L.V + 15) / 16; g.KT = L.kt_d; g.N = L.V; g.K = L.d; g.m = n; g.mode = GEMM_STATIONARY;
     g.epi = EPI_HEAD; g.head_part = m->head_part;
     if (slot >= 0 && m->T[slot]) {
         // lightweight head of Sec. 2.1: E = E* T, applied as E* (T norm(h))
         GemmArgs t;
         memset(&t, 0, sizeof t);
+        t.elem = bf;
         t.W = m->T[slot]; t.NT = L.d / 16; t.KT = L.kt_d; t.N = L.d; t.K = L.d; t.m = n; t.mode = GEMM_STATIONARY;
-        t.x = (const float *)hidden; t.ldx = L.d; t.norm_w = m->final_norm; t.norm_is_bf16 = bf; t.inv_dim = 1.0f / (float)L.d; t.eps = c.rms_eps;
+        t.x = (const float *)hidden; t.ldx = L.d; t.norm_w = m->final_norm; t.norm_elem = bf; t.inv_dim = 1.0f / (float)L.d; t.eps = c.rms_eps;
         t.epi = EPI_PACK; t.Bnext = m->B1; t.Bnext_KT = L.kt_d;
         if ((rc = gemm(m, t, L.d, L.d, ctx))) return hip_fail(rc, who);
         g.B = m->B1;
     } else {
-        g.x = (const float *)hidden; g.ldx = L.d; g.norm_w = m->final_norm; g.norm_is_bf16 = bf; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
+        g.x = (const float *)hidden; g.ldx = L.d; g.norm_w = m->final_norm; g.norm_elem = bf; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
     }
     if ((rc = gemm(m, g, L.V, L.d, ctx))) return hip_fail(rc, who);
     return AD_OK;
@@ -640,7 +650,7 @@ struct GpuBackend : Backend {
         if ((rc = fused_health(m, stream))) return rc;
         *token = m->pin[0];
         *conf = m->pin_conf[0];
-        const int64_t s = m->cfg.dtype == AD_BF16 ? 2 : 4;
+        const int64_t s = m->cfg.dtype == AD_F32 ? 4 : 2;
         bytes += (int64_t)m->cfg.vocab * m->cfg.d_model * s;
         return AD_OK;
     }
@@ -652,7 +662,7 @@ struct GpuBackend : Backend {
         *n_accept = m->pin[8];
         *next = m->pin[9];
         for (int i = 0; i < n; ++i) row_argmax[i] = m->pin[16 + i];
-        const int64_t s = m->cfg.dtype == AD_BF16 ? 2 : 4;
+        const int64_t s = m->cfg.dtype == AD_F32 ? 4 : 2;
         bytes += (int64_t)m->cfg.vocab * m->cfg.d_model * s;
         return AD_OK;
     }

@@ -6,12 +6,14 @@
 
 namespace ad {
 
+enum : int { kElemF32 = 0, kElemBF16 = 1, kElemF16 = 2 };   // host-side names of ElemKind (ad_device.h)
+
 // ---- packed operand layouts ---------------------------------------------------------------------------
 // Weight matrix W [N, K] -> tiles of 16 output rows x 32 inputs.  Tile (rt, ks) is stored as P planes of
 // 64 lanes x 8 bf16 (1 KiB per plane): lane l holds W[rt*16 + (l & 15)][ks*32 + (l >> 4)*8 .. +8), which
 // is the A operand of one 16x16x32 bf16 MFMA, so that a wavefront loads a whole tile plane with one
 // 128-bit load per lane from 1 KiB of contiguous memory.  Tiles are ordered [rt][ks][plane].
-// bf16 weights have one plane; fp32 weights are split exactly into three bf16 planes (W = p0 + p1 + p2).
+// 16-bit weights (bf16 or fp16) have one plane; fp32 weights are split exactly into three bf16 planes (W = p0 + p1 + p2).
 // Rows >= N and inputs >= K are zero.
 //
 // Activation block [m <= 8 tokens, K]: the MFMA's B operand has 16 columns; columns 0..7 are the tokens' bf16
@@ -40,12 +42,13 @@ struct GemmArgs {
     int N, K;             // valid output rows (EPI_SWIGLU: rows of the interleaved gate/up matrix = 2F), valid inputs
     int m;                // tokens
     int mode;             // GemmMode
+    int elem;             // ElemKind of the weights: fp32 (three bf16 planes), bf16, or fp16 (fp16 MFMA, fp16 hi/lo activations)
     // activations: either fp32 rows x [m][ldx] (stationary mode; multiplied by norm_w and, in the epilogue, by
     // rsqrt(mean(x^2) + eps) when norm_w is given), or a packed block B
     const float *x;
     int ldx;
     const void *norm_w;
-    int norm_is_bf16;
+    int norm_elem;        // ElemKind of norm_w
     float inv_dim, eps;
     const void *B;
     int epi;
@@ -64,7 +67,7 @@ struct GemmArgs {
     // to ssq_out[tile][token].  The consumer (stationary mode, B = that block, ssq_in = those partials, ssq_tiles
     // of them) only has to load its operand registers and add the partials up for the 1/rms factor.
     const void *next_norm_w;
-    int next_norm_is_bf16;
+    int next_norm_elem;
     float *ssq_out;
     const float *ssq_in;
     int ssq_tiles;
@@ -97,7 +100,7 @@ struct AttnArgs {
     void *Bo;             // packed attention output for the Wo GEMM
     int Bo_KT;            // k-steps of that block (n_q_heads * head_dim / 32)
     float scale;
-    int kv_is_bf16;
+    int kv_elem;          // ElemKind of the cache (and of the 16-bit operands of the MFMA kernel)
 };
 
 // One decoder-layer step as a single persistent kernel (bf16 models): the four GEMMs and the attention phase
@@ -116,14 +119,14 @@ constexpr int kBarrierWords = 32 * 9;      // one 128-byte line for the global c
 constexpr int kFusedBarriers = 5;          // barriers per launch
 
 struct EmbedArgs {
-    const void *table; int is_bf16; int d; int m; int32_t tok[8]; float *out;
+    const void *table; int elem; int d; int m; int32_t tok[8]; float *out;
 };
 
 struct LaunchCtx { void *stream; int n_wg; };
 
 // All launchers return 0 or a hipError_t value.
 // mode 0: W [N, K] -> packed.  mode 1: gate (src) and up (src2), each [N, K], interleaved 8 rows at a time.
-int launch_pack_weights(const void *src, const void *src2, int src_is_bf16, int64_t N, int64_t K, int mode, void *dst,
+int launch_pack_weights(const void *src, const void *src2, int src_elem, int64_t N, int64_t K, int mode, void *dst,
                         void *stream);
 int launch_copy(const void *src, void *dst, size_t bytes, void *stream);
 int launch_zero(void *dst, size_t bytes, void *stream);
@@ -134,7 +137,7 @@ int launch_gemm(const GemmArgs &, int planes, const LaunchCtx &);   // EPI_HEAD:
 int launch_attn(const AttnArgs &, const LaunchCtx &);
 int launch_layer_fused(const FusedArgs &, const LaunchCtx &);   // n_wg must not exceed the number of compute units
 int fused_phase_workgroups(int n_tiles, int n_wg);               // workgroups that own row tiles of a GEMM phase
-int attn_chunk(int kv_is_bf16, int dh);   // cached positions per attention work item
+int attn_chunk(int kv_elem, int dh);   // cached positions per attention work item
 int device_info(int *n_cu);
 const char *hip_error_text(int code);
 int stream_sync(void *stream);

@@ -14,7 +14,7 @@ namespace ad {
 // ---------------------------------------------------------------------------------------------------
 // One thread per (tile, lane).  mode 0: dst row r = src row r.  mode 1 (gate/up interleave): tile rt holds
 // gate rows rt*8..+8 in tile rows 0..7 and up rows rt*8..+8 in tile rows 8..15.
-__global__ void k_pack_weights(const void *src, const void *src2, int is_bf16, int64_t N, int64_t K, int64_t NT,
+__global__ void k_pack_weights(const void *src, const void *src2, int elem, int64_t N, int64_t K, int64_t NT,
                                int64_t KT, int mode, uint16_t *dst) {
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= NT * KT * 64) return;
@@ -29,12 +29,12 @@ __global__ void k_pack_weights(const void *src, const void *src2, int is_bf16, i
         row = rt * 8 + (i & 7);
         if (i >= 8) s = src2;
     }
-    const int planes = is_bf16 ? 1 : 3;
+    const int planes = elem != ELEM_F32 ? 1 : 3;
     uint16_t *d = dst + (size_t)tile * planes * 512 + (size_t)lane * 8;
     for (int e = 0; e < 8; ++e) {
         const int64_t k = ks * 32 + g * 8 + e;
         const bool ok = row < N && k < K;
-        if (is_bf16) {
+        if (elem != ELEM_F32) {     // 16-bit elements (bf16 or fp16) are copied as they are
             d[e] = ok ? ((const uint16_t *)s)[row * K + k] : (uint16_t)0;
         } else {
             const float w = ok ? ((const float *)s)[row * K + k] : 0.0f;
@@ -61,7 +61,7 @@ __global__ void k_zero16(u32x4 *dst, size_t n16) {
 __global__ void k_embed(EmbedArgs a) {
     for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < a.m * a.d; idx += gridDim.x * blockDim.x) {
         const int r = idx / a.d, c = idx % a.d;
-        a.out[idx] = load_w(a.table, a.is_bf16, (size_t)a.tok[r] * a.d + c);
+        a.out[idx] = load_w(a.table, a.elem, (size_t)a.tok[r] * a.d + c);
     }
 }
 
@@ -84,12 +84,12 @@ __global__ void k_rope_table(RopeArgs a) {
 // ---------------------------------------------------------------------------------------------------
 static inline hipStream_t S(void *s) { return (hipStream_t)s; }
 
-int launch_pack_weights(const void *src, const void *src2, int src_is_bf16, int64_t N, int64_t K, int mode, void *dst,
+int launch_pack_weights(const void *src, const void *src2, int src_elem, int64_t N, int64_t K, int mode, void *dst,
                         void *stream) {
     const int64_t rows = (mode == 0) ? N : 2 * N;
     const int64_t NT = (rows + 15) / 16, KT = (K + 31) / 32;
     const int64_t threads = NT * KT * 64;
-    hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, S(stream), src, src2, src_is_bf16,
+    hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, S(stream), src, src2, src_elem,
                        N, K, NT, KT, mode, (uint16_t *)dst);
     return (int)hipGetLastError();
 }

@@ -105,19 +105,19 @@ __global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f) {
     s_qkv.prefetch();
     AttnKv<DH> kv;
     auto pre_attn = [&]() { attn_load_kv<DH, kFusedThreads>(f.attn, wg, kv); };   // the cached K/V block of the first item
-    if (wg < f.nwg_qkv) gemm_stationary<1, CH, NCHMAX, IoAgent, EPI_STORE>(f.qkv, s_qkv, L.gemm, NoTail());
+    if (wg < f.nwg_qkv) gemm_stationary<1, CH, NCHMAX, IoAgent, EPI_STORE, false>(f.qkv, s_qkv, L.gemm, NoTail());
     stamp();
     if (!bar.sync(false, pre_attn)) return;
     stamp();
 
     // ---- 2. rotary embedding, KV append, attention partials ------------------------------------------------
-    attn_mfma_items<DH, kFusedThreads, IoAgent>(f.attn, L.attn, wg, nwg, kv, true);
+    attn_mfma_items<DH, kFusedThreads, IoAgent, false>(f.attn, L.attn, wg, nwg, kv, true);
     stamp();
     if (!bar.sync(false, NoTail())) return;
     stamp();
 
     // ---- 3. fold the splits of each query row (one wavefront per row), packed for Wo -------------------------
-    for (int row = wave * nwg + wg; row < f.attn.Hq * f.attn.m; row += NW * nwg) attn_combine_row<IoAgent>(f.attn, row);
+    for (int row = wave * nwg + wg; row < f.attn.Hq * f.attn.m; row += NW * nwg) attn_combine_row<IoAgent, false>(f.attn, row);
     s_wo.init(f.wo, wg, f.nwg_wo);
     auto pre_wo = [&]() { s_wo.prefetch(f.wo); };
     stamp();
@@ -127,7 +127,7 @@ __global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f) {
     // ---- 4. x' = x + Wo o ------------------------------------------------------------------------------------
     s_gu.init(f.gu, wg, f.nwg_gu);
     auto pre_gu = [&]() { s_gu.prefetch(); };
-    if (wg < f.nwg_wo) gemm_streamed<1, U, NW, IoAcquired, EPI_RESID, true>(f.wo, s_wo, L.gemm, NoTail());
+    if (wg < f.nwg_wo) gemm_streamed<1, U, NW, IoAcquired, EPI_RESID, true, false>(f.wo, s_wo, L.gemm, NoTail());
     stamp();
     if (!bar.sync(true, pre_gu)) return;
     stamp();
@@ -135,13 +135,13 @@ __global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f) {
     // ---- 5. g = silu(Wg b) * (Wu b), b = RMSNorm(x') -----------------------------------------------------------
     s_down.init(f.down, wg, f.nwg_down);
     auto pre_down = [&]() { s_down.prefetch(f.down); };
-    if (wg < f.nwg_gu) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_SWIGLU>(f.gu, s_gu, L.gemm, NoTail());
+    if (wg < f.nwg_gu) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_SWIGLU, false>(f.gu, s_gu, L.gemm, NoTail());
     stamp();
     if (!bar.sync(true, pre_down)) return;
     stamp();
 
     // ---- 6. y = x' + Wd g ----------------------------------------------------------------------------------------
-    if (wg < f.nwg_down) gemm_streamed<1, U, NW, IoAcquired, EPI_RESID, true>(f.down, s_down, L.gemm, NoTail());
+    if (wg < f.nwg_down) gemm_streamed<1, U, NW, IoAcquired, EPI_RESID, true, false>(f.down, s_down, L.gemm, NoTail());
     stamp();
 }
 
@@ -168,7 +168,7 @@ int launch_layer_fused(const FusedArgs &f, const LaunchCtx &c) {
     // the streamed phases run a single round of at most 8 row tiles per workgroup
     if (f.wo.NT > 8 * f.nwg_wo || f.down.NT > 8 * f.nwg_down) return (int)hipErrorInvalidValue;
     if ((f.qkv.KT + kStatWaves - 1) / kStatWaves > kKsMax || f.qkv.K < 8) return (int)hipErrorInvalidValue;
-    if (!f.attn.kv_is_bf16 || c.n_wg < 1) return (int)hipErrorInvalidValue;
+    if (f.attn.kv_elem != kElemBF16 || f.qkv.elem != kElemBF16 || c.n_wg < 1) return (int)hipErrorInvalidValue;
     const bool small = (f.qkv.KT + kStatWaves - 1) / kStatWaves <= 16;
     if (f.attn.dh == 128) return small ? launch_fused_dh<128, 2>(f, c) : launch_fused_dh<128, 3>(f, c);
     if (f.attn.dh == 64) return small ? launch_fused_dh<64, 2>(f, c) : launch_fused_dh<64, 3>(f, c);

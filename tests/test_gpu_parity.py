@@ -3,7 +3,8 @@
 Tolerances (stated by the build's target): hidden states and KV entries within max relative error 1e-4
 for fp32 models and 2e-2 for bf16 models, where the relative error of a tensor is max|gpu - oracle| /
 max|oracle|; token ids and exit / verify decisions bit-exact except where the oracle's top-2 logit
-margin is below 1e-2.
+margin is below 1e-2.  fp16 models (11 significant bits against bf16's 8) are held to the 16-bit bound
+divided by 2^3: 2.5e-3.
 """
 import numpy as np
 import pytest
@@ -13,7 +14,7 @@ from paper_2506_03700_amd import synth
 
 pytestmark = pytest.mark.gpu
 
-TOL = {synth.F32: 1e-4, synth.BF16: 2e-2}
+TOL = {synth.F32: 1e-4, synth.BF16: 2e-2, synth.F16: 2.5e-3}
 NEAR_TIE = 1e-2
 
 
@@ -50,7 +51,8 @@ ODD = synth.TINY.with_(name="tiny-odd", n_q_heads=6, n_kv_heads=2, head_dim=64, 
 
 
 @pytest.mark.parametrize("shape,mode", with_modes([synth.TINY, synth.TINY_BF16, synth.TINY_GQA, ODD,
-                                                    ODD.with_(name="tiny-odd-bf16", dtype=synth.BF16)]))
+                                                    ODD.with_(name="tiny-odd-bf16", dtype=synth.BF16), synth.TINY_F16,
+                                                    ODD.with_(name="tiny-odd-f16", dtype=synth.F16)]))
 def test_layer_steps_ragged_small_models(ad, shape, mode):
     import torch
     print(f"case {shape.name} layer mode {mode}", flush=True)
@@ -93,10 +95,14 @@ def test_layer_steps_ragged_small_models(ad, shape, mode):
 
 
 L13 = synth.LLAMA13B.with_(name="13b-layer", n_layers=1, exit_layers=(), vocab=256)
+L8_F16 = synth.LLAMA8B_LAYER.with_(name="8b-layer-f16", dtype=synth.F16)
+L13_F16 = L13.with_(name="13b-layer-f16", dtype=synth.F16)
 
 
-@pytest.mark.parametrize("shape,ctx,mode", [(synth.LLAMA8B_LAYER, 4096, 0), (synth.LLAMA8B_LAYER, 4096, 1), (L13, 1000, 0), (L13, 1000, 1)],
-                         ids=["8b-layer-kernels", "8b-layer-fused", "13b-layer-kernels", "13b-layer-fused"])
+@pytest.mark.parametrize("shape,ctx,mode", [(synth.LLAMA8B_LAYER, 4096, 0), (synth.LLAMA8B_LAYER, 4096, 1), (L13, 1000, 0), (L13, 1000, 1),
+                                            (L8_F16, 4096, 0), (L13_F16, 1000, 0)],
+                         ids=["8b-layer-kernels", "8b-layer-fused", "13b-layer-kernels", "13b-layer-fused",
+                              "8b-layer-f16-kernels", "13b-layer-f16-kernels"])
 def test_layer_step_full_width_shapes(ad, shape, ctx, mode):
     """The single-layer microbenchmark workload: prefilled N(0,1) cache, N(0,1) hidden rows, m in {1,2,3,4,6,8}
     at positions ctx .. ctx+m-1, cache length reset before each call."""
@@ -181,7 +187,8 @@ def compare_runs(shape, g, o, prompt, max_new, gamma, cap, **kw):
     return cmp(g, o, prompt, max_new, gamma, cap, TOL[shape.dtype], **kw)[0]
 
 
-@pytest.mark.parametrize("shape,mode", with_modes([synth.TINY, UNTIED, synth.TINY_GQA, UNTIED.with_(name="tiny-untied-bf16", dtype=synth.BF16)]))
+@pytest.mark.parametrize("shape,mode", with_modes([synth.TINY, UNTIED, synth.TINY_GQA, UNTIED.with_(name="tiny-untied-bf16", dtype=synth.BF16),
+                                                    UNTIED.with_(name="tiny-untied-f16", dtype=synth.F16)]))
 def test_generate_matches_oracle_decisions(ad, shape, mode):
     w = synth.make_weights(shape, seed=0)
     max_pos = 160
@@ -209,7 +216,7 @@ def test_generate_matches_oracle_decisions(ad, shape, mode):
     g.close()
 
 
-@pytest.mark.parametrize("shape,mode", with_modes([synth.MINI8B, synth.MINI13B]))
+@pytest.mark.parametrize("shape,mode", with_modes([synth.MINI8B, synth.MINI13B, synth.MINI8B.with_(name="8b-mini-f16", dtype=synth.F16)]))
 def test_generate_full_width_reduced_depth(ad, shape, mode):
     """8B- and 13B-shaped layers (real d, heads, FFN), 4 layers and a reduced vocabulary so that the oracle
     finishes in seconds; forced schedules exercise ragged catch-up, scripted drafts force rejections."""
