@@ -50,7 +50,7 @@ typedef enum { AD_F32 = 0, AD_BF16 = 1, AD_F16 = 2 } ad_dtype;
 enum { AD_MAX_EXIT = 8, AD_M_MAX = 8 };
 
 typedef struct {
-    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;   /* d_model % 16 == 0 and <= 5120,
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;   /* d_model % 16 == 0 and <= 8192 (fp32: 5120),
                                                                                    head_dim 64 or 128, d_ffn % 8 == 0 */
     float   rope_base, rms_eps;
     int32_t dtype;                       /* ad_dtype: storage of the weights passed in and of the KV cache.  AD_F16 is
@@ -112,7 +112,7 @@ ad_status ad_layer_step(const ad_model *, ad_kv *, int32_t layer, void *hidden, 
                         void *stream);
 
 /* How ad_layer_step runs.  AD_LAYER_KERNELS (the default): one kernel per phase (QKV, attention, fold, Wo,
- * gate/up, down).  AD_LAYER_FUSED (bf16 models only): one persistent kernel with one workgroup per compute unit
+ * gate/up, down).  AD_LAYER_FUSED (bf16 models with d_model <= 5120 only): one persistent kernel with one workgroup per compute unit
  * and grid barriers between the phases; it needs the device to itself while it runs (no other kernel of this
  * process may occupy compute units at the same time, or a barrier wait can time out; the call after such a
  * time-out returns AD_EDEVICE).  Both modes compute the same function; results may differ in the last bits. */

@@ -10,13 +10,15 @@
 
 namespace ad {
 
-// NCHMAX (stationary mode): chunks of k-steps per tile and wavefront that the B registers cover
+// NCHMAX (stationary mode): chunks of k-steps per tile and wavefront that the B registers cover.  Chunks have 8
+// k-steps for 16-bit weights, except in the widest instance (NCHMAX 8), whose 32 B registers leave room for
+// chunks of 4 only; fp32 weights (three planes per k-step) have chunks of 2.
 template <int NPL, int MODE, int NCHMAX, bool F16>
 __global__ void __launch_bounds__(MODE == GEMM_STATIONARY ? kStatThreads : kThreads) k_gemm(GemmArgs g) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     GemmLds &L = *reinterpret_cast<GemmLds *>(lds_raw);
     if constexpr (MODE == GEMM_STATIONARY) {
-        constexpr int CH = NPL == 1 ? 8 : 2;
+        constexpr int CH = NPL == 1 ? (NCHMAX > 3 ? 4 : 8) : 2;
         StatStream<NPL, CH> S;
         S.init(g, blockIdx.x, gridDim.x);
         S.prefetch();
@@ -79,6 +81,14 @@ static int launch_one(const GemmArgs &g, int grid, hipStream_t s) {
     return (int)hipGetLastError();
 }
 
+// 16-bit weights: the instance whose B registers cover the wavefront's K slice (d_model <= 4096, <= 6144, <= 8192)
+template <bool F16>
+static int stationary16(const GemmArgs &g, int nks, int grid, hipStream_t s) {
+    if (nks <= 16) return launch_one<1, GEMM_STATIONARY, 2, F16>(g, grid, s);
+    if (nks <= 24) return launch_one<1, GEMM_STATIONARY, 3, F16>(g, grid, s);
+    return launch_one<1, GEMM_STATIONARY, kKsMaxWide / 4, F16>(g, grid, s);
+}
+
 int launch_gemm(const GemmArgs &g, int planes, const LaunchCtx &c) {
     // equal numbers of row tiles per workgroup: with per = ceil(NT / n_wg) tiles each, ceil(NT / per) workgroups
     const int per = (g.NT + c.n_wg - 1) / c.n_wg;
@@ -89,11 +99,11 @@ int launch_gemm(const GemmArgs &g, int planes, const LaunchCtx &c) {
     if ((planes == 1) != (g.elem != kElemF32)) return (int)hipErrorInvalidValue;     // fp32 weights are three bf16 planes
     int rc;
     if (g.mode == GEMM_STATIONARY) {
-        if ((g.KT + kStatWaves - 1) / kStatWaves > kKsMax || g.K < 8) return (int)hipErrorInvalidValue;
         const int nks = (g.KT + kStatWaves - 1) / kStatWaves;     // most k-steps of a wavefront
+        if (nks > (planes == 1 ? kKsMaxWide : kKsMax) || g.K < 8) return (int)hipErrorInvalidValue;
         if (planes != 1) rc = launch_one<3, GEMM_STATIONARY, kKsMax / 2>(g, grid, s);
-        else if (f16) rc = nks <= 16 ? launch_one<1, GEMM_STATIONARY, 2, true>(g, grid, s) : launch_one<1, GEMM_STATIONARY, 3, true>(g, grid, s);
-        else rc = nks <= 16 ? launch_one<1, GEMM_STATIONARY, 2>(g, grid, s) : launch_one<1, GEMM_STATIONARY, 3>(g, grid, s);
+        else if (f16) rc = stationary16<true>(g, nks, grid, s);
+        else rc = stationary16<false>(g, nks, grid, s);
     } else {
         if (planes != 1) rc = launch_one<3, GEMM_STREAMED, 0>(g, grid, s);
         else rc = f16 ? launch_one<1, GEMM_STREAMED, 0, true>(g, grid, s) : launch_one<1, GEMM_STREAMED, 0>(g, grid, s);
@@ -108,6 +118,6 @@ int launch_gemm(const GemmArgs &g, int planes, const LaunchCtx &c) {
     return rc;
 }
 
-int gemm_max_stationary_k(int) { return kKsMax * kStatWaves * 32; }
+int gemm_max_stationary_k(int planes) { return (planes == 1 ? kKsMaxWide : kKsMax) * kStatWaves * 32; }
 
 }  // namespace ad

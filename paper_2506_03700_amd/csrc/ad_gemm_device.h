@@ -37,7 +37,9 @@ namespace ad {
 constexpr int kTilesPerRound = 8;       // row tiles reduced together
 constexpr int kStatWaves = 8;           // stationary mode: wavefronts per workgroup (512 threads, up to 256 registers each)
 constexpr int kStatThreads = kStatWaves * 64;
-constexpr int kKsMax = 20;              // stationary mode: most k-steps per wavefront (K <= 8 * 20 * 32 = 5120)
+constexpr int kKsMax = 20;              // stationary mode, fp32 weights and the fused layer kernel: most k-steps per
+                                        // wavefront (K <= 8 * 20 * 32 = 5120)
+constexpr int kKsMaxWide = 32;          // stationary mode, 16-bit weights: K <= 8 * 32 * 32 = 8192
 
 struct GemmLds {
     // stationary: [tile 0..8)[wave][token 0..8)[row 0..16)      streamed: [slot][col 0..16)[row 0..16)
@@ -265,7 +267,7 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
     // which are not in use yet.
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     const bool lane_on = t_lane < g.m;
-    constexpr int NPASS = KSB / 8;
+    constexpr int NPASS = (KSB + 7) / 8;
     // 16-byte units of the strip are permuted (unit u -> u ^ ((u >> 4) & 15)) so that the 8-byte writes of a
     // wavefront, which all go to the same operand column, spread over the LDS banks
     uint16_t *strip16 = reinterpret_cast<uint16_t *>(L.slots) + (size_t)wave * 8 * 512;
@@ -317,12 +319,14 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 #pragma unroll
-                for (int jj = 0; jj < 8; ++jj) b[p * 8 + jj] = (lane_on && jj < jn) ? strip[sw(jj * 64 + lane)] : zero;
+                for (int jj = 0; jj < 8; ++jj)
+                    if (p * 8 + jj < KSB) b[p * 8 + jj] = (lane_on && jj < jn) ? strip[sw(jj * 64 + lane)] : zero;
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                 __builtin_amdgcn_wave_barrier();
             } else {
 #pragma unroll
-                for (int jj = 0; jj < 8; ++jj) b[p * 8 + jj] = zero;
+                for (int jj = 0; jj < 8; ++jj)
+                    if (p * 8 + jj < KSB) b[p * 8 + jj] = zero;
             }
         }
         // sum of squares of this K slice, per token, over the 64 lanes (fixed butterfly order)

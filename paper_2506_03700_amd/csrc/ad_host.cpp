@@ -72,7 +72,7 @@ bool config_ok(const ad_config *c, const char **why) {
         if (i && c->exit_layers[i] <= c->exit_layers[i - 1]) { *why = "exit layers must ascend"; return false; }
     }
     if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) { *why = "bad rope_base / rms_eps"; return false; }
-    if (c->d_model > gemm_max_stationary_k(c->dtype == AD_F32 ? 3 : 1)) { *why = "d_model above 5120 is not supported"; return false; }
+    if (c->d_model > gemm_max_stationary_k(c->dtype == AD_F32 ? 3 : 1)) { *why = "d_model above 8192 (fp32 models: 5120) is not supported"; return false; }
     return true;
 }
 
@@ -565,7 +565,8 @@ static void profile_clear(Profile &p) {
 ad_status ad_set_layer_mode(ad_model *m, int32_t mode) {
     if (!m) return (ad_status)fail(AD_EINVAL, "ad_set_layer_mode: null model");
     if (mode != AD_LAYER_KERNELS && mode != AD_LAYER_FUSED) return (ad_status)fail(AD_EINVAL, "ad_set_layer_mode: unknown mode %d", mode);
-    if (mode == AD_LAYER_FUSED && m->cfg.dtype != AD_BF16) return (ad_status)fail(AD_ESTATE, "ad_set_layer_mode: the fused layer step needs a bf16 model");
+    if (mode == AD_LAYER_FUSED && (m->cfg.dtype != AD_BF16 || m->cfg.d_model > 5120))
+        return (ad_status)fail(AD_ESTATE, "ad_set_layer_mode: the fused layer step needs a bf16 model with d_model <= 5120");
     m->layer_mode = mode;
     return AD_OK;
 }

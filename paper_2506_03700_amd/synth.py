@@ -84,8 +84,15 @@ MINI8B = LLAMA8B.with_(name="8b-mini", n_layers=4, exit_layers=(1, 2, 3), vocab=
 MINI13B = LLAMA13B.with_(name="13b-mini", n_layers=4, exit_layers=(1, 2, 3), vocab=4016,
                          prompt_len=24, gen_len=24)
 
-SHAPES = {s.name: s for s in (TINY, LLAMA8B, LLAMA8B_LAYER, LLAMA13B, LLAMA8B_LONG, TINY_BF16,
-                              TINY_GQA, MINI8B, MINI13B)}
+# A d_model = 8192 decoder, the width of the largest LM head the paper lists in Table 4 (32000 x 8192), in
+# the paper's inference precision.  The paper does not print that model's head counts or FFN width: the values
+# here are stand-ins chosen for this workload, not that model's.
+WIDE_LAYER = ModelShape("wide-layer", 1, 8192, 64, 16, 128, 20480, 256, 10000.0, (), F16, False,
+                        prompt_len=16, gen_len=16)
+WIDE_MINI = WIDE_LAYER.with_(name="wide-mini", n_layers=3, exit_layers=(1, 2), vocab=4000)
+
+SHAPES = {s.name: s for s in (TINY, LLAMA8B, LLAMA8B_LAYER, LLAMA13B, LLAMA8B_LONG, TINY_BF16, TINY_F16,
+                              TINY_GQA, MINI8B, MINI13B, WIDE_LAYER, WIDE_MINI)}
 
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:

@@ -97,12 +97,17 @@ def test_layer_steps_ragged_small_models(ad, shape, mode):
 L13 = synth.LLAMA13B.with_(name="13b-layer", n_layers=1, exit_layers=(), vocab=256)
 L8_F16 = synth.LLAMA8B_LAYER.with_(name="8b-layer-f16", dtype=synth.F16)
 L13_F16 = L13.with_(name="13b-layer-f16", dtype=synth.F16)
+L13_F32 = L13.with_(name="13b-layer-f32", dtype=synth.F32)
+WIDE_BF16 = synth.WIDE_LAYER.with_(name="wide-layer-bf16", dtype=synth.BF16)
+D6144 = synth.WIDE_LAYER.with_(name="d6144-layer", d_model=6144, n_q_heads=40, n_kv_heads=8, d_ffn=9992, dtype=synth.BF16)
 
 
 @pytest.mark.parametrize("shape,ctx,mode", [(synth.LLAMA8B_LAYER, 4096, 0), (synth.LLAMA8B_LAYER, 4096, 1), (L13, 1000, 0), (L13, 1000, 1),
-                                            (L8_F16, 4096, 0), (L13_F16, 1000, 0)],
+                                            (L8_F16, 4096, 0), (L13_F16, 1000, 0), (L13_F32, 300, 0),
+                                            (synth.WIDE_LAYER, 2048, 0), (WIDE_BF16, 500, 0), (D6144, 300, 0)],
                          ids=["8b-layer-kernels", "8b-layer-fused", "13b-layer-kernels", "13b-layer-fused",
-                              "8b-layer-f16-kernels", "13b-layer-f16-kernels"])
+                              "8b-layer-f16-kernels", "13b-layer-f16-kernels", "13b-layer-f32-kernels",
+                              "wide-layer-f16-kernels", "wide-layer-bf16-kernels", "d6144-layer-bf16-kernels"])
 def test_layer_step_full_width_shapes(ad, shape, ctx, mode):
     """The single-layer microbenchmark workload: prefilled N(0,1) cache, N(0,1) hidden rows, m in {1,2,3,4,6,8}
     at positions ctx .. ctx+m-1, cache length reset before each call."""
@@ -216,7 +221,8 @@ def test_generate_matches_oracle_decisions(ad, shape, mode):
     g.close()
 
 
-@pytest.mark.parametrize("shape,mode", with_modes([synth.MINI8B, synth.MINI13B, synth.MINI8B.with_(name="8b-mini-f16", dtype=synth.F16)]))
+@pytest.mark.parametrize("shape,mode", with_modes([synth.MINI8B, synth.MINI13B, synth.MINI8B.with_(name="8b-mini-f16", dtype=synth.F16),
+                                                    synth.WIDE_MINI]))
 def test_generate_full_width_reduced_depth(ad, shape, mode):
     """8B- and 13B-shaped layers (real d, heads, FFN), 4 layers and a reduced vocabulary so that the oracle
     finishes in seconds; forced schedules exercise ragged catch-up, scripted drafts force rejections."""
@@ -227,11 +233,11 @@ def test_generate_full_width_reduced_depth(ad, shape, mode):
     p = synth.make_prompt(shape, 0)
     print(f"case {shape.name} layer mode {mode} natural", flush=True)
     compare_runs(shape, g, o, p, shape.gen_len, 0.9, 7)
-    forced = synth.make_forced_schedule(shape, 1, max_pos, probs=[0.25, 0.25, 0.25])
+    forced = synth.make_forced_schedule(shape, 1, max_pos, probs=[0.25] * len(shape.exit_layers))
     print(f"case {shape.name} forced", flush=True)
     compare_runs(shape, g, o, p, shape.gen_len, 0.9, 7, forced_exit=forced)
     script = np.full(max_pos, -1, dtype=np.int32)
-    script[[26, 31, 40]] = [5, 6, 7]
+    script[[shape.prompt_len + 2, shape.prompt_len + 7, shape.prompt_len + 16]] = [5, 6, 7]
     print(f"case {shape.name} forced+scripted", flush=True)
     compare_runs(shape, g, o, p, shape.gen_len, 0.9, 5, forced_exit=forced, scripted_draft=script)
     # cache parity after the run
