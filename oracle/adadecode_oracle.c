@@ -140,6 +140,66 @@ void orc_confidence(const double *z, int32_t n, int32_t *token, double *conf, do
     if (margin) *margin = (n > 1) ? z[best] - second : INFINITY;
 }
 
+/* ---- sampling (Sec. 2.2) ---------------------------------------------------------------------------- */
+
+/* softmax(z / temperature): the distribution a token is sampled from when decoding is not greedy */
+void orc_softmax_t(const double *z, int32_t n, double temperature, double *p) {
+    double zmax = z[0];
+    for (int32_t j = 1; j < n; ++j)
+        if (z[j] > zmax) zmax = z[j];
+    double sum = 0.0;
+    for (int32_t j = 0; j < n; ++j) {
+        p[j] = exp((z[j] - zmax) / temperature);
+        sum += p[j];
+    }
+    for (int32_t j = 0; j < n; ++j) p[j] /= sum;
+}
+
+/* Inversion sampling: token j owns the interval [c_{j-1}, c_j) of the cumulative weights, and the draw
+ * u * c_{n-1} falls into exactly one interval of positive length. */
+int32_t orc_sample_cdf(const double *w, int32_t n, double u, double *margin) {
+    double total = 0.0;
+    for (int32_t j = 0; j < n; ++j) total += w[j];
+    const double target = u * total;
+    double c = 0.0;
+    int32_t last_pos = 0;
+    for (int32_t j = 0; j < n; ++j) {
+        const double lo = c;
+        c += w[j];
+        if (w[j] > 0.0) last_pos = j;
+        if (c > target) {
+            if (margin) *margin = fmin(target - lo, c - target) / total;
+            return j;
+        }
+    }
+    if (margin) *margin = 0.0;
+    return last_pos;
+}
+
+/* Eq. 2: the drafted token t survives with probability min(1, p(t) / q(t)); a rejected token is replaced by a
+ * draw from the normalised positive part of p - q. */
+int orc_accept_or_resample(const double *p, const double *q, int32_t n, int32_t t, double u_accept, double u_resample,
+                           int32_t *replacement, double *ratio, double *margin) {
+    const double r = (q[t] > 0.0) ? p[t] / q[t] : (p[t] > 0.0 ? INFINITY : 0.0);
+    if (ratio) *ratio = r;
+    double mg = (r >= 1.0) ? 1.0 : fabs(u_accept - r);
+    const int accepted = u_accept < fmin(1.0, r);
+    if (!accepted) {
+        double *res = (double *)malloc(sizeof(double) * (size_t)n);
+        double mass = 0.0;
+        for (int32_t j = 0; j < n; ++j) {
+            res[j] = (p[j] > q[j]) ? p[j] - q[j] : 0.0;
+            mass += res[j];
+        }
+        double ms;
+        *replacement = orc_sample_cdf(mass > 0.0 ? res : p, n, u_resample, &ms);
+        if (ms < mg) mg = ms;
+        free(res);
+    }
+    if (margin) *margin = mg;
+    return accepted;
+}
+
 /* ---- model and cache objects ---------------------------------------------------------------------- */
 
 orc_model *orc_model_new(const orc_config *cfg, const orc_layer_weights *layers, const orc_top_weights *top) {
@@ -426,7 +486,7 @@ static int32_t exit_head_index(const orc_config *c, int32_t layer) {
 }
 
 /*
- * Algorithm 1 (adaptive layer parallelism), greedy decoding.
+ * Algorithm 1 (adaptive layer parallelism), greedy decoding or, with temperature > 0, sampled decoding.
  *
  * State.  `rows` are the tokens whose deeper layers are still owed, oldest first: the early-predicted
  * tokens since the last verification plus the current token.  depth[r] is the number of layers row r
@@ -447,7 +507,13 @@ static int32_t exit_head_index(const orc_config *c, int32_t layer) {
  *    predictions"): when the cap is reached the current token runs to the last layer;
  *  - with a token budget instead of an EOS stop, a token that would be the last one is not drafted:
  *    it runs to the last layer, so that every returned token is verified; an early prediction equal to
- *    the EOS id is not taken either.
+ *    the EOS id is not taken either;
+ *  - sampled decoding (temperature > 0): the head's token is drawn from softmax(z / temperature) and the
+ *    probability compared with gamma is that token's (Eq. 1); the head's whole distribution is kept until
+ *    the verification, which walks the drafts in order with Eq. 2, replaces the first rejected one by a
+ *    draw from the residual distribution, and, if none is rejected, draws the next token from the final
+ *    distribution of the newest row.  Every draw is an input (gp->uniforms), one column per use, so that a
+ *    position that samples at several heads uses a fresh draw at each.
  */
 int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, int32_t n_prompt,
                      const orc_gen_params *gp, int32_t *out_tokens, int32_t *n_out, orc_stats *stats,
@@ -456,6 +522,8 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
     const int32_t L = c->n_layers, d = c->d_model;
     if (n_prompt < 1 || gp->max_new < 1 || gp->max_pending < 0) return -1;
     const int32_t cap_rows = gp->max_pending + 1;
+    const int sampled = gp->temperature > 0.0;
+    if (sampled && (!gp->uniforms || cap_rows > 9)) return -1;
 
     int32_t *row_pos = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap_rows);
     int32_t *row_tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap_rows);
@@ -463,6 +531,11 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
     int32_t *row_arg = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap_rows);
     double *row_margin = (double *)malloc(sizeof(double) * (size_t)cap_rows);
     double *row_h = (double *)malloc(sizeof(double) * (size_t)cap_rows * d);
+    const int32_t V = c->vocab, ucols = c->n_exit + 3;
+    /* sampled runs keep the draft distribution of every open row's successor, and work on one final distribution */
+    double *row_q = sampled ? (double *)malloc(sizeof(double) * (size_t)cap_rows * V) : NULL;
+    double *zbuf = sampled ? (double *)malloc(sizeof(double) * (size_t)V) : NULL;
+    double *pbuf = sampled ? (double *)malloc(sizeof(double) * (size_t)V) : NULL;
     orc_stats st;
     memset(&st, 0, sizeof st);
     int64_t n_events = 0;
@@ -502,7 +575,15 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
                 /* Eq. 1 on the newest row only: the older rows already have a drafted successor */
                 int32_t tok;
                 double conf, margin;
-                orc_head(model, hi, row_h + (size_t)(n_rows - 1) * d, &tok, &conf, &margin, NULL);
+                if (!sampled) {
+                    orc_head(model, hi, row_h + (size_t)(n_rows - 1) * d, &tok, &conf, &margin, NULL);
+                } else {
+                    double *q = row_q + (size_t)(n_rows - 1) * V;
+                    head_logits(model, hi, row_h + (size_t)(n_rows - 1) * d, zbuf);
+                    orc_softmax_t(zbuf, V, gp->temperature, q);
+                    tok = orc_sample_cdf(q, V, (double)gp->uniforms[(size_t)pos * ucols + hi], &margin);
+                    conf = q[tok];
+                }
                 ++st.head_evals;
                 int fire = gp->forced_exit ? 1 : (conf > gp->gamma);
                 if (gp->scripted_draft && gp->scripted_draft[pos] >= 0) tok = gp->scripted_draft[pos];
@@ -520,14 +601,48 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
             if (l == L) {
                 /* every row is now complete at every layer: verify the early predictions in order */
                 int32_t n_accept, next;
-                orc_verify(model, row_h, row_tok + 1, n_rows, &n_accept, &next, row_arg, row_margin);
-                ++st.verifies;
-                emit(events, max_events, &n_events, (orc_event){ORC_EV_VERIFY, L, row_pos[0], n_rows, next, n_accept, 0.0, 0.0});
-                for (int32_t r = 0; r < n_rows; ++r) {
-                    const int32_t cmp = (r < n_rows - 1 && r <= n_accept) ? (row_arg[r] == row_tok[r + 1]) : -1;
-                    emit(events, max_events, &n_events, (orc_event){ORC_EV_VERIFY_ROW, L, row_pos[r], 1, row_arg[r], cmp, 0.0, row_margin[r]});
-                }
                 const int32_t n_draft = n_rows - 1;
+                if (!sampled) {
+                    orc_verify(model, row_h, row_tok + 1, n_rows, &n_accept, &next, row_arg, row_margin);
+                    ++st.verifies;
+                    emit(events, max_events, &n_events, (orc_event){ORC_EV_VERIFY, L, row_pos[0], n_rows, next, n_accept, 0.0, 0.0});
+                    for (int32_t r = 0; r < n_rows; ++r) {
+                        const int32_t cmp = (r < n_rows - 1 && r <= n_accept) ? (row_arg[r] == row_tok[r + 1]) : -1;
+                        emit(events, max_events, &n_events, (orc_event){ORC_EV_VERIFY_ROW, L, row_pos[r], 1, row_arg[r], cmp, 0.0, row_margin[r]});
+                    }
+                } else {
+                    /* Eq. 2, draft by draft in position order, against the final distribution of the row before it */
+                    double ratio[8 + 1] = {0}, mg[8 + 1] = {0};
+                    int32_t flag[8 + 1];
+                    n_accept = n_draft;
+                    next = -1;
+                    for (int32_t r = 0; r < n_rows; ++r) flag[r] = -1;
+                    for (int32_t r = 0; r < n_draft && next < 0; ++r) {
+                        const float *u = gp->uniforms + (size_t)row_pos[r] * ucols;
+                        head_logits(model, -1, row_h + (size_t)r * d, zbuf);
+                        orc_softmax_t(zbuf, V, gp->temperature, pbuf);
+                        int32_t repl = -1;
+                        flag[r] = orc_accept_or_resample(pbuf, row_q + (size_t)r * V, V, row_tok[r + 1], (double)u[c->n_exit + 1],
+                                                         (double)u[c->n_exit + 2], &repl, &ratio[r], &mg[r]);
+                        if (!flag[r]) {
+                            n_accept = r;
+                            next = repl;
+                        }
+                    }
+                    if (next < 0) {
+                        /* nothing rejected: the newest row's final distribution gives the next token */
+                        const int32_t r = n_rows - 1;
+                        head_logits(model, -1, row_h + (size_t)r * d, zbuf);
+                        orc_softmax_t(zbuf, V, gp->temperature, pbuf);
+                        next = orc_sample_cdf(pbuf, V, (double)gp->uniforms[(size_t)row_pos[r] * ucols + c->n_exit], &mg[r]);
+                    }
+                    ++st.verifies;
+                    emit(events, max_events, &n_events, (orc_event){ORC_EV_VERIFY, L, row_pos[0], n_rows, next, n_accept, 0.0, 0.0});
+                    for (int32_t r = 0; r < n_rows; ++r) {
+                        const int32_t tk = (r == n_accept) ? next : (r < n_accept ? row_tok[r + 1] : -1);
+                        emit(events, max_events, &n_events, (orc_event){ORC_EV_VERIFY_ROW, L, row_pos[r], 1, tk, flag[r], ratio[r], mg[r]});
+                    }
+                }
                 if (n_accept < n_draft) {
                     ++st.rejections;
                     st.rolled_back += n_draft - n_accept - 1;
@@ -550,6 +665,7 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
     if (stats) *stats = st;
     if (n_events_out) *n_events_out = n_events;
     free(row_pos); free(row_tok); free(row_depth); free(row_arg); free(row_margin); free(row_h);
+    free(row_q); free(zbuf); free(pbuf);
     return rc;
 }
 

@@ -3,7 +3,8 @@
  *
  * A plain, slow, double-precision implementation of what the GPU library computes: the Llama-style
  * decoder layer step over m ragged rows, the exit head (Sec. 2.1; Eq. 1), the verification of early
- * predictions (Sec. 2.2; Eq. 2 at temperature 0), plain greedy decoding, and Algorithm 1.
+ * predictions (Sec. 2.2; Eq. 2, at temperature 0 and in its general form with sampled tokens), plain greedy
+ * decoding, and Algorithm 1.
  * It shares no code with the HIP path and must never be linked into, imported by or called from the
  * product: only tests, the smoke check and the benchmark's CPU-baseline leg use it.
  *
@@ -15,7 +16,10 @@
  *
  * Pins (tests/test_oracle_*.py): whole-sequence causal forward written with library matmul/softmax,
  * closed forms for RMSNorm / RoPE / softmax confidence, AdaDecode == greedy by brute force, deferred
- * KV == sequential KV, the worked example of Fig. 2 (left), gamma = 0 and gamma = 1 (Sec. 4.4).
+ * KV == sequential KV, the worked example of Fig. 2 (left), gamma = 0 and gamma = 1 (Sec. 4.4); for the
+ * sampled form: inversion sampling against a library cumulative sum / search, the output law of
+ * draft-accept-resample against its closed form (exactly the final distribution when every draft is taken),
+ * and the low-temperature limit against greedy decoding.
  * Parity unpinned: natural exit and rejection *rates* on random-init models (the paper's 5-6 % are
  * for trained heads on real data); they are reported, not checked.
  */
@@ -83,6 +87,23 @@ void orc_verify(const orc_model *, const double *hidden /*[m][d]*/, const int32_
                 int32_t *n_accept, int32_t *next_token, int32_t *row_argmax /*[m] or NULL*/,
                 double *row_margin /*[m] or NULL*/);
 
+/* --- sampling (Sec. 2.2: the token of Eq. 1 may be sampled; Eq. 2 in its general form) -------------------
+ * Random numbers are inputs: every draw is a uniform u in [0, 1) handed in by the caller. */
+/* p = softmax(z / temperature), temperature > 0 */
+void    orc_softmax_t(const double *z, int32_t n, double temperature, double *p);
+/* Inversion of the cumulative distribution in index order over weights w >= 0 (not necessarily normalised):
+ * returns the first j whose cumulative weight exceeds u * sum(w); if rounding leaves none, the last j with
+ * w[j] > 0.  margin (may be NULL): distance from u * sum(w) to the nearer end of j's interval, as a
+ * fraction of sum(w): how far u is from producing a neighbouring token. */
+int32_t orc_sample_cdf(const double *w, int32_t n, double u, double *margin);
+/* Eq. 2 for one token t drafted from q and checked against p: accepted (returns 1) iff
+ * u_accept < min(1, p[t] / q[t]); otherwise returns 0 and *replacement is drawn with u_resample from
+ * Normalize(max(0, p - q)) (from p itself if that residual is identically zero).  *ratio = p[t] / q[t].
+ * *margin (may be NULL): min of |u_accept - ratio| (1 if ratio >= 1) and, after a rejection, the replacement
+ * draw's orc_sample_cdf margin. */
+int     orc_accept_or_resample(const double *p, const double *q, int32_t n, int32_t t, double u_accept,
+                               double u_resample, int32_t *replacement, double *ratio, double *margin);
+
 /* --- generation ------------------------------------------------------------------------------------ */
 enum { ORC_EV_LAYER_STEP = 1, ORC_EV_HEAD = 2, ORC_EV_VERIFY = 3, ORC_EV_VERIFY_ROW = 4 };
 typedef struct {
@@ -90,10 +111,13 @@ typedef struct {
     int32_t layer;      /* LAYER_STEP, HEAD */
     int32_t pos;        /* LAYER_STEP: first position; HEAD / VERIFY_ROW: the row's position; VERIFY: first row's position */
     int32_t m;          /* LAYER_STEP / VERIFY: rows */
-    int32_t token;      /* HEAD: argmax; VERIFY: next token; VERIFY_ROW: argmax */
-    int32_t flag;       /* HEAD: 1 = exit taken; VERIFY: n_accept; VERIFY_ROW: 1 = row was compared and matched, 0 = mismatched, -1 = not compared */
-    double  conf;       /* HEAD */
-    double  margin;     /* HEAD / VERIFY_ROW: top-2 logit margin */
+    int32_t token;      /* HEAD: argmax (sampled runs: the sampled token); VERIFY: next token; VERIFY_ROW: argmax
+                           (sampled runs: the draft checked on that row, the next token on row n_accept, else -1) */
+    int32_t flag;       /* HEAD: 1 = exit taken; VERIFY: n_accept; VERIFY_ROW: 1 = row was compared and matched
+                           (accepted), 0 = mismatched (rejected), -1 = not compared */
+    double  conf;       /* HEAD: the token's probability; VERIFY_ROW of a sampled run: the ratio of Eq. 2 (0 if not compared) */
+    double  margin;     /* HEAD / VERIFY_ROW: top-2 logit margin; sampled runs: how far the row's uniform draws were
+                           from changing its decisions (see orc_sample_cdf, orc_accept_or_resample) */
 } orc_event;
 
 typedef struct {
@@ -104,6 +128,13 @@ typedef struct {
     const uint8_t *forced_exit;     /* NULL, or [max_pos]: 0 = full depth, else the exit layer forced for that position */
     const int32_t *scripted_draft;  /* NULL, or [max_pos]: if >= 0, the token drafted when position pos exits early
                                        (replaces the head's argmax; lets a test force a rejection) */
+    double temperature;             /* 0: greedy (Eq. 1 and Eq. 2 at temperature 0).  > 0: tokens are sampled from
+                                       softmax(z / temperature) and verified with the general Eq. 2 */
+    const float *uniforms;          /* sampled runs: [max_pos][n_exit + 3] draws in [0, 1).  For the row at position
+                                       pos: column i < n_exit samples its successor at exit head i; column n_exit
+                                       samples its successor at the final layer; column n_exit + 1 decides the
+                                       acceptance of the token drafted after it; column n_exit + 2 draws that
+                                       token's replacement after a rejection */
 } orc_gen_params;
 
 typedef struct {

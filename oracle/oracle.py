@@ -45,7 +45,8 @@ assert EVENT_DTYPE.itemsize == C.sizeof(Event)
 
 class GenParams(C.Structure):
     _fields_ = [("gamma", C.c_double), ("max_pending", C.c_int32), ("max_new", C.c_int32), ("eos_id", C.c_int32),
-                ("forced_exit", C.c_void_p), ("scripted_draft", C.c_void_p)]
+                ("forced_exit", C.c_void_p), ("scripted_draft", C.c_void_p),
+                ("temperature", C.c_double), ("uniforms", C.c_void_p)]
 
 
 class Stats(C.Structure):
@@ -88,6 +89,11 @@ def lib() -> C.CDLL:
         L.orc_layer_step.argtypes = [P, P, i32, P, P, i32]
         L.orc_head.argtypes = [P, i32, P, P, P, P, P]
         L.orc_verify.argtypes = [P, P, P, i32, P, P, P, P]
+        L.orc_softmax_t.argtypes = [P, i32, f64, P]
+        L.orc_sample_cdf.restype = i32
+        L.orc_sample_cdf.argtypes = [P, i32, f64, P]
+        L.orc_accept_or_resample.restype = C.c_int
+        L.orc_accept_or_resample.argtypes = [P, P, i32, i32, f64, f64, P, P, P]
         L.orc_generate_greedy.restype = C.c_int
         L.orc_generate_greedy.argtypes = [P, P, P, i32, i32, i32, P, P, P]
         L.orc_generate_ada.restype = C.c_int
@@ -253,15 +259,20 @@ class Oracle:
 
     def generate_ada(self, prompt, max_new: int, gamma: float, max_pending: int = 5, eos_id: int = -1,
                      forced_exit: Optional[np.ndarray] = None, scripted_draft: Optional[np.ndarray] = None,
-                     max_events: int = 1 << 20):
+                     max_events: int = 1 << 20, temperature: float = 0.0, uniforms: Optional[np.ndarray] = None):
+        """temperature > 0: sampled decoding with the draws `uniforms`, float32 [max_pos, n_exit + 3]."""
         p = _i32(prompt)
+        if temperature > 0:
+            uniforms = np.ascontiguousarray(uniforms, dtype=np.float32)
+            assert uniforms.shape == (self.max_pos, len(self.shape.exit_layers) + 3)
         if forced_exit is not None:
             forced_exit = np.ascontiguousarray(forced_exit, dtype=np.uint8)
             assert forced_exit.size >= self.max_pos
         if scripted_draft is not None:
             scripted_draft = _i32(scripted_draft)
             assert scripted_draft.size >= self.max_pos
-        gp = GenParams(gamma, max_pending, max_new, eos_id, _ptr(forced_exit), _ptr(scripted_draft))
+        gp = GenParams(gamma, max_pending, max_new, eos_id, _ptr(forced_exit), _ptr(scripted_draft), temperature,
+                       _ptr(uniforms) if temperature > 0 else None)
         out = np.empty(max_new + max_pending + 2, dtype=np.int32)
         ev = np.zeros(max_events, dtype=EVENT_DTYPE)
         n, nev, st = C.c_int32(), C.c_int64(), Stats()
@@ -271,6 +282,32 @@ class Oracle:
             raise RuntimeError(f"orc_generate_ada rc={rc}")
         assert nev.value <= max_events, "event buffer too small"
         return out[:n.value].copy(), st.as_dict(), ev[:nev.value].copy()
+
+
+def softmax_t(z, temperature: float) -> np.ndarray:
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    p = np.empty_like(z)
+    lib().orc_softmax_t(z.ctypes.data, z.size, C.c_double(temperature), p.ctypes.data)
+    return p
+
+
+def sample_cdf(w, u: float):
+    """(token, margin) of the inversion draw u over the weights w."""
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    mg = C.c_double()
+    t = lib().orc_sample_cdf(w.ctypes.data, w.size, C.c_double(u), C.byref(mg))
+    return int(t), mg.value
+
+
+def accept_or_resample(p, q, t: int, u_accept: float, u_resample: float):
+    """Eq. 2 for one drafted token: (accepted, replacement or -1, ratio, margin)."""
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    assert p.size == q.size
+    repl, ratio, mg = C.c_int32(-1), C.c_double(), C.c_double()
+    acc = lib().orc_accept_or_resample(p.ctypes.data, q.ctypes.data, p.size, t, C.c_double(u_accept), C.c_double(u_resample),
+                                       C.byref(repl), C.byref(ratio), C.byref(mg))
+    return bool(acc), int(repl.value), ratio.value, mg.value
 
 
 def num_threads() -> int:

@@ -227,6 +227,15 @@ def make_forced_schedule(shape: ModelShape, seed: int, n_pos: int,
     return out
 
 
+def make_uniforms(shape: ModelShape, seed: int, n_pos: int) -> np.ndarray:
+    """float32[n_pos, n_exit + 3] uniform draws in [0, 1) for sampled decoding, one row per absolute position:
+    columns 0..n_exit-1 sample the position's successor at each exit head, column n_exit samples it at the final
+    layer, column n_exit + 1 decides the acceptance of the token drafted after the position, column n_exit + 2
+    draws that token's replacement after a rejection."""
+    u = _tensor_seed(seed, "uniforms").random((n_pos, len(shape.exit_layers) + 3), dtype=np.float32)
+    return np.minimum(u, np.float32(1.0 - 2.0 ** -24))
+
+
 def as_f32(w: np.ndarray) -> np.ndarray:
     """The real values a stored tensor represents (fp32 array), whatever its storage type."""
     return bf16_bits_to_f32(w) if w.dtype == np.uint16 else w.astype(np.float32, copy=False)   # float16 widens exactly
