@@ -134,8 +134,33 @@ ad_status ad_exit_head(const ad_model *, int32_t layer, const void *hidden_row, 
 ad_status ad_verify(const ad_model *, const void *hidden, const int32_t *draft, int32_t m, int32_t *n_accept,
                     int32_t *next_token, int32_t *row_argmax, void *stream);
 
-/* For tests: the logits the head at `layer` assigns to m rows.  logits: dev [m, vocab] fp32. */
+/* The logits the head at `layer` assigns to m rows (the distributions that sampled decoding draws from and
+ * verifies against; also used by tests).  logits: dev [m, vocab] fp32. */
 ad_status ad_head_logits(const ad_model *, int32_t layer, const void *hidden, int32_t m, void *logits, void *stream);
+
+/* ---- sampled decoding (Sec. 2.2: the token of Eq. 1 may be drawn with any sampling strategy; Eq. 2 in its
+ * general form).  Random numbers are inputs: every draw is a uniform u in [0, 1) supplied by the caller and
+ * turned into a token by inversion of the cumulative distribution in token-id order (the first id whose
+ * cumulative probability exceeds u).  temperature > 0 scales the logits: p = softmax(z / temperature).
+ *
+ * ad_sample_logits: token ~ softmax(logits / temperature) with the draw u; prob = that token's probability
+ * (the quantity Eq. 1 compares with gamma).  logits: dev [vocab] fp32.  token, prob: pinned host or dev. */
+ad_status ad_sample_logits(const ad_model *, const void *logits, float temperature, float u, int32_t *token, float *prob,
+                           void *stream);
+
+/* Eq. 2 over the m rows of the last layer's pending list.  final_logits: dev [m, vocab] fp32, the final head's
+ * logits of the rows in position order (p* = softmax(. / temperature)); draft_logits: dev [m-1, vocab] fp32,
+ * row k = the logits that draft[k] (the token predicted early after row k) was drawn from; draft, u_accept,
+ * u_resample: host [m-1]; all draws in [0, 1).  In order k = 0, 1, ...: draft[k] is accepted iff
+ * u_accept[k] < min(1, p*_k(draft[k]) / p_draft_k(draft[k])); the first rejected draft ends the run:
+ * n_accept = k and next_token is drawn with u_resample[k] from Normalize(max(0, p*_k - p_draft_k)) (from p*_k if
+ * that residual is identically zero).  If every draft is accepted, n_accept = m-1 and next_token is drawn from
+ * p*_{m-1} with u_final.  ratio: NULL, or [m-1]: the probability ratio of each draft that was checked, 0 for
+ * the rest.  n_accept, next_token, ratio: pinned host or dev.  Uses the model's scratch: calls on one model
+ * must be stream-ordered. */
+ad_status ad_verify_sampled(const ad_model *, const void *final_logits, const void *draft_logits, const int32_t *draft,
+                            int32_t m, float temperature, const float *u_accept, const float *u_resample, float u_final,
+                            int32_t *n_accept, int32_t *next_token, float *ratio, void *stream);
 
 /* ---- Algorithm 1 --------------------------------------------------------------------------------- */
 typedef struct {
@@ -147,6 +172,14 @@ typedef struct {
                                     token at that absolute position (confidence ignored) */
     const int32_t *scripted_draft; /* host; NULL, or [max_pos]: if >= 0, replaces the head's token when the
                                     token at that position exits early (failure injection for tests) */
+    float   temperature;         /* 0: greedy decoding (Eq. 1 and Eq. 2 at temperature 0).  > 0: sampled decoding:
+                                    tokens are drawn from softmax(z / temperature), the probability compared with
+                                    gamma is the drawn token's, and verification is ad_verify_sampled's */
+    const float *uniforms;       /* host; sampled decoding only: [max_pos][n_exit + 3] draws in [0, 1).  Row = the
+                                    absolute position of a token; column i < n_exit draws its successor at exit
+                                    head i, column n_exit draws its successor at the final layer, column
+                                    n_exit + 1 decides the acceptance of the token drafted after it, column
+                                    n_exit + 2 draws that token's replacement after a rejection */
 } ad_gen_params;
 
 typedef struct {
@@ -159,7 +192,10 @@ enum { AD_EV_LAYER_STEP = 1, AD_EV_HEAD = 2, AD_EV_VERIFY = 3, AD_EV_VERIFY_ROW 
 /* Decision trace, one record per scheduler action (same meaning of the fields for every kind:
  * LAYER_STEP: layer, pos = first row's position, m.  HEAD: layer, pos, token, flag = exit taken, conf.
  * VERIFY: pos = first row's position, m, token = next token, flag = n_accept.
- * VERIFY_ROW: pos, token = final-head argmax, flag = 1 matched / 0 mismatched / -1 not compared.) */
+ * VERIFY_ROW: pos, token = final-head argmax, flag = 1 matched / 0 mismatched / -1 not compared.
+ * Sampled decoding: HEAD: token = the drawn token, conf = its probability.  VERIFY_ROW: flag = 1 accepted /
+ * 0 rejected / -1 not checked, conf = the ratio of Eq. 2 (0 if not checked), token = the accepted draft, on row
+ * n_accept the next token, -1 on later rows.) */
 typedef struct { int32_t kind, layer, pos, m, token, flag; float conf; float reserved; } ad_event;
 
 /* Runs Algorithm 1 from an empty cache: prompt (host [n_prompt]) -> out_tokens (host [max_new]).

@@ -25,7 +25,7 @@ AD_PROF_GEMM, AD_PROF_LAYER = 0, 1
 
 EXPORTS = ["ad_workspace_bytes", "ad_model_create", "ad_model_destroy", "ad_kv_bytes", "ad_kv_create", "ad_kv_destroy",
            "ad_kv_len", "ad_kv_set_len", "ad_kv_truncate", "ad_embed", "ad_layer_step", "ad_set_layer_mode", "ad_exit_head", "ad_verify",
-           "ad_head_logits", "ad_generate", "ad_layer_trace", "ad_profile_start", "ad_profile_stop", "ad_last_error", "ad_version"]
+           "ad_head_logits", "ad_sample_logits", "ad_verify_sampled", "ad_generate", "ad_layer_trace", "ad_profile_start", "ad_profile_stop", "ad_last_error", "ad_version"]
 
 
 class Config(C.Structure):
@@ -45,7 +45,7 @@ class TopWeights(C.Structure):
 
 class GenParams(C.Structure):
     _fields_ = [("gamma", C.c_float), ("max_pending", C.c_int32), ("max_new", C.c_int32), ("eos_id", C.c_int32),
-                ("forced_exit", C.c_void_p), ("scripted_draft", C.c_void_p)]
+                ("forced_exit", C.c_void_p), ("scripted_draft", C.c_void_p), ("temperature", C.c_float), ("uniforms", C.c_void_p)]
 
 
 class Stats(C.Structure):
@@ -97,6 +97,8 @@ def lib() -> C.CDLL:
         L.ad_exit_head.argtypes = [P, i32, P, P, P, P]
         L.ad_verify.argtypes = [P, P, P, i32, P, P, P, P]
         L.ad_head_logits.argtypes = [P, i32, P, i32, P, P]
+        L.ad_sample_logits.argtypes = [P, P, C.c_float, C.c_float, P, P, P]
+        L.ad_verify_sampled.argtypes = [P, P, P, P, i32, C.c_float, P, P, C.c_float, P, P, P, P]
         L.ad_generate.argtypes = [P, P, P, i32, C.POINTER(GenParams), P, P, C.POINTER(Stats), P, C.c_int64, P, P]
         L.ad_profile_start.argtypes = [P, i32, i32, i32]
         L.ad_set_layer_mode.argtypes = [P, i32]
@@ -288,11 +290,49 @@ class Model:
         _check(self.L.ad_head_logits(self.model, layer, C.c_void_p(hidden.data_ptr()), m, C.c_void_p(z.data_ptr()), _stream_ptr(torch)))
         return z
 
+    def ad_sample_logits(self, logits, temperature: float, u: float):
+        """(token, its probability) drawn from softmax(logits / temperature) with the uniform draw u."""
+        torch = self.torch
+        assert logits.dtype == torch.float32 and logits.is_contiguous() and logits.numel() == self.shape.vocab
+        out = self._pinned
+        _check(self.L.ad_sample_logits(self.model, C.c_void_p(logits.data_ptr()), temperature, u, C.c_void_p(out.data_ptr()),
+                                       C.c_void_p(out.data_ptr() + 4), _stream_ptr(torch)))
+        torch.cuda.current_stream().synchronize()
+        return int(out[0]), float(out[1:2].view(torch.float32)[0])
+
+    def ad_verify_sampled(self, final_logits, draft_logits, draft: Sequence[int], temperature: float, u_accept, u_resample,
+                          u_final: float):
+        """Eq. 2 on device logits: (n_accept, next_token, ratios[m-1])."""
+        torch = self.torch
+        m = final_logits.shape[0]
+        V = self.shape.vocab
+        assert final_logits.dtype == torch.float32 and final_logits.is_contiguous() and final_logits.shape[1] == V
+        d = np.ascontiguousarray(draft, dtype=np.int32)
+        ua = np.ascontiguousarray(u_accept, dtype=np.float32)
+        ur = np.ascontiguousarray(u_resample, dtype=np.float32)
+        assert d.size == ua.size == ur.size == m - 1
+        if m > 1:
+            assert draft_logits.dtype == torch.float32 and draft_logits.is_contiguous() and tuple(draft_logits.shape) == (m - 1, V)
+        out = self._pinned
+        _check(self.L.ad_verify_sampled(self.model, C.c_void_p(final_logits.data_ptr()),
+                                        C.c_void_p(draft_logits.data_ptr()) if m > 1 else None,
+                                        d.ctypes.data if m > 1 else None, m, temperature,
+                                        ua.ctypes.data if m > 1 else None, ur.ctypes.data if m > 1 else None, u_final,
+                                        C.c_void_p(out.data_ptr() + 32), C.c_void_p(out.data_ptr() + 36),
+                                        C.c_void_p(out.data_ptr() + 64), _stream_ptr(torch)))
+        torch.cuda.current_stream().synchronize()
+        return int(out[8]), int(out[9]), out[16:16 + m - 1].view(torch.float32).numpy().copy()
+
     def ad_generate(self, prompt, max_new: int, gamma: float, max_pending: int = 5, eos_id: int = -1,
                     forced_exit: Optional[np.ndarray] = None, scripted_draft: Optional[np.ndarray] = None,
-                    max_events: int = 1 << 20, want_events: bool = True):
+                    max_events: int = 1 << 20, want_events: bool = True, temperature: float = 0.0,
+                    uniforms: Optional[np.ndarray] = None):
+        """temperature > 0: sampled decoding with the draws `uniforms`, float32 [max_pos, n_exit + 3]."""
         torch = self.torch
         p = np.ascontiguousarray(prompt, dtype=np.int32)
+        if temperature > 0:
+            uniforms = np.ascontiguousarray(uniforms, dtype=np.float32)
+            assert uniforms.shape == (self.max_pos, len(self.shape.exit_layers) + 3)
         if forced_exit is not None:
             forced_exit = np.ascontiguousarray(forced_exit, dtype=np.uint8)
             assert forced_exit.size >= self.max_pos
@@ -301,7 +341,8 @@ class Model:
             assert scripted_draft.size >= self.max_pos
         gp = GenParams(gamma, max_pending, max_new, eos_id,
                        None if forced_exit is None else forced_exit.ctypes.data,
-                       None if scripted_draft is None else scripted_draft.ctypes.data)
+                       None if scripted_draft is None else scripted_draft.ctypes.data,
+                       temperature, uniforms.ctypes.data if temperature > 0 else None)
         out = np.empty(max_new, dtype=np.int32)
         ev = np.zeros(max_events if want_events else 1, dtype=EVENT_DTYPE)
         n, nev, st = C.c_int32(), C.c_int64(), Stats()
@@ -348,7 +389,7 @@ def sched_test_lib() -> C.CDLL:
         P, i32 = C.c_void_p, C.c_int32
         L.ad_sched_test_run.restype = C.c_int
         L.ad_sched_test_run.argtypes = [i32, i32, P, i32, i32, i32, i32, i32, P, P, P, C.POINTER(GenParams), P, i32, P, P,
-                                        C.POINTER(Stats), P, C.c_int64, P]
+                                        C.POINTER(Stats), P, C.c_int64, P, P]
         _sched = L
     return _sched
 
@@ -356,7 +397,8 @@ def sched_test_lib() -> C.CDLL:
 def sched_test_run(n_layers: int, exit_layers: Sequence[int], m_max: int, head_tok: np.ndarray, head_conf: np.ndarray,
                    final_tok: np.ndarray, prompt, max_new: int, gamma: float, max_pending: int, eos_id: int = -1,
                    forced_exit: Optional[np.ndarray] = None, scripted_draft: Optional[np.ndarray] = None, max_events: int = 1 << 18,
-                   max_pos: Optional[int] = None, sequence: bool = False):
+                   max_pos: Optional[int] = None, sequence: bool = False, temperature: float = 0.0,
+                   uniforms: Optional[np.ndarray] = None):
     """Runs the library's host scheduler over scripted head outputs (no GPU).
 
     Table mode: head_tok/head_conf [max_pos, n_exit], final_tok [max_pos], looked up by position.
@@ -376,12 +418,16 @@ def sched_test_run(n_layers: int, exit_layers: Sequence[int], m_max: int, head_t
     if scripted_draft is not None:
         scripted_draft = np.ascontiguousarray(scripted_draft, dtype=np.int32)
     gp = GenParams(gamma, max_pending, max_new, eos_id, None if forced_exit is None else forced_exit.ctypes.data,
-                   None if scripted_draft is None else scripted_draft.ctypes.data)
+                   None if scripted_draft is None else scripted_draft.ctypes.data, temperature,
+                   None if uniforms is None else uniforms.ctypes.data)
+    draws = np.full(4, -1.0, dtype=np.float32)
     out = np.empty(max_new + AD_M_MAX, dtype=np.int32)
     ev = np.zeros(max_events, dtype=EVENT_DTYPE)
     n, nev, st = C.c_int32(), C.c_int64(), Stats()
     rc = L.ad_sched_test_run(n_layers, ex.size, ex.ctypes.data, m_max, max_pos, int(sequence), head_tok.size, final_tok.size,
                              head_tok.ctypes.data, head_conf.ctypes.data,
                              final_tok.ctypes.data, C.byref(gp), p.ctypes.data, p.size, out.ctypes.data, C.byref(n), C.byref(st),
-                             ev.ctypes.data, max_events, C.byref(nev))
+                             ev.ctypes.data, max_events, C.byref(nev), draws.ctypes.data)
+    if temperature > 0:
+        return rc, out[:max(0, n.value)].copy(), st.as_dict(), ev[:nev.value].copy(), draws
     return rc, out[:max(0, n.value)].copy(), st.as_dict(), ev[:nev.value].copy()

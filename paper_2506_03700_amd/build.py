@@ -34,7 +34,7 @@ def _all_deps():
 def build_hip(force=True):
     if not force and not _stale(LIB, _all_deps()):
         return LIB
-    cmd = [HIPCC] + HIP_FLAGS + ["-o", LIB + ".tmp"] + _sources(["ad_kernels.hip", "ad_gemm.hip", "ad_attention.hip", "ad_layer_fused.hip", "ad_host.cpp", "ad_sched.cpp"])
+    cmd = [HIPCC] + HIP_FLAGS + ["-o", LIB + ".tmp"] + _sources(["ad_kernels.hip", "ad_gemm.hip", "ad_attention.hip", "ad_layer_fused.hip", "ad_sample.hip", "ad_host.cpp", "ad_sched.cpp"])
     p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in p.stdout.splitlines() if "packed-fp32-ops" not in l)
     if p.returncode != 0:

@@ -111,6 +111,8 @@ void make_layout(const ad_config &c, Layout &L) {
     s += 2 * align_up((size_t)8 * L.d * 4);                    // x1, rows
     s += align_up((size_t)4096 * 8 * 4 * 4);                   // head partials (up to 4096 workgroups)
     s += align_up((size_t)kBarrierWords * 4);                  // grid-barrier counters of the fused layer step
+    s += align_up((size_t)64 * 4);                             // sampled verification: (max, sum) per row
+    s += 2 * align_up((size_t)AD_M_MAX * L.V * 4);             // sampled decoding: draft and final logits of the open rows
     L.scratch_bytes = s;
     L.total = off + s;
 }
@@ -138,6 +140,7 @@ struct ad_model {
     char *B1, *Bo, *Bg, *Bx;
     float *ssq;
     float *qkv, *x1, *rows, *head_part;
+    float *samp_stats, *draft_logits, *final_logits;   // sampled decoding
     // pinned host results for ad_generate
     int32_t *pin;         // [0..8) tok, [8] n_accept, [9] next, [16..24) row argmax
     float *pin_conf;      // [8]
@@ -251,6 +254,9 @@ ad_status ad_model_create(const ad_config *cfg, const ad_layer_weights *layers, 
     m->head_part = (float *)take((size_t)4096 * 8 * 4 * 4);
     m->bar_ctr = (unsigned *)take((size_t)kBarrierWords * 4);     // zeroed with the rest of the scratch above
     m->bar_round = 0;
+    m->samp_stats = (float *)take((size_t)64 * 4);
+    m->draft_logits = (float *)take((size_t)AD_M_MAX * L.V * 4);
+    m->final_logits = (float *)take((size_t)AD_M_MAX * L.V * 4);
     m->pin = (int32_t *)pinned_alloc(4096);
     if (!m->pin) { delete m; return (ad_status)fail(AD_ENOMEM, "ad_model_create: pinned allocation failed"); }
     m->pin_conf = (float *)(m->pin + 32);
@@ -553,6 +559,36 @@ ad_status ad_head_logits(const ad_model *m, int32_t layer, const void *hidden, i
     return (ad_status)run_head(m, layer, hidden, n, g, stream, "ad_head_logits");
 }
 
+ad_status ad_sample_logits(const ad_model *m, const void *logits, float temperature, float u, int32_t *token, float *prob, void *stream) {
+    if (!m || !logits || !token || !prob) return (ad_status)fail(AD_EINVAL, "ad_sample_logits: null argument");
+    if (!(temperature > 0.f) || !(u >= 0.f && u < 1.f)) return (ad_status)fail(AD_ERANGE, "ad_sample_logits: temperature must be > 0 and u in [0, 1)");
+    SampleArgs a;
+    a.z = (const float *)logits; a.V = m->cfg.vocab; a.inv_t = 1.0f / temperature; a.u = u; a.tok_out = token; a.prob_out = prob;
+    const int rc = launch_sample_row(a, stream);
+    return rc ? (ad_status)hip_fail(rc, "ad_sample_logits") : AD_OK;
+}
+
+ad_status ad_verify_sampled(const ad_model *m, const void *final_logits, const void *draft_logits, const int32_t *draft, int32_t n,
+                            float temperature, const float *u_accept, const float *u_resample, float u_final, int32_t *n_accept,
+                            int32_t *next_token, float *ratio, void *stream) {
+    if (!m || !final_logits || !n_accept || !next_token || (n > 1 && (!draft || !draft_logits || !u_accept || !u_resample)))
+        return (ad_status)fail(AD_EINVAL, "ad_verify_sampled: null argument");
+    if (n < 1 || n > m->cfg.m_max) return (ad_status)fail(AD_ERANGE, "ad_verify_sampled: m = %d outside 1..%d", n, m->cfg.m_max);
+    if (!(temperature > 0.f) || !(u_final >= 0.f && u_final < 1.f)) return (ad_status)fail(AD_ERANGE, "ad_verify_sampled: temperature must be > 0 and draws in [0, 1)");
+    VerifySampledArgs a;
+    memset(&a, 0, sizeof a);
+    a.zf = (const float *)final_logits; a.zq = (const float *)draft_logits; a.V = m->cfg.vocab; a.m = n; a.inv_t = 1.0f / temperature;
+    for (int i = 0; i + 1 < n; ++i) {
+        if (draft[i] < 0 || draft[i] >= m->cfg.vocab) return (ad_status)fail(AD_ERANGE, "ad_verify_sampled: draft token outside the vocabulary");
+        if (!(u_accept[i] >= 0.f && u_accept[i] < 1.f) || !(u_resample[i] >= 0.f && u_resample[i] < 1.f))
+            return (ad_status)fail(AD_ERANGE, "ad_verify_sampled: draws must be in [0, 1)");
+        a.draft[i] = draft[i]; a.u_accept[i] = u_accept[i]; a.u_resample[i] = u_resample[i];
+    }
+    a.u_final = u_final; a.stats = m->samp_stats; a.n_accept_out = n_accept; a.next_out = next_token; a.ratio_out = ratio;
+    const int rc = launch_verify_sampled(a, stream);
+    return rc ? (ad_status)hip_fail(rc, "ad_verify_sampled") : AD_OK;
+}
+
 // ---- measurement -------------------------------------------------------------------------------------
 
 static void profile_clear(Profile &p) {
@@ -667,6 +703,36 @@ struct GpuBackend : Backend {
         bytes += (int64_t)m->cfg.vocab * m->cfg.d_model * s;
         return AD_OK;
     }
+    // Eq. 1 with a sampled token: the head's logits stay in the draft slot of this row until the verification
+    int sample_head(int32_t layer, int32_t r, int32_t, float temperature, float u, int32_t *token, float *prob) override {
+        float *z = m->draft_logits + (size_t)r * m->cfg.vocab;
+        int rc = ad_head_logits(m, layer, row(r), 1, z, stream);
+        if (rc == AD_OK) rc = ad_sample_logits(m, z, temperature, u, m->pin, m->pin_conf, stream);
+        if (rc != AD_OK) return rc;
+        if ((rc = stream_sync(stream))) return hip_fail(rc, "ad_generate: sampled head");
+        if ((rc = fused_health(m, stream))) return rc;
+        *token = m->pin[0];
+        *prob = m->pin_conf[0];
+        const int64_t s = m->cfg.dtype == AD_F32 ? 4 : 2;
+        bytes += (int64_t)m->cfg.vocab * m->cfg.d_model * s;
+        return AD_OK;
+    }
+    int verify_sampled(int32_t n, int32_t, const int32_t *draft, float temperature, const float *u_accept, const float *u_resample,
+                       float u_final, int32_t *n_accept, int32_t *next, float *ratio) override {
+        int rc = ad_head_logits(m, m->cfg.n_layers, row(0), n, m->final_logits, stream);
+        if (rc == AD_OK)
+            rc = ad_verify_sampled(m, m->final_logits, m->draft_logits, draft, n, temperature, u_accept, u_resample, u_final, m->pin + 8,
+                                   m->pin + 9, m->pin_conf + 8, stream);
+        if (rc != AD_OK) return rc;
+        if ((rc = stream_sync(stream))) return hip_fail(rc, "ad_generate: sampled verify");
+        if ((rc = fused_health(m, stream))) return rc;
+        *n_accept = m->pin[8];
+        *next = m->pin[9];
+        for (int i = 0; i + 1 < n; ++i) ratio[i] = m->pin_conf[8 + i];
+        const int64_t s = m->cfg.dtype == AD_F32 ? 4 : 2;
+        bytes += (int64_t)m->cfg.vocab * m->cfg.d_model * s;
+        return AD_OK;
+    }
     int truncate(int32_t new_len) override { return ad_kv_truncate(kv, new_len); }
 };
 
@@ -680,6 +746,8 @@ ad_status ad_generate(const ad_model *m, ad_kv *kv, const int32_t *prompt, int32
     if (n_prompt < 1 || gp->max_new < 1) return (ad_status)fail(AD_EINVAL, "ad_generate: empty prompt or max_new < 1");
     if (gp->max_pending < 0 || gp->max_pending + 1 > m->cfg.m_max)
         return (ad_status)fail(AD_ERANGE, "ad_generate: max_pending %d outside 0..%d", gp->max_pending, m->cfg.m_max - 1);
+    if (gp->temperature < 0.f || (gp->temperature > 0.f && !gp->uniforms))
+        return (ad_status)fail(AD_EINVAL, "ad_generate: sampled decoding needs temperature > 0 and the table of uniform draws");
     if ((int64_t)n_prompt + gp->max_new > kv->max_pos)
         return (ad_status)fail(AD_ERANGE, "ad_generate: prompt + max_new = %lld exceeds max_pos %d", (long long)n_prompt + gp->max_new, kv->max_pos);
     for (int i = 0; i < n_prompt; ++i)

@@ -122,6 +122,26 @@ struct EmbedArgs {
     const void *table; int elem; int d; int m; int32_t tok[8]; float *out;
 };
 
+// Sampled decoding (Sec. 2.2).  inv_t = 1 / temperature; u, u_accept, u_resample, u_final are uniform draws in [0, 1).
+struct SampleArgs {
+    const float *z;         // dev [V] logits
+    int V;
+    float inv_t, u;
+    int32_t *tok_out;       // pinned host or dev
+    float *prob_out;        // pinned host or dev: probability of the drawn token
+};
+struct VerifySampledArgs {
+    const float *zf;        // dev [m][V]: final-layer logits of the m rows
+    const float *zq;        // dev [m - 1][V]: logits each draft was drawn from (row k: the draft that follows row k)
+    int V, m;
+    float inv_t;
+    int32_t draft[8];
+    float u_accept[8], u_resample[8], u_final;
+    float *stats;           // dev scratch [2 * (2m - 1)]: (max, sum of exp) per row
+    int32_t *n_accept_out, *next_out;   // pinned host or dev
+    float *ratio_out;       // null, or pinned host or dev [m - 1]: p*(t) / p_draft(t) of the drafts that were checked, else 0
+};
+
 struct LaunchCtx { void *stream; int n_wg; };
 
 // All launchers return 0 or a hipError_t value.
@@ -135,6 +155,8 @@ int launch_rope_table(const RopeArgs &, void *stream);
 int gemm_max_stationary_k(int planes);   // largest d_model the stationary GEMM variants cover
 int launch_gemm(const GemmArgs &, int planes, const LaunchCtx &);   // EPI_HEAD: also launches the vocabulary combine
 int launch_attn(const AttnArgs &, const LaunchCtx &);
+int launch_sample_row(const SampleArgs &, void *stream);
+int launch_verify_sampled(const VerifySampledArgs &, void *stream);
 int launch_layer_fused(const FusedArgs &, const LaunchCtx &);   // n_wg must not exceed the number of compute units
 int fused_phase_workgroups(int n_tiles, int n_wg);               // workgroups that own row tiles of a GEMM phase
 int attn_chunk(int kv_elem, int dh);   // cached positions per attention work item

@@ -17,7 +17,11 @@
 //  * at most max_pending early predictions stay unverified (App. D); at the cap the current token runs to
 //    the last layer;
 //  * generation stops after max_new verified tokens: a token that would be the last is not drafted, and
-//    an early prediction equal to eos_id is not taken, so EOS is only ever emitted by the last layer.
+//    an early prediction equal to eos_id is not taken, so EOS is only ever emitted by the last layer;
+//  * sampled decoding (temperature > 0): the head's token is drawn from its distribution and the probability
+//    compared with gamma is that token's; the verification applies Eq. 2 in its general form.  The uniform
+//    draws come from the caller's table, one row per position and one column per use (exit head i, final
+//    layer, acceptance, replacement), so that a position that samples at several heads uses fresh draws.
 #include "ad_sched.h"
 
 #include <string.h>
@@ -49,6 +53,9 @@ int run_algorithm1(Backend &be, const SchedConfig &cfg, const ad_gen_params &gp,
     if (!prompt || !out_tokens || !n_out || n_prompt < 1 || gp.max_new < 1) return AD_EINVAL;
     if (gp.max_pending < 0 || gp.max_pending + 1 > cfg.m_max) return AD_ERANGE;
     const int32_t L = cfg.n_layers;
+    const bool sampled = gp.temperature > 0.0f;
+    if (sampled && !gp.uniforms) return AD_EINVAL;
+    const int32_t ucols = cfg.n_exit + 3;
     ad_stats st;
     memset(&st, 0, sizeof st);
     Trace tr{events, max_events, 0};
@@ -87,7 +94,11 @@ int run_algorithm1(Backend &be, const SchedConfig &cfg, const ad_gen_params &gp,
             if (l < L && may_exit && head_slot(cfg, l) >= 0 && (!gp.forced_exit || gp.forced_exit[pos] == l)) {
                 int32_t tok = -1;
                 float conf = 0.0f;
-                if ((rc = be.exit_head(l, n_open - 1, pos, &tok, &conf)) != AD_OK) return rc;
+                if (sampled)
+                    rc = be.sample_head(l, n_open - 1, pos, gp.temperature, gp.uniforms[(size_t)pos * ucols + head_slot(cfg, l)], &tok, &conf);
+                else
+                    rc = be.exit_head(l, n_open - 1, pos, &tok, &conf);
+                if (rc != AD_OK) return rc;
                 ++st.head_evals;
                 bool take = gp.forced_exit ? true : (conf > gp.gamma);
                 if (gp.scripted_draft && gp.scripted_draft[pos] >= 0) tok = gp.scripted_draft[pos];
@@ -106,13 +117,32 @@ int run_algorithm1(Backend &be, const SchedConfig &cfg, const ad_gen_params &gp,
 
         // the current token reached the last layer: every open token is complete, verify the drafts
         int32_t n_accept = 0, next = -1;
-        if ((rc = be.verify(n_open, open_pos[0], open_tok + 1, &n_accept, &next, row_arg)) != AD_OK) return rc;
-        ++st.verifies;
-        tr.add(AD_EV_VERIFY, L, open_pos[0], n_open, next, n_accept, 0.0f);
         const int32_t n_draft = n_open - 1;
-        for (int32_t k = 0; k < n_open; ++k) {
-            const int32_t cmp = (k < n_draft && k <= n_accept) ? (row_arg[k] == open_tok[k + 1] ? 1 : 0) : -1;
-            tr.add(AD_EV_VERIFY_ROW, L, open_pos[k], 1, row_arg[k], cmp, 0.0f);
+        if (!sampled) {
+            if ((rc = be.verify(n_open, open_pos[0], open_tok + 1, &n_accept, &next, row_arg)) != AD_OK) return rc;
+            ++st.verifies;
+            tr.add(AD_EV_VERIFY, L, open_pos[0], n_open, next, n_accept, 0.0f);
+            for (int32_t k = 0; k < n_open; ++k) {
+                const int32_t cmp = (k < n_draft && k <= n_accept) ? (row_arg[k] == open_tok[k + 1] ? 1 : 0) : -1;
+                tr.add(AD_EV_VERIFY_ROW, L, open_pos[k], 1, row_arg[k], cmp, 0.0f);
+            }
+        } else {
+            float u_acc[AD_M_MAX], u_res[AD_M_MAX], ratio[AD_M_MAX];
+            for (int32_t k = 0; k < n_draft; ++k) {
+                u_acc[k] = gp.uniforms[(size_t)open_pos[k] * ucols + cfg.n_exit + 1];
+                u_res[k] = gp.uniforms[(size_t)open_pos[k] * ucols + cfg.n_exit + 2];
+                ratio[k] = 0.0f;
+            }
+            const float u_final = gp.uniforms[(size_t)open_pos[n_open - 1] * ucols + cfg.n_exit];
+            if ((rc = be.verify_sampled(n_open, open_pos[0], open_tok + 1, gp.temperature, u_acc, u_res, u_final, &n_accept, &next, ratio)) != AD_OK)
+                return rc;
+            ++st.verifies;
+            tr.add(AD_EV_VERIFY, L, open_pos[0], n_open, next, n_accept, 0.0f);
+            for (int32_t k = 0; k < n_open; ++k) {
+                const bool checked = k < n_draft && k <= n_accept;
+                const int32_t tok = (k == n_accept) ? next : (k < n_accept ? open_tok[k + 1] : -1);
+                tr.add(AD_EV_VERIFY_ROW, L, open_pos[k], 1, tok, checked ? (k < n_accept ? 1 : 0) : -1, checked ? ratio[k] : 0.0f);
+            }
         }
         if (n_accept < n_draft) {
             ++st.rejections;

@@ -21,6 +21,13 @@ struct Backend {
     virtual int exit_head(int32_t layer, int32_t row, int32_t pos, int32_t *token, float *conf) = 0;
     // Eq. 2 at temperature 0 on rows [0, m)
     virtual int verify(int32_t m, int32_t pos0, const int32_t *draft, int32_t *n_accept, int32_t *next, int32_t *row_argmax) = 0;
+    // Sampled decoding (temperature > 0).  Eq. 1 with the token drawn from softmax(z / temperature) by the uniform
+    // draw u; prob is that token's probability.  The backend keeps the row's distribution for verify_sampled.
+    virtual int sample_head(int32_t, int32_t, int32_t, float, float, int32_t *, float *) { return AD_ESTATE; }
+    // Eq. 2 over rows [0, m): draft[k] was drawn at row k; u_accept[k], u_resample[k] belong to it; u_final draws
+    // the next token if nothing is rejected.  ratio[k]: p*(t) / p_draft(t) of the drafts that were checked, else 0.
+    virtual int verify_sampled(int32_t, int32_t, const int32_t *, float, const float *, const float *, float, int32_t *, int32_t *,
+                               float *) { return AD_ESTATE; }
     virtual int truncate(int32_t new_len) = 0;
 };
 

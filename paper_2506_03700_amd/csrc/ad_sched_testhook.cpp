@@ -67,6 +67,32 @@ struct Scripted : ad::Backend {
         *next = row_argmax[acc];
         return AD_OK;
     }
+    // Sampled decoding over the same tables: the "drawn" token and its probability are the scripted head outputs
+    // (the draw is ignored); draft k is accepted iff u_accept[k] < accept_below; the replacement after a rejection
+    // and the next token after a clean run are the scripted final tokens.
+    float accept_below = 0.5f;
+    float last_u_head = -1.0f, last_u_final = -1.0f, last_u_accept0 = -1.0f, last_u_resample0 = -1.0f;
+    int sample_head(int32_t layer, int32_t row, int32_t pos, float, float u, int32_t *token, float *prob) override {
+        last_u_head = u;
+        return exit_head(layer, row, pos, token, prob);
+    }
+    int verify_sampled(int32_t m, int32_t pos0, const int32_t *, float, const float *u_accept, const float *u_resample, float u_final,
+                       int32_t *n_accept, int32_t *next, float *ratio) override {
+        for (int l = 1; l < n_layers; ++l)
+            if (len[l] != len[0]) return AD_ESTATE;
+        if (len[0] != pos0 + m) return AD_ESTATE;
+        if (seq_mode) return AD_ESTATE;
+        last_u_final = u_final;
+        if (m > 1) { last_u_accept0 = u_accept[0]; last_u_resample0 = u_resample[0]; }
+        int acc = m - 1;
+        for (int j = 0; j < m - 1; ++j) {
+            ratio[j] = accept_below;
+            if (!(u_accept[j] < accept_below)) { acc = j; break; }
+        }
+        *n_accept = acc;
+        *next = final_tok[pos0 + acc];
+        return AD_OK;
+    }
     int truncate(int32_t new_len) override {
         for (int l = 0; l < n_layers; ++l)
             if (len[l] > new_len) len[l] = new_len;
@@ -80,7 +106,9 @@ extern "C" int ad_sched_test_run(int32_t n_layers, int32_t n_exit, const int32_t
                                  int32_t seq_mode, int32_t n_head, int32_t n_final,
                                  const int32_t *head_tok, const float *head_conf, const int32_t *final_tok,
                                  const ad_gen_params *gp, const int32_t *prompt, int32_t n_prompt, int32_t *out_tokens,
-                                 int32_t *n_out, ad_stats *stats, ad_event *events, int64_t max_events, int64_t *n_events) {
+                                 int32_t *n_out, ad_stats *stats, ad_event *events, int64_t max_events, int64_t *n_events,
+                                 float *last_draws /* NULL, or [4]: the head, final, first-acceptance and first-replacement
+                                                      draws the backend saw last in a sampled run */) {
     if (n_layers < 1 || n_layers > 256 || n_exit < 0 || n_exit > AD_MAX_EXIT) return AD_EINVAL;
     Scripted be;
     be.n_layers = n_layers; be.n_exit = n_exit; be.max_pos = max_pos; be.exit_layers = exit_layers;
@@ -91,5 +119,9 @@ extern "C" int ad_sched_test_run(int32_t n_layers, int32_t n_exit, const int32_t
     memset(&sc, 0, sizeof sc);
     sc.n_layers = n_layers; sc.n_exit = n_exit; sc.m_max = m_max;
     for (int i = 0; i < n_exit; ++i) sc.exit_layers[i] = exit_layers[i];
-    return ad::run_algorithm1(be, sc, *gp, prompt, n_prompt, out_tokens, n_out, stats, events, max_events, n_events);
+    const int rc = ad::run_algorithm1(be, sc, *gp, prompt, n_prompt, out_tokens, n_out, stats, events, max_events, n_events);
+    if (last_draws) {
+        last_draws[0] = be.last_u_head; last_draws[1] = be.last_u_final; last_draws[2] = be.last_u_accept0; last_draws[3] = be.last_u_resample0;
+    }
+    return rc;
 }

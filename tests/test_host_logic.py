@@ -37,10 +37,12 @@ def test_size_queries_and_config_checks_without_gpu():
     cfg = ad.make_config(synth.LLAMA8B)
     ws = L.ad_workspace_bytes(C.byref(cfg))
     # the library keeps one copy of every weight (same bytes as the originals for bf16), room for one d x d
-    # transform per exit head (Sec. 2.1), and small scratch
+    # transform per exit head (Sec. 2.1), the logits of up to 8 draft and 8 final rows for sampled decoding, and
+    # small scratch
     s = synth.LLAMA8B
     weights = (s.n_layers * s.layer_weight_elems() + 2 * s.vocab * s.d_model + len(s.exit_layers) * s.d_model ** 2) * 2
-    assert weights <= ws <= weights + (8 << 20)
+    logits = 2 * 8 * s.vocab * 4
+    assert weights + logits <= ws <= weights + logits + (8 << 20)
     kvb = L.ad_kv_bytes(C.byref(cfg), 4096 + 8)
     assert kvb >= s.n_layers * 2 * s.n_kv_heads * s.head_dim * (4096 + 8) * 2
     # per cached position, one layer reads K and V rows of 2 * Hkv * dh * 2 bytes = 4096 B (8B shape)
@@ -164,3 +166,42 @@ def test_scheduler_replays_the_oracle_run(shape, gamma, cap, forced_seed):
         assert st[k] == st_o[k], k
     assert st["steps_by_m"] == st_o["steps_by_m"]
     assert _events(ev) == [(int(e["kind"]), int(e["layer"]), int(e["pos"]), int(e["m"]), int(e["token"]), int(e["flag"])) for e in ev_o]
+
+
+def test_sampled_schedule_uses_the_draw_table_by_position_and_column():
+    """Sampled decoding over a scripted backend: drafts are accepted iff their acceptance draw is below 0.5, and the
+    scheduler must hand each use the draw of the right position and column of the caller's table."""
+    n_pos, L = 32, 4
+    final_tok = (100 + np.arange(n_pos)).astype(np.int32)
+    head_tok = np.stack([200 + np.arange(n_pos), 300 + np.arange(n_pos)], axis=1).astype(np.int32)
+    head_conf = np.zeros((n_pos, 2), dtype=np.float32)
+    head_conf[:, 0] = 0.95                                        # every token exits at the first head (layer 1)
+    u = np.zeros((n_pos, 5), dtype=np.float32)                    # columns: head 0, head 1, final, accept, replace
+    u[:, 0] = 0.01 + np.arange(n_pos) * 1e-3
+    u[:, 2] = 0.02 + np.arange(n_pos) * 1e-3
+    u[:, 3] = 0.1                                                 # accept ...
+    u[6, 3] = 0.9                                                 # ... except the token drafted after position 6
+    u[:, 4] = 0.03 + np.arange(n_pos) * 1e-3
+    prompt = [1, 2, 3, 4, 5]
+    rc, out, st, ev, draws = ad.sched_test_run(L, [1, 3], 8, head_tok, head_conf, final_tok, prompt, 8, 0.9, 3,
+                                               temperature=0.7, uniforms=u)
+    assert rc == ad.AD_OK
+    # positions 4, 5, 6 exit (cap 3), position 7 runs to the end; the draft after 6 is rejected -> next = final_tok[6]
+    assert list(out[:3]) == [204, 205, 106] and st["rejections"] >= 1
+    ver = [e for e in ev if e["kind"] == ad.EV_VERIFY]
+    assert int(ver[0]["pos"]) == 4 and int(ver[0]["m"]) == 4 and int(ver[0]["flag"]) == 2 and int(ver[0]["token"]) == 106
+    rows = [e for e in ev if e["kind"] == ad.EV_VERIFY_ROW][:4]
+    assert [(int(r["token"]), int(r["flag"])) for r in rows] == [(204, 1), (205, 1), (106, 0), (-1, -1)]
+    assert [float(r["conf"]) for r in rows] == [0.5, 0.5, 0.5, 0.0]
+    assert len(out) == 8 and st["tokens"] == 8
+    # the last verification of the run: check which table entries reached the backend
+    last = [e for e in ev if e["kind"] == ad.EV_VERIFY][-1]
+    p0, m = int(last["pos"]), int(last["m"])
+    assert draws[1] == u[p0 + m - 1, 2]                           # final-layer draw of the newest row
+    if m > 1:
+        assert draws[2] == u[p0, 3] and draws[3] == u[p0, 4]
+    heads = [e for e in ev if e["kind"] == ad.EV_HEAD]
+    assert draws[0] == u[int(heads[-1]["pos"]), 0]
+    # without the table a sampled run is refused
+    rc, *_ = ad.sched_test_run(L, [1, 3], 8, head_tok, head_conf, final_tok, prompt, 8, 0.9, 3, temperature=0.7, uniforms=None)
+    assert rc == ad.AD_EINVAL
