@@ -570,7 +570,8 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
             if (m <= 8) ++st.steps_by_m[m];
             emit(events, max_events, &n_events, (orc_event){ORC_EV_LAYER_STEP, l, row_pos[first], m, 0, 0, 0.0, 0.0});
 
-            const int32_t hi = (l < L) ? exit_head_index(c, l) : -1;
+            int32_t hi = (l < L) ? exit_head_index(c, l) : -1;
+            if (hi >= 0 && gp->head_mask != 0 && !((gp->head_mask >> hi) & 1)) hi = -1;   /* head switched off */
             if (hi >= 0 && exits_ok && (!gp->forced_exit || gp->forced_exit[pos] == l)) {
                 /* Eq. 1 on the newest row only: the older rows already have a drafted successor */
                 int32_t tok;
@@ -602,7 +603,23 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
                 /* every row is now complete at every layer: verify the early predictions in order */
                 int32_t n_accept, next;
                 const int32_t n_draft = n_rows - 1;
-                if (!sampled) {
+                if (gp->no_verify) {
+                    /* ablation: the drafts stand unchecked; the newest row's final head gives the next token */
+                    const int32_t r = n_rows - 1;
+                    double conf = 0.0, margin = 0.0;
+                    if (!sampled) {
+                        orc_head(model, -1, row_h + (size_t)r * d, &next, &conf, &margin, NULL);
+                    } else {
+                        head_logits(model, -1, row_h + (size_t)r * d, zbuf);
+                        orc_softmax_t(zbuf, V, gp->temperature, pbuf);
+                        next = orc_sample_cdf(pbuf, V, (double)gp->uniforms[(size_t)row_pos[r] * ucols + c->n_exit], &margin);
+                    }
+                    n_accept = n_draft;
+                    ++st.verifies;
+                    emit(events, max_events, &n_events, (orc_event){ORC_EV_VERIFY, L, row_pos[0], n_rows, next, n_accept, 0.0, 0.0});
+                    for (int32_t q = 0; q < n_rows; ++q)
+                        emit(events, max_events, &n_events, (orc_event){ORC_EV_VERIFY_ROW, L, row_pos[q], 1, q == r ? next : -1, -1, 0.0, q == r ? margin : INFINITY});
+                } else if (!sampled) {
                     orc_verify(model, row_h, row_tok + 1, n_rows, &n_accept, &next, row_arg, row_margin);
                     ++st.verifies;
                     emit(events, max_events, &n_events, (orc_event){ORC_EV_VERIFY, L, row_pos[0], n_rows, next, n_accept, 0.0, 0.0});

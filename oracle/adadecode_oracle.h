@@ -135,6 +135,12 @@ typedef struct {
                                        samples its successor at the final layer; column n_exit + 1 decides the
                                        acceptance of the token drafted after it; column n_exit + 2 draws that
                                        token's replacement after a rejection */
+    /* ablation switches (Table 3 of the paper, in shape only) */
+    int32_t head_mask;              /* 0: every exit head may fire; else bit i enables exit head i (one bit set =
+                                       the fixed-layer variant with a single head) */
+    int32_t no_verify;              /* 1: no verification -- every early prediction is kept as emitted, and the last
+                                       layer only produces the next token from the newest row (the output may then
+                                       differ from plain decoding) */
 } orc_gen_params;
 
 typedef struct {

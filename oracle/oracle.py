@@ -46,7 +46,7 @@ assert EVENT_DTYPE.itemsize == C.sizeof(Event)
 class GenParams(C.Structure):
     _fields_ = [("gamma", C.c_double), ("max_pending", C.c_int32), ("max_new", C.c_int32), ("eos_id", C.c_int32),
                 ("forced_exit", C.c_void_p), ("scripted_draft", C.c_void_p),
-                ("temperature", C.c_double), ("uniforms", C.c_void_p)]
+                ("temperature", C.c_double), ("uniforms", C.c_void_p), ("head_mask", C.c_int32), ("no_verify", C.c_int32)]
 
 
 class Stats(C.Structure):
@@ -259,8 +259,10 @@ class Oracle:
 
     def generate_ada(self, prompt, max_new: int, gamma: float, max_pending: int = 5, eos_id: int = -1,
                      forced_exit: Optional[np.ndarray] = None, scripted_draft: Optional[np.ndarray] = None,
-                     max_events: int = 1 << 20, temperature: float = 0.0, uniforms: Optional[np.ndarray] = None):
-        """temperature > 0: sampled decoding with the draws `uniforms`, float32 [max_pos, n_exit + 3]."""
+                     max_events: int = 1 << 20, temperature: float = 0.0, uniforms: Optional[np.ndarray] = None,
+                     head_mask: int = 0, no_verify: bool = False):
+        """temperature > 0: sampled decoding with the draws `uniforms`, float32 [max_pos, n_exit + 3].
+        head_mask / no_verify: the ablation switches (bit i enables exit head i; drafts are kept unchecked)."""
         p = _i32(prompt)
         if temperature > 0:
             uniforms = np.ascontiguousarray(uniforms, dtype=np.float32)
@@ -272,7 +274,7 @@ class Oracle:
             scripted_draft = _i32(scripted_draft)
             assert scripted_draft.size >= self.max_pos
         gp = GenParams(gamma, max_pending, max_new, eos_id, _ptr(forced_exit), _ptr(scripted_draft), temperature,
-                       _ptr(uniforms) if temperature > 0 else None)
+                       _ptr(uniforms) if temperature > 0 else None, head_mask, int(no_verify))
         out = np.empty(max_new + max_pending + 2, dtype=np.int32)
         ev = np.zeros(max_events, dtype=EVENT_DTYPE)
         n, nev, st = C.c_int32(), C.c_int64(), Stats()

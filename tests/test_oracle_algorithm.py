@@ -185,3 +185,70 @@ def test_rejection_accounting():
     k_first_ver = [i for i, e in enumerate(ev) if e["kind"] == orc.EV_VERIFY][0]
     nxt = [e for e in ev[k_first_ver:] if e["kind"] == orc.EV_LAYER_STEP][0]
     assert (nxt["layer"], nxt["pos"], nxt["m"]) == (1, bad_pos + 1, 1)
+
+
+# ---- ablation switches (Table 3 of the paper, in shape only): a single exit head, no verification ------------
+
+def test_head_mask_with_one_bit_is_the_one_head_model():
+    s, o, p, g, kv = model("tiny-untied")                      # heads at layers 1, 2, 3
+    w = synth.make_weights(s, 0)
+    for i, layer in enumerate(s.exit_layers):
+        one = s.with_(name=f"one-head-{layer}", exit_layers=(layer,))
+        o1 = orc.Oracle(one, w, max_pos=256)
+        for gamma, cap in [(0.0, 5), (0.004, 7)]:
+            a, st, ev = o.generate_ada(p, 40, gamma, cap, head_mask=1 << i)
+            a1, st1, ev1 = o1.generate_ada(p, 40, gamma, cap)
+            np.testing.assert_array_equal(a, a1)
+            assert st == st1
+            for f in ("kind", "layer", "pos", "m", "token", "flag"):
+                np.testing.assert_array_equal(ev[f], ev1[f])
+            assert {int(e["layer"]) for e in ev if e["kind"] == orc.EV_HEAD} <= {layer}
+            np.testing.assert_array_equal(a, g[:40])            # still exactly greedy decoding
+        o1.close()
+    # every bit set is the same as no mask
+    a, st, ev = o.generate_ada(p, 40, 0.004, 7, head_mask=0b111)
+    a0, st0, ev0 = o.generate_ada(p, 40, 0.004, 7)
+    assert st == st0 and np.array_equal(ev["flag"], ev0["flag"]) and np.array_equal(a, a0)
+
+
+def test_no_verify_keeps_drafts_unchecked():
+    s, o, p, g, kv = model("tiny-untied")
+    n = 30
+    # without early predictions there is nothing to verify: the run is plain decoding, one final-head row per token
+    a, st, ev = o.generate_ada(p, n, 1.0, 5, no_verify=True)
+    np.testing.assert_array_equal(a, g[:n])
+    assert st["early_preds"] == 0 and st["verifies"] == n and st["rejections"] == 0
+    # drafts that happen to be right (scripted to the greedy tokens): same output, nothing rolled back
+    forced = np.full(256, s.exit_layers[0], dtype=np.uint8)
+    script = np.full(256, -1, dtype=np.int32)
+    script[len(p) - 1:len(p) - 1 + 48] = g
+    a, st, ev = o.generate_ada(p, n, 0.9, 5, forced_exit=forced, scripted_draft=script, no_verify=True)
+    np.testing.assert_array_equal(a, g[:n])
+    assert st["early_preds"] > 10 and st["rejections"] == 0 and st["rolled_back"] == 0
+    check_bookkeeping(s, ev, st, len(p), 5)
+    # one wrong draft, at the k-th generated token, everything else at full depth: it is emitted as it is, and what
+    # follows is plain decoding from the sequence that contains it (brute force: greedy decoding of that prefix)
+    k = 7
+    bad_pos = len(p) - 1 + k
+    forced = np.zeros(256, dtype=np.uint8)
+    forced[bad_pos] = s.exit_layers[1]
+    script = np.full(256, -1, dtype=np.int32)
+    wrong = (int(g[k]) + 5) % s.vocab
+    script[bad_pos] = wrong
+    a, st, ev = o.generate_ada(p, n, 0.9, 5, forced_exit=forced, scripted_draft=script, no_verify=True)
+    np.testing.assert_array_equal(a[:k], g[:k])
+    assert a[k] == wrong and st["rejections"] == 0 and st["early_preds"] == 1
+    cache = [o.kv_read(l, 0, len(p) + n - 1) for l in range(1, s.n_layers + 1)]
+    o2 = orc.Oracle(s, o.weights, max_pos=256)
+    cont, _ = o2.generate_greedy(np.concatenate([p, a[:k + 1]]), n - k - 1)
+    np.testing.assert_array_equal(a[k + 1:], cont)
+    # ... and the cache is the sequential one of prompt + output
+    for l in range(1, s.n_layers + 1):
+        k2, v2 = o2.kv_read(l, 0, len(p) + n - 1)
+        np.testing.assert_allclose(cache[l - 1][0], k2, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(cache[l - 1][1], v2, rtol=0, atol=1e-12)
+    o2.close()
+    # with verification the same schedule repairs the token
+    a, st, ev = o.generate_ada(p, n, 0.9, 5, forced_exit=forced, scripted_draft=script)
+    np.testing.assert_array_equal(a, g[:n])
+    assert st["rejections"] == 1
