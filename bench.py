@@ -12,6 +12,9 @@ The same JSON line also carries:
                 model's 32 distinct layers so that no cache can hold the weights
   forced        the same generation with exits forced from a seeded schedule (0.2/0.2/0.2 at layers 8/16/24)
   cpu_baseline  the CPU oracle, as it stands, timed on a bounded sample on this machine's host cores
+  gamma_sweep   (only with --gamma-sweep) the threshold sweep of Fig. 5 and the schedule switches of Table 3, in shape
+                only: early-prediction rate, rejection rate and tokens/s per threshold, thresholds placed at quantiles
+                of the synthetic model's own head confidences (random-init heads are never 0.9-confident)
 """
 import argparse
 import json
@@ -48,6 +51,7 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-micro", action="store_true")
     ap.add_argument("--skip-forced", action="store_true")
+    ap.add_argument("--gamma-sweep", action="store_true", help="also run the threshold sweep and the ablation switches")
     ap.add_argument("--layer-mode", default="kernels", choices=["fused", "kernels"],
                     help="layer step as one kernel per phase (default) or as one persistent kernel")
     args = ap.parse_args()
@@ -137,6 +141,44 @@ def main():
                   "achieved_GBps": round(fst["bytes_algorithmic"] / fdt / 1e9, 1)}
         log(f"[bench] forced schedule: {forced}")
 
+    sweep = None
+    if args.gamma_sweep and shape.exit_layers:
+        n_sw = min(gen_len, 256)
+
+        def timed(gamma, **kw):
+            g.ad_generate(prompt, min(n_sw, 32), gamma, cap, want_events=False, **kw)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            _, st, _ = g.ad_generate(prompt, n_sw, gamma, cap, want_events=False, **kw)
+            torch.cuda.synchronize()
+            sdt = time.perf_counter() - t0
+            return {"gamma": float(gamma), "tokens_per_s": round(n_sw / sdt, 1),
+                    "early_prediction_rate": round(st["early_preds"] / max(1, st["early_preds"] + st["verifies"]), 4),
+                    "rejection_rate": round(st["rejections"] / max(1, st["early_preds"]), 4),
+                    "layer_steps": st["layer_steps"], "head_evals": st["head_evals"], "steps_by_m": st["steps_by_m"]}
+
+        # the confidences the heads report when nothing exits (gamma = 1): their quantiles place the thresholds
+        _, _, ev = g.ad_generate(prompt, n_sw, 1.0, cap)
+        confs = np.sort(ev[ev["kind"] == binding.EV_HEAD]["conf"].astype(np.float64))
+        rows = []
+        for q in (1.0, 0.9, 0.75, 0.5, 0.25, 0.1, 0.0):
+            gam = 1.0 if q == 1.0 else (0.0 if q == 0.0 else float(confs[int(q * (len(confs) - 1))]))
+            r = timed(gam)
+            r["confidence_quantile"] = q
+            rows.append(r)
+            log(f"[bench] gamma sweep: {r}")
+        gam = float(confs[len(confs) // 2])
+        abl = []
+        for name, kw in [("all heads, verified", {}), ("no verification", {"no_verify": True})] + \
+                        [(f"only the head at layer {l}", {"head_mask": 1 << i}) for i, l in enumerate(shape.exit_layers)]:
+            r = timed(gam, **kw)
+            r["variant"] = name
+            abl.append(r)
+            log(f"[bench] ablation: {r}")
+        sweep = {"tokens": n_sw, "note": "thresholds at quantiles of the head confidences of this random-init model; "
+                 "early_prediction_rate = early predictions / (early predictions + tokens produced by the last layer)",
+                 "rows": rows, "ablations_at_median_confidence": abl}
+
     micro = None
     if not args.skip_micro:
         micro = {}
@@ -195,6 +237,8 @@ def main():
                                   f"cap {cap}, prompt {prompt_len}, generate {gen_len}, batch 1, random-init N(0,0.02)",
                       "global_batch": 1, "seq_len": prompt_len + gen_len},
            "roofline": roofline, "end_to_end": e2e, "forced": forced, "layer_step": micro, "cpu_baseline": cpu}
+    if sweep is not None:
+        out["gamma_sweep"] = sweep
     print(json.dumps(out), flush=True)
     g.close()
 

@@ -180,6 +180,11 @@ typedef struct {
                                     head i, column n_exit draws its successor at the final layer, column
                                     n_exit + 1 decides the acceptance of the token drafted after it, column
                                     n_exit + 2 draws that token's replacement after a rejection */
+    /* ablation switches (the variants of Table 3, in shape only) */
+    int32_t head_mask;           /* 0: every exit head may fire; else bit i enables exit head i (a single bit = the
+                                    fixed-layer variant with one head) */
+    int32_t no_verify;           /* 1: early predictions are kept unchecked; the last layer only produces the next
+                                    token from the newest row (the output may then differ from plain decoding) */
 } ad_gen_params;
 
 typedef struct {

@@ -21,7 +21,9 @@
 //  * sampled decoding (temperature > 0): the head's token is drawn from its distribution and the probability
 //    compared with gamma is that token's; the verification applies Eq. 2 in its general form.  The uniform
 //    draws come from the caller's table, one row per position and one column per use (exit head i, final
-//    layer, acceptance, replacement), so that a position that samples at several heads uses fresh draws.
+//    layer, acceptance, replacement), so that a position that samples at several heads uses fresh draws;
+//  * ablation switches: head_mask switches exit heads off (one bit left = the fixed-layer variant); no_verify keeps
+//    every early prediction unchecked and lets the last layer produce only the next token from the newest row.
 #include "ad_sched.h"
 
 #include <string.h>
@@ -91,11 +93,13 @@ int run_algorithm1(Backend &be, const SchedConfig &cfg, const ad_gen_params &gp,
             ++st.steps_by_m[m];
             tr.add(AD_EV_LAYER_STEP, l, open_pos[first], m, 0, 0, 0.0f);
 
-            if (l < L && may_exit && head_slot(cfg, l) >= 0 && (!gp.forced_exit || gp.forced_exit[pos] == l)) {
+            const int32_t slot = head_slot(cfg, l);
+            const bool head_on = slot >= 0 && (gp.head_mask == 0 || ((gp.head_mask >> slot) & 1));
+            if (l < L && may_exit && head_on && (!gp.forced_exit || gp.forced_exit[pos] == l)) {
                 int32_t tok = -1;
                 float conf = 0.0f;
                 if (sampled)
-                    rc = be.sample_head(l, n_open - 1, pos, gp.temperature, gp.uniforms[(size_t)pos * ucols + head_slot(cfg, l)], &tok, &conf);
+                    rc = be.sample_head(l, n_open - 1, pos, gp.temperature, gp.uniforms[(size_t)pos * ucols + slot], &tok, &conf);
                 else
                     rc = be.exit_head(l, n_open - 1, pos, &tok, &conf);
                 if (rc != AD_OK) return rc;
@@ -118,7 +122,19 @@ int run_algorithm1(Backend &be, const SchedConfig &cfg, const ad_gen_params &gp,
         // the current token reached the last layer: every open token is complete, verify the drafts
         int32_t n_accept = 0, next = -1;
         const int32_t n_draft = n_open - 1;
-        if (!sampled) {
+        if (gp.no_verify) {
+            // ablation: the drafts stand; the final head on the newest row gives the next token
+            float conf = 0.0f;
+            if (sampled)
+                rc = be.sample_head(L, n_open - 1, pos, gp.temperature, gp.uniforms[(size_t)pos * ucols + cfg.n_exit], &next, &conf);
+            else
+                rc = be.exit_head(L, n_open - 1, pos, &next, &conf);
+            if (rc != AD_OK) return rc;
+            n_accept = n_draft;
+            ++st.verifies;
+            tr.add(AD_EV_VERIFY, L, open_pos[0], n_open, next, n_accept, 0.0f);
+            for (int32_t k = 0; k < n_open; ++k) tr.add(AD_EV_VERIFY_ROW, L, open_pos[k], 1, k == n_open - 1 ? next : -1, -1, 0.0f);
+        } else if (!sampled) {
             if ((rc = be.verify(n_open, open_pos[0], open_tok + 1, &n_accept, &next, row_arg)) != AD_OK) return rc;
             ++st.verifies;
             tr.add(AD_EV_VERIFY, L, open_pos[0], n_open, next, n_accept, 0.0f);

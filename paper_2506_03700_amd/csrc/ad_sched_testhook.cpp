@@ -39,6 +39,13 @@ struct Scripted : ad::Backend {
         return AD_OK;
     }
     int exit_head(int32_t layer, int32_t row, int32_t pos, int32_t *token, float *conf) override {
+        if (layer == n_layers && !seq_mode) {
+            // the final head on one row (a run without verification asks for it): the scripted final token
+            if (row_pos[row] != pos || len[n_layers - 1] != pos + 1) return AD_ESTATE;
+            *token = final_tok[pos];
+            *conf = 1.0f;
+            return AD_OK;
+        }
         int slot = -1;
         for (int i = 0; i < n_exit; ++i)
             if (exit_layers[i] == layer) slot = i;

@@ -318,3 +318,33 @@ def test_runs_are_reproducible(ad):
         np.testing.assert_array_equal(a, outs[0][0])      # fixed-order reductions: bit-identical reruns
         np.testing.assert_array_equal(b, outs[0][1])
     g.close()
+
+
+@pytest.mark.parametrize("shape", [UNTIED, UNTIED.with_(name="tiny-untied-bf16", dtype=synth.BF16)], ids=lambda s: s.name)
+def test_ablation_switches_match_oracle(ad, shape):
+    """The variants of Table 3 that are switches of the schedule: a single exit head (head_mask) and no
+    verification, greedy and sampled, decision by decision against the oracle."""
+    from compare_runs import compare_sampled_runs
+    w = synth.make_weights(shape, seed=0, with_T=True, T_std=0.03)
+    max_pos = 128
+    o = orc.Oracle(shape, w, max_pos=max_pos)
+    g = ad.Model(shape, w, max_pos=max_pos)
+    p = synth.make_prompt(shape, 0)
+    forced = synth.make_forced_schedule(shape, 2, max_pos, probs=[0.25, 0.25, 0.25])
+    script = np.full(max_pos, -1, dtype=np.int32)
+    script[[40, 47, 61, 75]] = [1, 2, 3, 4]
+    for mask in (0b001, 0b010, 0b100, 0b101):
+        print(f"case {shape.name} head_mask={mask:03b}", flush=True)
+        compare_runs(shape, g, o, p, 48, 0.0045, 7, head_mask=mask)
+        compare_runs(shape, g, o, p, 48, 0.9, 5, forced_exit=forced, scripted_draft=script, head_mask=mask)
+    print(f"case {shape.name} no_verify", flush=True)
+    compare_runs(shape, g, o, p, 48, 0.0045, 7, no_verify=True)
+    compare_runs(shape, g, o, p, 48, 0.9, 5, forced_exit=forced, scripted_draft=script, no_verify=True)
+    # an unverified wrong draft stays in the GPU's output
+    tg, sg, _ = g.ad_generate(p, 48, 0.9, 5, forced_exit=forced, scripted_draft=script, no_verify=True)
+    assert sg["rejections"] == 0 and sg["rolled_back"] == 0
+    u = synth.make_uniforms(shape, 4, max_pos)
+    print(f"case {shape.name} sampled no_verify / head_mask", flush=True)
+    compare_sampled_runs(g, o, p, 48, 0.3, 7, TOL[shape.dtype], 0.05, u, no_verify=True)
+    compare_sampled_runs(g, o, p, 48, 0.3, 7, TOL[shape.dtype], 0.05, u, head_mask=0b010)
+    g.close()

@@ -205,3 +205,29 @@ def test_sampled_schedule_uses_the_draw_table_by_position_and_column():
     # without the table a sampled run is refused
     rc, *_ = ad.sched_test_run(L, [1, 3], 8, head_tok, head_conf, final_tok, prompt, 8, 0.9, 3, temperature=0.7, uniforms=None)
     assert rc == ad.AD_EINVAL
+
+
+def test_ablation_switches_in_the_scheduler():
+    n_pos, L = 48, 4
+    final_tok = (100 + np.arange(n_pos)).astype(np.int32)
+    head_tok = np.stack([100 + np.arange(n_pos), 100 + np.arange(n_pos)], axis=1).astype(np.int32)
+    head_tok[9, 0] = 7                                            # the first head drafts a wrong token after position 9
+    head_conf = np.full((n_pos, 2), 0.95, dtype=np.float32)
+    prompt = [1, 2, 3, 4, 5]
+    # both heads on: every exit happens at the first head (layer 1)
+    rc, out, st, ev = ad.sched_test_run(L, [1, 3], 8, head_tok, head_conf, final_tok, prompt, 12, 0.9, 3)
+    assert rc == ad.AD_OK and {int(e["layer"]) for e in ev if e["kind"] == ad.EV_HEAD} == {1}
+    assert list(out) == list(final_tok[4:16]) and st["rejections"] == 1
+    # only the second head (bit 1): exits at layer 3, the wrong draft of head 0 is never seen
+    rc, out, st, ev = ad.sched_test_run(L, [1, 3], 8, head_tok, head_conf, final_tok, prompt, 12, 0.9, 3, head_mask=0b10)
+    assert rc == ad.AD_OK and {int(e["layer"]) for e in ev if e["kind"] == ad.EV_HEAD} == {3}
+    assert list(out) == list(final_tok[4:16]) and st["rejections"] == 0 and st["early_preds"] > 0
+    # no verification: the wrong draft stays in the output, nothing is rolled back, every layer still sees every token once
+    rc, out, st, ev = ad.sched_test_run(L, [1, 3], 8, head_tok, head_conf, final_tok, prompt, 12, 0.9, 3, no_verify=True)
+    assert rc == ad.AD_OK and st["rejections"] == 0 and st["rolled_back"] == 0
+    want = list(final_tok[4:16])
+    want[5] = 7                                                   # the token after position 9 is the 6th generated one
+    assert list(out) == want
+    assert st["layer_step_rows"] == L * 12
+    rows = [e for e in ev if e["kind"] == ad.EV_VERIFY_ROW]
+    assert all(int(r["flag"]) == -1 for r in rows)
