@@ -693,3 +693,12 @@ int orc_num_threads(void) {
     return 1;
 #endif
 }
+
+/* Threads the row loops may use from now on (no effect on any result: rows are independent). */
+void orc_set_num_threads(int n) {
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

@@ -157,6 +157,7 @@ int orc_generate_ada(const orc_model *, orc_kv *, const int32_t *prompt, int32_t
                      int64_t *n_events);
 
 int orc_num_threads(void);
+void orc_set_num_threads(int n);   /* timing aid: threads used by the row loops; results do not depend on it */
 
 #ifdef __cplusplus
 }

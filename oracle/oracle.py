@@ -99,6 +99,7 @@ def lib() -> C.CDLL:
         L.orc_generate_ada.restype = C.c_int
         L.orc_generate_ada.argtypes = [P, P, P, i32, C.POINTER(GenParams), P, P, C.POINTER(Stats), P, C.c_int64, P]
         L.orc_num_threads.restype = C.c_int
+        L.orc_set_num_threads.argtypes = [C.c_int]
         _lib = L
     return _lib
 
@@ -314,3 +315,7 @@ def accept_or_resample(p, q, t: int, u_accept: float, u_resample: float):
 
 def num_threads() -> int:
     return lib().orc_num_threads()
+
+
+def set_num_threads(n: int) -> None:
+    lib().orc_set_num_threads(int(n))

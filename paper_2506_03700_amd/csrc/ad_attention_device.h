@@ -30,7 +30,8 @@ constexpr int kAttnSlots = 5;   // 4 cached blocks + the call's own rows
 template <int DH>
 struct AttnMfmaLds {
     bf16x8 qb[4 * (DH / 32) * 64];                       // [row block][k-step][lane]
-    uint16_t knew[8 * DH], vnew[8 * DH];                  // the call's own rows, cache type
+    uint16_t knew[8 * DH];                               // the call's own K rows, cache type: [row][dim]
+    uint16_t vnewT[DH * 8];                              // the call's own V rows, transposed: [dim][row]
     float part[kAttnSlots * kAttnRowsPerPass * (DH + 4)];   // rows padded to 16 bytes for 128-bit LDS stores
 };
 
@@ -104,8 +105,8 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
                 const uint16_t v0 = f32_to_16<F16>(Io::ld(vp + i)), v1 = f32_to_16<F16>(Io::ld(vp + i + half));
                 L.knew[t * DH + i] = k0;
                 L.knew[t * DH + i + half] = k1;
-                L.vnew[t * DH + i] = v0;
-                L.vnew[t * DH + i + half] = v1;
+                L.vnewT[i * 8 + t] = v0;
+                L.vnewT[(i + half) * 8 + t] = v1;
                 const size_t p = (size_t)(a.pos0 + t);
                 Kg[p * DH + i] = k0;
                 Kg[p * DH + i + half] = k1;
@@ -159,14 +160,17 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
             }
             __syncthreads();
 
-            // this wavefront's key blocks: one cached block, and (one wavefront only) the call's own rows
-            const int w_new = nbc % kAttnWaves;
+            // this wavefront's key blocks: one cached block (row blocks rh, rh + NRH, ...), and, in the item that
+            // holds the end of the cache, the call's own rows: row block b of those goes to wavefront NW - 1 - b, so
+            // that the wavefronts with the least cached work (none at all while m <= 2) take them in parallel
+            constexpr int NW = NTHREADS / 64;
+            const int wave8 = tid >> 6;
             for (int pass = 0; pass < 2; ++pass) {
                 const bool is_new = (pass == 1);
-                if (!has_rows || rh >= nblk) continue;
-                if (!is_new && wave >= nbc) continue;
-                if (is_new && !(last && wave == w_new)) continue;
+                if (!is_new && (!has_rows || rh >= nblk || wave >= nbc)) continue;
+                if (is_new && !(last && NW - 1 - wave8 < nblk)) continue;
                 const int slot = is_new ? 4 : wave;
+                const int b_first = is_new ? NW - 1 - wave8 : rh, b_step = is_new ? nblk : NRH;
                 bf16x8 (&kreg)[2][KS] = kv.k;
                 bf16x8 (&vreg)[DT] = kv.v;
                 if (!is_new) {
@@ -188,19 +192,18 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
                     }
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
-                        union { bf16x8 v; uint16_t u[8]; } cv;
+                        // keys gq * 8 .. + 7 of dimension dt * 16 + n: only the first lane group has live keys
+                        bf16x8 cv = (gq == 0) ? *(const bf16x8 *)(L.vnewT + (dt * 16 + n) * 8) : zero;
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            const int key = gq * 8 + e;
-                            cv.u[e] = (key < a.m) ? L.vnew[key * DH + dt * 16 + n] : (uint16_t)0;
-                        }
-                        vreg[dt] = cv.v;
+                        for (int e = 0; e < 8; ++e)
+                            if (e >= a.m) cv[e] = 0;
+                        vreg[dt] = cv;
                     }
                 }
                 // Half precision has a narrow exponent range: probabilities below 2^-14 of their block's maximum would
                 // be subnormal.  They enter the MFMA scaled by 2^10 (exact), and the products are scaled back.
                 constexpr float kPScale = F16 ? 1024.0f : 1.0f;
-                for (int b = rh; b < nblk; b += NRH) {
+                for (int b = b_first; b < nblk; b += b_step) {
                     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int j = 0; j < KS; ++j) {
