@@ -348,3 +348,39 @@ def test_ablation_switches_match_oracle(ad, shape):
     compare_sampled_runs(g, o, p, 48, 0.3, 7, TOL[shape.dtype], 0.05, u, no_verify=True)
     compare_sampled_runs(g, o, p, 48, 0.3, 7, TOL[shape.dtype], 0.05, u, head_mask=0b010)
     g.close()
+
+
+def test_caller_stream_and_two_models(ad):
+    """Every entry point launches on the stream it is handed: a run on a caller-created stream (default priority),
+    with a second model alive and used in between, gives the bits of the run on the default stream."""
+    import torch
+    shape = synth.TINY_BF16
+    w = synth.make_weights(shape, seed=2, norm_jitter=0.1)
+    w2 = synth.make_weights(shape, seed=3)
+    g = ad.Model(shape, w, max_pos=64)
+    g2 = ad.Model(shape, w2, max_pos=64)
+    p = synth.make_prompt(shape, 2)[:12]
+    h0 = synth.make_hidden(shape, 5, 4)
+
+    def run():
+        g.kv_truncate(0)
+        h = torch.from_numpy(h0).to("cuda:0")
+        for l in range(1, shape.n_layers + 1):
+            g.ad_layer_step(l, h, np.arange(4))
+            g2.kv_truncate(0)
+            g2.ad_layer_step(l if l == 1 else 1, torch.from_numpy(h0).to("cuda:0"), np.arange(4))     # the other model, interleaved
+        tok = g.ad_exit_head(shape.n_layers, h[3])
+        toks, st, _ = g.ad_generate(p, 24, 0.0045, 5)
+        torch.cuda.current_stream().synchronize()
+        return h.cpu().numpy().copy(), tok, toks
+
+    base = run()
+    s = torch.cuda.Stream()            # default priority
+    with torch.cuda.stream(s):
+        other = run()
+    s.synchronize()
+    np.testing.assert_array_equal(base[0], other[0])
+    assert base[1] == other[1]
+    np.testing.assert_array_equal(base[2], other[2])
+    g.close()
+    g2.close()
