@@ -201,7 +201,7 @@ ad_status ad_model_create(const ad_config *cfg, const ad_layer_weights *layers, 
     if (rc) { delete m; return (ad_status)hip_fail(rc, "device query"); }
     m->n_wg = n_cu;
     m->ws = (char *)workspace;
-    const int bf = elem_kind(*cfg);
+    const int ek = elem_kind(*cfg);
     const size_t tile_kb = (size_t)L.planes * 1024u;
 
 #define AD_TRY(expr, what) do { int rc_ = (expr); if (rc_) { delete m; return (ad_status)hip_fail(rc_, what); } } while (0)
@@ -218,12 +218,12 @@ ad_status ad_model_create(const ad_config *cfg, const ad_layer_weights *layers, 
         lp.ffn_norm = p;
         const ad_layer_weights &w = layers[l];
         // q, k, v share one packed matrix: q rows first, then k, then v
-        AD_TRY(launch_pack_weights(w.wq, nullptr, bf, L.dq, L.d, 0, lp.wqkv, stream), "pack wq");
-        AD_TRY(launch_pack_weights(w.wk, nullptr, bf, L.dkv, L.d, 0, lp.wqkv + (size_t)(L.dq / 16) * L.kt_d * tile_kb, stream), "pack wk");
-        AD_TRY(launch_pack_weights(w.wv, nullptr, bf, L.dkv, L.d, 0, lp.wqkv + (size_t)((L.dq + L.dkv) / 16) * L.kt_d * tile_kb, stream), "pack wv");
-        AD_TRY(launch_pack_weights(w.wo, nullptr, bf, L.d, L.dq, 0, lp.wo, stream), "pack wo");
-        AD_TRY(launch_pack_weights(w.w_gate, w.w_up, bf, L.f, L.d, 1, lp.wgu, stream), "pack gate/up");
-        AD_TRY(launch_pack_weights(w.w_down, nullptr, bf, L.d, L.f, 0, lp.wd, stream), "pack down");
+        AD_TRY(launch_pack_weights(w.wq, nullptr, ek, L.dq, L.d, 0, lp.wqkv, stream), "pack wq");
+        AD_TRY(launch_pack_weights(w.wk, nullptr, ek, L.dkv, L.d, 0, lp.wqkv + (size_t)(L.dq / 16) * L.kt_d * tile_kb, stream), "pack wk");
+        AD_TRY(launch_pack_weights(w.wv, nullptr, ek, L.dkv, L.d, 0, lp.wqkv + (size_t)((L.dq + L.dkv) / 16) * L.kt_d * tile_kb, stream), "pack wv");
+        AD_TRY(launch_pack_weights(w.wo, nullptr, ek, L.d, L.dq, 0, lp.wo, stream), "pack wo");
+        AD_TRY(launch_pack_weights(w.w_gate, w.w_up, ek, L.f, L.d, 1, lp.wgu, stream), "pack gate/up");
+        AD_TRY(launch_pack_weights(w.w_down, nullptr, ek, L.d, L.f, 0, lp.wd, stream), "pack down");
         AD_TRY(launch_zero(lp.attn_norm, 2 * L.sz_norm, stream), "zero norms");
         AD_TRY(launch_copy(w.attn_norm, lp.attn_norm, align_up(L.d * L.elem, 16), stream), "copy attn_norm");
         AD_TRY(launch_copy(w.ffn_norm, lp.ffn_norm, align_up(L.d * L.elem, 16), stream), "copy ffn_norm");
@@ -233,12 +233,12 @@ ad_status ad_model_create(const ad_config *cfg, const ad_layer_weights *layers, 
     m->head = m->ws + L.off_head;
     AD_TRY(launch_copy(top->embed, m->embed, align_up((size_t)L.V * L.d * L.elem, 16), stream), "copy embed");
     AD_TRY(launch_copy(top->final_norm, m->final_norm, align_up(L.d * L.elem, 16), stream), "copy final_norm");
-    AD_TRY(launch_pack_weights(top->lm_head, nullptr, bf, L.V, L.d, 0, m->head, stream), "pack lm_head");
+    AD_TRY(launch_pack_weights(top->lm_head, nullptr, ek, L.V, L.d, 0, m->head, stream), "pack lm_head");
     for (int i = 0; i < AD_MAX_EXIT; ++i) {
         m->T[i] = nullptr;
         if (i < cfg->n_exit && top->exit_T && top->exit_T[i]) {
             m->T[i] = m->ws + L.off_T[i];
-            AD_TRY(launch_pack_weights(top->exit_T[i], nullptr, bf, L.d, L.d, 0, m->T[i], stream), "pack exit transform");
+            AD_TRY(launch_pack_weights(top->exit_T[i], nullptr, ek, L.d, L.d, 0, m->T[i], stream), "pack exit transform");
         }
     }
     char *s = m->ws + L.off_scratch;
@@ -430,14 +430,14 @@ ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidde
     const Layout &L = m->lay;
     const LayerPacked &lp = m->layers[layer - 1];
     const LaunchCtx ctx{stream, m->n_wg};
-    const int bf = elem_kind(c);
+    const int ek = elem_kind(c);
     int rc;
     // 1. q, k, v = W (RMSNorm(x)): the norm is fused into the GEMM (B operand built from x in its prologue)
     GemmArgs gq;
     memset(&gq, 0, sizeof gq);
-    gq.elem = bf;
+    gq.elem = ek;
     gq.W = lp.wqkv; gq.NT = L.nqkv / 16; gq.KT = L.kt_d; gq.N = L.nqkv; gq.K = L.d; gq.m = n; gq.mode = GEMM_STATIONARY;
-    gq.x = (const float *)hidden; gq.ldx = L.d; gq.norm_w = lp.attn_norm; gq.norm_elem = bf; gq.inv_dim = 1.0f / (float)L.d; gq.eps = c.rms_eps;
+    gq.x = (const float *)hidden; gq.ldx = L.d; gq.norm_w = lp.attn_norm; gq.norm_elem = ek; gq.inv_dim = 1.0f / (float)L.d; gq.eps = c.rms_eps;
     gq.epi = EPI_STORE; gq.out = m->qkv; gq.ld = L.nqkv;
     // 2. rotary embedding, KV append, attention (partials + combine)
     AttnArgs a;
@@ -445,28 +445,28 @@ ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidde
     a.qkv = m->qkv; a.ld = L.nqkv; a.rope = kv->rope + (size_t)pos[0] * (L.dh / 2) * 2;
     a.Kc = kv->storage + (size_t)(layer - 1) * kv->layer_bytes; a.Vc = (char *)a.Kc + kv->half_bytes;
     a.stride = kv->stride; a.pos0 = pos[0]; a.m = n; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = L.dh;
-    a.C = attn_chunk(bf, L.dh);
+    a.C = attn_chunk(ek, L.dh);
     a.S = pos[0] > 0 ? (pos[0] + a.C - 1) / a.C : 1;
-    a.part = kv->part; a.Bo = m->Bo; a.Bo_KT = L.kt_q; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_elem = bf;
+    a.part = kv->part; a.Bo = m->Bo; a.Bo_KT = L.kt_q; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_elem = ek;
     // 3. x' = x + Wo o
     GemmArgs go;
     memset(&go, 0, sizeof go);
-    go.elem = bf;
+    go.elem = ek;
     go.W = lp.wo; go.B = m->Bo; go.NT = L.d / 16; go.KT = L.kt_q; go.N = L.d; go.K = L.dq; go.m = n; go.mode = GEMM_STREAMED;
     go.epi = EPI_RESID; go.resid = (const float *)hidden; go.out = m->x1; go.ld = L.d;
     // ... and the Wo epilogue already prepares the gate/up GEMM's input: x' * ffn norm weight packed, sum(x'^2) per tile
-    go.Bnext = m->Bx; go.Bnext_KT = L.kt_d; go.next_norm_w = lp.ffn_norm; go.next_norm_elem = bf; go.ssq_out = m->ssq;
+    go.Bnext = m->Bx; go.Bnext_KT = L.kt_d; go.next_norm_w = lp.ffn_norm; go.next_norm_elem = ek; go.ssq_out = m->ssq;
     // 4. g = silu(Wg b) * (Wu b), b = RMSNorm(x') fused as in step 1
     GemmArgs gg;
     memset(&gg, 0, sizeof gg);
-    gg.elem = bf;
+    gg.elem = ek;
     gg.W = lp.wgu; gg.NT = (2 * L.f) / 16; gg.KT = L.kt_d; gg.N = 2 * L.f; gg.K = L.d; gg.m = n; gg.mode = GEMM_STATIONARY;
     gg.B = m->Bx; gg.ssq_in = m->ssq; gg.ssq_tiles = go.NT; gg.inv_dim = 1.0f / (float)L.d; gg.eps = c.rms_eps;
     gg.epi = EPI_SWIGLU; gg.Bnext = m->Bg; gg.Bnext_KT = L.kt_f;
     // 5. y = x' + Wd g
     GemmArgs gd;
     memset(&gd, 0, sizeof gd);
-    gd.elem = bf;
+    gd.elem = ek;
     gd.W = lp.wd; gd.B = m->Bg; gd.NT = L.d / 16; gd.KT = L.kt_f; gd.N = L.d; gd.K = L.f; gd.m = n; gd.mode = GEMM_STREAMED;
     gd.epi = EPI_RESID; gd.resid = m->x1; gd.out = (float *)hidden; gd.ld = L.d;
 
@@ -507,23 +507,23 @@ static int run_head(const ad_model *m, int32_t layer, const void *hidden, int32_
     }
     const Layout &L = m->lay;
     const LaunchCtx ctx{stream, m->n_wg};
-    const int bf = elem_kind(c);
+    const int ek = elem_kind(c);
     int rc;
-    g.elem = bf;
+    g.elem = ek;
     g.W = m->head; g.NT = (L.V + 15) / 16; g.KT = L.kt_d; g.N = L.V; g.K = L.d; g.m = n; g.mode = GEMM_STATIONARY;
     g.epi = EPI_HEAD; g.head_part = m->head_part;
     if (slot >= 0 && m->T[slot]) {
         // lightweight head of Sec. 2.1: E = E* T, applied as E* (T norm(h))
         GemmArgs t;
         memset(&t, 0, sizeof t);
-        t.elem = bf;
+        t.elem = ek;
         t.W = m->T[slot]; t.NT = L.d / 16; t.KT = L.kt_d; t.N = L.d; t.K = L.d; t.m = n; t.mode = GEMM_STATIONARY;
-        t.x = (const float *)hidden; t.ldx = L.d; t.norm_w = m->final_norm; t.norm_elem = bf; t.inv_dim = 1.0f / (float)L.d; t.eps = c.rms_eps;
+        t.x = (const float *)hidden; t.ldx = L.d; t.norm_w = m->final_norm; t.norm_elem = ek; t.inv_dim = 1.0f / (float)L.d; t.eps = c.rms_eps;
         t.epi = EPI_PACK; t.Bnext = m->B1; t.Bnext_KT = L.kt_d;
         if ((rc = gemm(m, t, L.d, L.d, ctx))) return hip_fail(rc, who);
         g.B = m->B1;
     } else {
-        g.x = (const float *)hidden; g.ldx = L.d; g.norm_w = m->final_norm; g.norm_elem = bf; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
+        g.x = (const float *)hidden; g.ldx = L.d; g.norm_w = m->final_norm; g.norm_elem = ek; g.inv_dim = 1.0f / (float)L.d; g.eps = c.rms_eps;
     }
     if ((rc = gemm(m, g, L.V, L.d, ctx))) return hip_fail(rc, who);
     return AD_OK;
