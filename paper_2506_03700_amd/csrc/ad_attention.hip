@@ -30,6 +30,7 @@ constexpr int kAttnThreads = 512;
 
 template <int DH, bool F16>
 __global__ void __launch_bounds__(kAttnThreads) k_attn_mfma(AttnArgs a) {
+    warm_kernel_args<sizeof(AttnArgs)>();
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     AttnKv<DH> kv;
     attn_mfma_items<DH, kAttnThreads, IoPlain, F16>(a, *reinterpret_cast<AttnMfmaLds<DH> *>(lds_raw), blockIdx.x, gridDim.x, kv, false);
@@ -167,10 +168,12 @@ __global__ void __launch_bounds__(kValuThreads) k_attn_valu(AttnArgs a) {
 // fold the splits of every query row, in split order, and pack the result for the Wo GEMM
 // ---------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_attn_combine(AttnArgs a) {
+    warm_kernel_args<sizeof(AttnArgs)>();
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= a.Hq * a.m) return;
-    if (a.kv_elem == ELEM_F16) attn_combine_row<IoPlain, true>(a, row);
-    else attn_combine_row<IoPlain, false>(a, row);
+    if (row < a.Hq * a.m) {
+        if (a.kv_elem == ELEM_F16) attn_combine_row<IoPlain, true>(a, row);
+        else attn_combine_row<IoPlain, false>(a, row);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------

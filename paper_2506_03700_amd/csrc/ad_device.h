@@ -28,6 +28,23 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
 __device__ __forceinline__ float f16_bits_to_f32(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
 __device__ __forceinline__ uint16_t f32_to_f16_bits(float x) { return __builtin_bit_cast(uint16_t, (_Float16)x); }
 
+// Kernel arguments are fetched with scalar loads that the compiler places where each field is first used; every
+// 64-byte line of the argument block that is touched for the first time costs a trip to memory, and those trips
+// come one after the other on the path to the kernel's first useful load.  Reading one word of every line of the
+// block at the kernel's entry (and waiting for them together) overlaps them all: later argument loads hit in the
+// scalar cache.  BYTES: the size of the kernel's explicit arguments; nothing beyond them is read.
+template <int BYTES>
+__device__ __forceinline__ void warm_kernel_args() {
+    typedef const __attribute__((address_space(4))) uint32_t *kptr;
+    kptr p = (kptr)__builtin_amdgcn_kernarg_segment_ptr();
+    constexpr int LINES = (BYTES + 63) / 64;
+    uint32_t v[LINES];
+#pragma unroll
+    for (int i = 0; i < LINES; ++i) v[i] = p[i * 16 < BYTES / 4 ? i * 16 : BYTES / 4 - 1];
+#pragma unroll
+    for (int i = 0; i < LINES; ++i) asm volatile("" ::"s"(v[i]));
+}
+
 // Element kinds of stored tensors (weights, norm vectors, embedding table, KV cache).  16-bit activations use
 // the same type as the weights they meet in an MFMA: bf16 for fp32 and bf16 models, fp16 for fp16 models.
 enum ElemKind : int { ELEM_F32 = 0, ELEM_BF16 = 1, ELEM_F16 = 2 };

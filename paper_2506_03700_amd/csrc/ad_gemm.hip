@@ -3,6 +3,7 @@
 // of Eq. 1 / Eq. 2 with its vocabulary reduction.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 #include "ad_device.h"
 #include "ad_gemm_device.h"
@@ -15,18 +16,18 @@ namespace ad {
 // chunks of 4 only; fp32 weights (three planes per k-step) have chunks of 2.
 template <int NPL, int MODE, int NCHMAX, bool F16>
 __global__ void __launch_bounds__(MODE == GEMM_STATIONARY ? kStatThreads : kThreads) k_gemm(GemmArgs g) {
+    warm_kernel_args<sizeof(GemmArgs)>();
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     GemmLds &L = *reinterpret_cast<GemmLds *>(lds_raw);
     if constexpr (MODE == GEMM_STATIONARY) {
         constexpr int CH = NPL == 1 ? (NCHMAX > 3 ? 4 : 8) : 2;
         StatStream<NPL, CH> S;
-        S.init(g, blockIdx.x, gridDim.x);
-        S.prefetch();
-        gemm_stationary<NPL, CH, NCHMAX, IoPlain, -1, F16>(g, S, L, NoTail());
+        S.init(g, blockIdx.x, 0x7fffffff);       // every workgroup of this launch has tiles (the grid size is an argument fetch away)
+        gemm_stationary<NPL, CH, NCHMAX, IoPlain, -1, F16, false>(g, S, L, NoTail());
     } else {
         constexpr int U = NPL == 1 ? 4 : 2;
         StreamStream<NPL, U, kWaves> S;
-        S.init(g, blockIdx.x, gridDim.x);
+        S.init(g, blockIdx.x, 0x7fffffff);
         S.prefetch(g);
         gemm_streamed<NPL, U, kWaves, IoPlain, -1, false, F16>(g, S, L, NoTail());
     }
@@ -77,7 +78,9 @@ static int launch_one(const GemmArgs &g, int grid, hipStream_t s) {
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_gemm<NPL, MODE, NCHMAX, F16>), dim3(grid), dim3(MODE == GEMM_STATIONARY ? kStatThreads : kThreads), sizeof(GemmLds), s, g);
+    GemmArgs ga = g;
+    set_tile_partition(ga, grid);
+    hipLaunchKernelGGL((k_gemm<NPL, MODE, NCHMAX, F16>), dim3(grid), dim3(MODE == GEMM_STATIONARY ? kStatThreads : kThreads), sizeof(GemmLds), s, ga);
     return (int)hipGetLastError();
 }
 

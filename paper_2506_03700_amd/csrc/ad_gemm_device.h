@@ -219,8 +219,8 @@ struct StatStream {
 
     __device__ __forceinline__ void init(const GemmArgs &g, int wg, int nwg) {
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        t0 = (int)(((long)g.NT * wg) / nwg);
-        t1 = (int)(((long)g.NT * (wg + 1)) / nwg);
+        t0 = wg * g.tq + (wg < g.tr ? wg : g.tr);
+        t1 = t0 + g.tq + (wg < g.tr ? 1 : 0);
         if (wg >= nwg) t0 = t1 = 0;                // not one of this GEMM's workgroups
         ks0 = part_start(g.KT, wave, kStatWaves);
         nks = part_start(g.KT, wave + 1, kStatWaves) - ks0;
@@ -232,20 +232,40 @@ struct StatStream {
     }
     __device__ __forceinline__ unsigned chunk_ptr(int c) const { return wbase + (unsigned)(c / nch) * tstride + (unsigned)(c % nch) * (CH * NPL * 64u); }
     __device__ __forceinline__ int chunk_len(int c) const { const int r = nks - (c % nch) * CH; return r < CH ? r : CH; }
-    // the first two weight chunks go in flight
+    // The first two weight chunks go in flight.  The loads are unconditional (a wavefront with fewer chunks reads
+    // the start of the matrix instead, and nothing is done with it): code after this call then knows how many loads
+    // are outstanding, and can wait for an earlier load without waiting for these.
     __device__ __forceinline__ void prefetch() {
         // the address arithmetic of these loads stays here (behind an opaque copy of the base offset) instead of
         // being hoisted to where the caller's own stream needs the registers
         asm volatile("" : "+v"(wbase));
-        if (total > 0) load_chunk<NPL, CH>(a0, W, chunk_ptr(0), chunk_len(0));
-        if (total > 1) load_chunk<NPL, CH>(a1, W, chunk_ptr(1), chunk_len(1));
+        const unsigned lane = threadIdx.x & 63;
+        const unsigned p0 = total > 0 ? chunk_ptr(0) : lane, p1 = total > 1 ? chunk_ptr(1) : lane;
+        const int n0 = total > 0 ? chunk_len(0) : 1, n1 = total > 1 ? chunk_len(1) : 1;
+        load_chunk_clamped(a0, p0, n0);
+        load_chunk_clamped(a1, p1, n1);
+    }
+    __device__ __forceinline__ void load_chunk_clamped(bf16x8 (&a)[CH][NPL], unsigned p, int n) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            const int jj = j < n ? j : n - 1;
+#pragma unroll
+            for (int q = 0; q < NPL; ++q) a[j][q] = load_tile(W, p + (unsigned)(jj * NPL + q) * 64u);
+        }
     }
 };
 
 // `tail` runs once, after the workgroup's last MFMA and before its last reduction and epilogue.
+// PREFETCHED: S.prefetch() has been called already (a phase whose weights went in flight while the workgroup
+// waited for its inputs).  Otherwise the function calls it itself, right after it has issued the loads of its
+// activations: a wavefront's loads return in order, so activations requested behind 16 KiB of weights would arrive
+// after them, and the B operand, without which no weight can be consumed, would be late by the whole prefetch.
+// All loads of the prologue are unconditional (rows, k-steps and tiles past the end are clamped to the last valid
+// one, which costs no extra cache lines, and masked afterwards), so that their number is known at compile time and
+// the waits for the activations do not also wait for the weights behind them.
 // NCHMAX: most chunks per tile and wavefront this instance covers (the B slice takes NCHMAX * CH registers x 4).
 // F16: the weights and the 16-bit halves of the activations are fp16 (else bf16).
-template <int NPL, int CH, int NCHMAX, class Io, int EPI, bool F16, class Tail>
+template <int NPL, int CH, int NCHMAX, class Io, int EPI, bool F16, bool PREFETCHED, class Tail>
 __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NPL, CH> &S, GemmLds &L, Tail tail) {
     constexpr int KSB = NCHMAX * CH;   // B registers cover whole chunks
     constexpr int kWaves = kStatWaves, kThreads = kStatThreads;         // this mode's workgroup shape
@@ -275,27 +295,38 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
     auto sw = [](int u) { return u ^ ((u >> 4) & 15); };
     if (g.x) {
         // two passes' worth of loads are in flight: those of pass p + 1 are issued before pass p is converted
-        f32x4 xr[2][8], wr[2];
-        auto load_pass = [&](f32x4 (&xp)[8], f32x4 &wp, int p) {
+        f32x4 xr[2][8];
+        u32x4 wraw[2];
+        const bool w16 = g.norm_elem != ELEM_F32;
+        const char *wsrc = g.norm_w ? (const char *)g.norm_w : (const char *)g.x;     // without a norm vector: any valid address
+        auto load_pass = [&](f32x4 (&xp)[8], u32x4 &wp, int p) {
             const int k = (ks0 + p * 8) * 32 + lane * 4;
             const int kc = (k > g.K - 4) ? g.K - 4 : k;              // clamped address, masked result
-            if (p * 8 < nks) {
-                float w8[8];
-                load_w8(g.norm_w, g.norm_elem, (size_t)(kc & ~7), w8);
-                const int o = kc & 4;
-                wp = (f32x4){w8[o], w8[o + 1], w8[o + 2], w8[o + 3]};
+            // the lane's four norm weights: 16-bit kinds load the aligned group of eight that holds them
+            wp = *(const u32x4 *)(wsrc + (w16 ? (size_t)(kc & ~7) * 2 : (size_t)kc * 4));
 #pragma unroll
-                for (int t = 0; t < 8; ++t)
-                    if (t < g.m) xp[t] = Io::ld4(g.x + (size_t)t * g.ldx + kc);
-            }
+            for (int t = 0; t < 8; ++t) xp[t] = Io::ld4(g.x + (size_t)(t < g.m ? t : g.m - 1) * g.ldx + kc);
         };
-        load_pass(xr[0], wr[0], 0);
+        auto norm4 = [&](const u32x4 &raw, int p) -> f32x4 {
+            if (!g.norm_w) return (f32x4){1.f, 1.f, 1.f, 1.f};
+            if (g.norm_elem == ELEM_F32) return (f32x4){__uint_as_float(raw[0]), __uint_as_float(raw[1]), __uint_as_float(raw[2]), __uint_as_float(raw[3])};
+            const int k = (ks0 + p * 8) * 32 + lane * 4;
+            const int kc = (k > g.K - 4) ? g.K - 4 : k;
+            const unsigned lo = (kc & 4) ? raw[2] : raw[0], hi = (kc & 4) ? raw[3] : raw[1];
+            if (g.norm_elem == ELEM_BF16)
+                return (f32x4){__uint_as_float(lo << 16), __uint_as_float(lo & 0xffff0000u), __uint_as_float(hi << 16), __uint_as_float(hi & 0xffff0000u)};
+            return (f32x4){f16_bits_to_f32((uint16_t)(lo & 0xffffu)), f16_bits_to_f32((uint16_t)(lo >> 16)),
+                           f16_bits_to_f32((uint16_t)(hi & 0xffffu)), f16_bits_to_f32((uint16_t)(hi >> 16))};
+        };
+        load_pass(xr[0], wraw[0], 0);
+        if (NPASS > 1) load_pass(xr[1], wraw[1], 1);
+        if (!PREFETCHED) S.prefetch();
         float ssq[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
-            if (p + 1 < NPASS) load_pass(xr[(p + 1) & 1], wr[(p + 1) & 1], p + 1);
+            if (p > 0 && p + 1 < NPASS) load_pass(xr[(p + 1) & 1], wraw[(p + 1) & 1], p + 1);
             const f32x4 (&xp)[8] = xr[p & 1];
-            const f32x4 wp = wr[p & 1];
+            const f32x4 wp = norm4(wraw[p & 1], p);
             const int jn = (nks - p * 8 < 8) ? nks - p * 8 : 8;       // k-steps of this pass (<= 0: none)
             if (jn > 0) {
                 const int k = (ks0 + p * 8) * 32 + lane * 4;
@@ -338,19 +369,34 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
                 if (lane == 0) L.ssq_part[wave * 8 + t] = v;
             }
     } else {
-        // B was packed by an earlier epilogue: only the lanes of the call's tokens load
+        // B was packed by an earlier epilogue.  The lanes of tokens past the call's load token 0's unit (the same cache
+        // lines) and k-steps past the slice repeat its last one; both are zeroed below.
+        const int src_lane = lane_on ? lane : (lane & ~7);
+        const int ks_last = nks > 0 ? ks0 + nks - 1 : (ks0 < g.KT ? ks0 : g.KT - 1);
 #pragma unroll
-        for (int j = 0; j < KSB; ++j) {
-            b[j] = zero;
-            if (lane_on && j < nks) b[j] = Io::ldb((const bf16x8 *)g.B + act_operand_index(ks0 + j, lane, g.KT));
+        for (int j = 0; j < KSB; ++j) b[j] = Io::ldb((const bf16x8 *)g.B + act_operand_index(j < nks ? ks0 + j : ks_last, src_lane, g.KT));
+        // the producer left per-tile sums of squares: wavefront t adds up token t's, in tile order per lane and
+        // then across the lanes (fixed order).  The first 512 tiles' loads are issued before the weights'.
+        const int t = wave;
+        float sq[8];
+        const float *sq_src = g.ssq_in ? g.ssq_in : (const float *)g.B;      // without partial sums: any valid address
+        const int sq_last = g.ssq_in ? g.ssq_tiles - 1 : 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int tile = lane + 64 * i;
+            sq[i] = Io::ld(sq_src + (size_t)(tile < sq_last ? tile : sq_last) * 8 + t);
         }
+        if (!PREFETCHED) S.prefetch();
+#pragma unroll
+        for (int j = 0; j < KSB; ++j)
+            if (!(lane_on && j < nks)) b[j] = zero;
         if (g.ssq_in) {
-            // the producer left per-tile sums of squares: wavefront t adds up token t's, in tile order per lane and
-            // then across the lanes (fixed order)
-            const int t = wave;
             float v = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (t < g.m && lane + 64 * i < g.ssq_tiles) v += sq[i];
             if (t < g.m)
-                for (int i = lane; i < g.ssq_tiles; i += 64) v += Io::ld(g.ssq_in + (size_t)i * 8 + t);
+                for (int i = lane + 512; i < g.ssq_tiles; i += 64) v += Io::ld(g.ssq_in + (size_t)i * 8 + t);
             for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
             if (lane == 0) L.ssq_part[t] = v;
         }
@@ -463,8 +509,8 @@ struct StreamStream {
     bool primed;
 
     __device__ __forceinline__ void init(const GemmArgs &g, int wg, int nwg) {
-        t0 = (int)(((long)g.NT * wg) / nwg);
-        t1 = (int)(((long)g.NT * (wg + 1)) / nwg);
+        t0 = wg * g.tq + (wg < g.tr ? wg : g.tr);
+        t1 = t0 + g.tq + (wg < g.tr ? 1 : 0);
         if (wg >= nwg) t0 = t1 = 0;                // not one of this GEMM's workgroups
         primed = false;
     }

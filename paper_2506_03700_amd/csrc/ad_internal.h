@@ -37,20 +37,25 @@ enum EpiKind : int { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3,
 enum GemmMode : int { GEMM_STREAMED = 0, GEMM_STATIONARY = 1 };
 
 struct GemmArgs {
+    // what a kernel needs before it can issue its first loads comes first (one line of the argument block)
     const void *W;        // packed weights
-    int NT, KT;           // row tiles, k-steps
-    int N, K;             // valid output rows (EPI_SWIGLU: rows of the interleaved gate/up matrix = 2F), valid inputs
-    int m;                // tokens
-    int mode;             // GemmMode
-    int elem;             // ElemKind of the weights: fp32 (three bf16 planes), bf16, or fp16 (fp16 MFMA, fp16 hi/lo activations)
     // activations: either fp32 rows x [m][ldx] (stationary mode; multiplied by norm_w and, in the epilogue, by
     // rsqrt(mean(x^2) + eps) when norm_w is given), or a packed block B
     const float *x;
-    int ldx;
+    const void *B;
     const void *norm_w;
+    int NT, KT;           // row tiles, k-steps
+    int K;                // valid inputs
+    int m;                // tokens
+    int tq, tr;           // row tiles per workgroup: workgroup w of the GEMM's n takes tq tiles, the first tr of them one more
+                          // (set by the launchers for the grid they choose)
+    int ldx;
+    int N;                // valid output rows (EPI_SWIGLU: rows of the interleaved gate/up matrix = 2F)
+    // ---- end of the first line ----
+    int mode;             // GemmMode
+    int elem;             // ElemKind of the weights: fp32 (three bf16 planes), bf16, or fp16 (fp16 MFMA, fp16 hi/lo activations)
     int norm_elem;        // ElemKind of norm_w
     float inv_dim, eps;
-    const void *B;
     int epi;
     // EPI_STORE: out[t*ld + n] = scale_t * acc
     // EPI_RESID: out[t*ld + n] = resid[t*ld + n] + acc
@@ -81,6 +86,10 @@ struct GemmArgs {
     int32_t draft[8];
     int verify;
 };
+
+static_assert(offsetof(GemmArgs, mode) == 64, "GemmArgs: the first line holds the fields needed first");
+// the launchers' partition of a GEMM's NT row tiles over n workgroups
+inline void set_tile_partition(GemmArgs &g, int n) { g.tq = g.NT / n; g.tr = g.NT % n; }
 
 struct RopeArgs {
     float *table;         // [n_pos][half][2] (cos, sin)

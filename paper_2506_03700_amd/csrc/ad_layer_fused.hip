@@ -82,6 +82,7 @@ union FusedLds {
 // NCHMAX: see gemm_stationary (2 covers d_model <= 4096, 3 covers d_model <= 5120)
 template <int DH, int NCHMAX>
 __global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f) {
+    warm_kernel_args<sizeof(FusedArgs)>();
     constexpr int CH = 8, U = 4, NW = kFusedThreads / 64;
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     FusedLds<DH> &L = *reinterpret_cast<FusedLds<DH> *>(lds_raw);
@@ -102,10 +103,9 @@ __global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f) {
 
     // ---- 1. q, k, v = W (RMSNorm(x)) ---------------------------------------------------------------------
     s_qkv.init(f.qkv, wg, f.nwg_qkv);
-    s_qkv.prefetch();
     AttnKv<DH> kv;
     auto pre_attn = [&]() { attn_load_kv<DH, kFusedThreads>(f.attn, wg, kv); };   // the cached K/V block of the first item
-    if (wg < f.nwg_qkv) gemm_stationary<1, CH, NCHMAX, IoAgent, EPI_STORE, false>(f.qkv, s_qkv, L.gemm, NoTail());
+    if (wg < f.nwg_qkv) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_STORE, false, false>(f.qkv, s_qkv, L.gemm, NoTail());   // x was written before the launch: ordinary loads
     stamp();
     if (!bar.sync(false, pre_attn)) return;
     stamp();
@@ -135,7 +135,7 @@ __global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f) {
     // ---- 5. g = silu(Wg b) * (Wu b), b = RMSNorm(x') -----------------------------------------------------------
     s_down.init(f.down, wg, f.nwg_down);
     auto pre_down = [&]() { s_down.prefetch(f.down); };
-    if (wg < f.nwg_gu) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_SWIGLU, false>(f.gu, s_gu, L.gemm, NoTail());
+    if (wg < f.nwg_gu) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_SWIGLU, false, true>(f.gu, s_gu, L.gemm, NoTail());
     stamp();
     if (!bar.sync(true, pre_down)) return;
     stamp();
@@ -163,7 +163,12 @@ int fused_phase_workgroups(int n_tiles, int n_wg) {
     return per < 1 ? 1 : (n_tiles + per - 1) / per;
 }
 
-int launch_layer_fused(const FusedArgs &f, const LaunchCtx &c) {
+int launch_layer_fused(const FusedArgs &f_in, const LaunchCtx &c) {
+    FusedArgs f = f_in;
+    set_tile_partition(f.qkv, f.nwg_qkv);
+    set_tile_partition(f.wo, f.nwg_wo);
+    set_tile_partition(f.gu, f.nwg_gu);
+    set_tile_partition(f.down, f.nwg_down);
     if (f.qkv.mode != GEMM_STATIONARY || f.gu.mode != GEMM_STATIONARY) return (int)hipErrorInvalidValue;
     // the streamed phases run a single round of at most 8 row tiles per workgroup
     if (f.wo.NT > 8 * f.nwg_wo || f.down.NT > 8 * f.nwg_down) return (int)hipErrorInvalidValue;
