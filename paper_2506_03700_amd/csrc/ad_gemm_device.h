@@ -587,13 +587,15 @@ __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NP
                     }
                 }
         };
-        // residual values of this thread's output entries, ahead of the stream
-        float rpre[RP];
+        // residual values of this thread's output entries (and the next GEMM's norm weights for them), ahead of the stream
+        float rpre[RP], npre[RP];
         if (epi == EPI_RESID) {
 #pragma unroll
             for (int j = 0; j < RP; ++j) {
                 const int idx = tid + j * NTHREADS, T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15, n = (ta + T) * 16 + i;
-                rpre[j] = (idx < nt * 128 && t < g.m && n < g.N) ? Io::ld(g.resid + (size_t)t * g.ld + n) : 0.f;
+                const bool on = idx < nt * 128 && t < g.m && n < g.N;
+                rpre[j] = on ? Io::ld(g.resid + (size_t)t * g.ld + n) : 0.f;
+                npre[j] = (on && g.Bnext) ? load_w(g.next_norm_w, g.next_norm_elem, (size_t)n) : 0.f;
             }
         }
         const bool primed = S.primed && ta == t0;     // the A tiles of batches 0 and 1 are in flight already
@@ -654,7 +656,7 @@ __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NP
                 if (g.Bnext) {
                     // input of the next GEMM: y * norm weight, packed; and this tile's share of sum(y^2) per token
                     // (the 16 outputs of a (tile, token) pair sit in 16 neighbouring lanes)
-                    if (on) store_act_io<Io, F16>((uint16_t *)g.Bnext, g.Bnext_KT, n, t, y * load_w(g.next_norm_w, g.next_norm_elem, (size_t)n));
+                    if (on) store_act_io<Io, F16>((uint16_t *)g.Bnext, g.Bnext_KT, n, t, y * npre[j]);
                     float q = y * y;
                     q += __shfl_xor(q, 8);
                     q += __shfl_xor(q, 4);

@@ -83,7 +83,7 @@ union FusedLds {
 template <int DH, int NCHMAX>
 __global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f) {
     warm_kernel_args<sizeof(FusedArgs)>();
-    constexpr int CH = 8, U = 4, NW = kFusedThreads / 64;
+    constexpr int CH = 8, U = 8, NW = kFusedThreads / 64;
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     FusedLds<DH> &L = *reinterpret_cast<FusedLds<DH> *>(lds_raw);
     __shared__ int bar_ok;
