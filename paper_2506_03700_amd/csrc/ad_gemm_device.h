@@ -514,28 +514,30 @@ struct StreamStream {
         if (wg >= nwg) t0 = t1 = 0;                // not one of this GEMM's workgroups
         primed = false;
     }
-    // batch [x, x + U) of the range that ends at xb; entries past the end repeat the last pair (their products
-    // are skipped), so that the buffer is always filled by straight-line loads into fixed registers
-    static __device__ __forceinline__ void load_a(bf16x8 (&a)[U][NPL], const bf16x8 *W, unsigned p, int x, int xb) {
-        if (x >= xb) return;
-        const int last = xb - 1 - x;
+    // Batch [x, x + U) of (tile, k-step) pairs of a round whose first pair sits at unit offset `base`: entries past
+    // `x_ok` (the wavefront's last pair, or any valid pair of the round if it has none) repeat that pair -- the same
+    // cache lines, products skipped -- so that every call issues exactly U * NPL loads into fixed registers and the
+    // code around it can wait for an earlier batch without waiting for this one.
+    static __device__ __forceinline__ void load_a(bf16x8 (&a)[U][NPL], const bf16x8 *W, unsigned base, int x, int x_ok) {
 #pragma unroll
         for (int j = 0; j < U; ++j) {
-            const int jj = j < last ? j : last;
+            const int xx = x + j < x_ok ? x + j : x_ok;
 #pragma unroll
-            for (int q = 0; q < NPL; ++q) a[j][q] = load_tile(W, p + (unsigned)(jj * NPL + q) * 64u);
+            for (int q = 0; q < NPL; ++q) a[j][q] = load_tile(W, base + (unsigned)(xx * NPL + q) * 64u);
         }
     }
+    static __device__ __forceinline__ int valid_pair(int xa, int xb, int tot) { return xb > xa ? xb - 1 : (xa < tot ? xa : tot - 1); }
     // the A tiles of the first two batches of the first round go in flight
     __device__ __forceinline__ void prefetch(const GemmArgs &g) {
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         if (t0 < t1) {
             const int tb = (t1 < t0 + 8) ? t1 : t0 + 8, tot = (tb - t0) * g.KT;
             const int xa = part_start(tot, wave, NW), xb = part_start(tot, wave + 1, NW);
-            unsigned pa = (unsigned)(((size_t)t0 * g.KT + xa) * NPL * 64 + lane);
-            asm volatile("" : "+v"(pa));     // keep the address arithmetic of these loads here (see StatStream)
-            load_a(a0, (const bf16x8 *)g.W, pa, xa, xb);
-            load_a(a1, (const bf16x8 *)g.W, pa + U * NPL * 64u, xa + U, xb);
+            unsigned base = (unsigned)((size_t)t0 * g.KT * NPL * 64 + lane);
+            asm volatile("" : "+v"(base));     // keep the address arithmetic of these loads here (see StatStream)
+            const int x_ok = valid_pair(xa, xb, tot);
+            load_a(a0, (const bf16x8 *)g.W, base, xa, x_ok);
+            load_a(a1, (const bf16x8 *)g.W, base, xa + U, x_ok);
         }
         primed = true;
     }
@@ -562,23 +564,31 @@ __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NP
         int tile = xa / KT, ks = xa % KT;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         const bf16x8 *W = (const bf16x8 *)g.W;
-        unsigned pa = (unsigned)(((size_t)ta * KT + xa) * NPL * 64 + lane);
+        const unsigned base = (unsigned)((size_t)ta * KT * NPL * 64 + lane);
+        const int x_ok = StreamStream<NPL, U, NW>::valid_pair(xa, xb, tot);
         bf16x8 b0[U], b1[U];
+        // the B operands of batch [x, x + U), whose first pair is k-step ks_at of its tile: every call issues exactly U
+        // loads (entries past the range read unit 0 of the block and are never multiplied; lanes of tokens past the
+        // call's read token 0's unit and are zeroed where the operand is used -- not here, where overwriting the
+        // register would have to wait for the load)
+        const int src_lane = bact ? lane : (lane & ~7);
         auto load_b = [&](bf16x8 (&b)[U], int x, int ks_at) {
 #pragma unroll
-            for (int j = 0; j < U; ++j)
-                if (x + j < xb) {
-                    int kk = ks_at + j;
-                    while (kk >= KT) kk -= KT;
-                    b[j] = bact ? Io::ldb(B + act_operand_index(kk, lane, KT)) : zero;
-                }
+            for (int j = 0; j < U; ++j) {
+                int kk = ks_at + j;
+                if (KT >= U) kk -= (kk >= KT) ? KT : 0;
+                else kk %= KT;
+                const bool on = x + j < xb;
+                b[j] = Io::ldb(B + (on ? act_operand_index(kk, src_lane, KT) : 0));
+            }
         };
         auto mma = [&](const bf16x8 (&a)[U][NPL], const bf16x8 (&b)[U], int x) {
 #pragma unroll
             for (int j = 0; j < U; ++j)
                 if (x + j < xb) {
+                    const bf16x8 bb = bact ? b[j] : zero;
 #pragma unroll
-                    for (int q = 0; q < NPL; ++q) acc = mma16<F16>(a[j][q], b[j], acc);
+                    for (int q = 0; q < NPL; ++q) acc = mma16<F16>(a[j][q], bb, acc);
                     if (++ks == KT) {
                         *(f32x4 *)(L.slots + (wave + tile) * 256 + (lane & 15) * 16 + (lane >> 4) * 4) = acc;
                         acc = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -598,28 +608,46 @@ __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NP
                 npre[j] = (on && g.Bnext) ? load_w(g.next_norm_w, g.next_norm_elem, (size_t)n) : 0.f;
             }
         }
+        // Two batches are in flight while a third is multiplied: a0/b0 hold batch x, a1/b1 batch x + U.  While four
+        // whole batches remain, every load of the loop is in range and unconditional, so each multiplication waits for
+        // its own operands only; the last batches take their loads under conditions (no duplicate traffic at the end).
         const bool primed = S.primed && ta == t0;     // the A tiles of batches 0 and 1 are in flight already
-        if (xa < xb) {
-            if (!primed) S.load_a(S.a0, W, pa, xa, xb);
-            load_b(b0, xa, ks);
+        auto wrap = [&](int k) { if (KT >= U) return k - (k >= KT ? KT : 0); return k % KT; };
+        int ks_b = ks;                                  // k-step of the first pair of the batch whose B operands load next
+        if (!primed) {
+            S.load_a(S.a0, W, base, xa, x_ok);
+            S.load_a(S.a1, W, base, xa + U, x_ok);
+        }
+        load_b(b0, xa, ks_b);
+        ks_b = wrap(ks_b + U);
+        load_b(b1, xa + U, ks_b);
+        ks_b = wrap(ks_b + U);
+        int x = xa;
+#pragma nounroll
+        for (; x + 4 * U <= xb; x += 2 * U) {
+            mma(S.a0, b0, x);
+            S.load_a(S.a0, W, base, x + 2 * U, x_ok);
+            load_b(b0, x + 2 * U, ks_b);
+            ks_b = wrap(ks_b + U);
+            mma(S.a1, b1, x + U);
+            S.load_a(S.a1, W, base, x + 3 * U, x_ok);
+            load_b(b1, x + 3 * U, ks_b);
+            ks_b = wrap(ks_b + U);
         }
 #pragma nounroll
-        for (int x = xa; x < xb; x += 2 * U) {
-            int ks_next = ks + U;
-            while (ks_next >= KT) ks_next -= KT;
-            if (x + U < xb) {
-                if (!(primed && x == xa)) S.load_a(S.a1, W, pa + U * NPL * 64u, x + U, xb);
-                load_b(b1, x + U, ks_next);
-            }
+        for (; x < xb; x += 2 * U) {
             mma(S.a0, b0, x);
-            int ks_next2 = ks + U;     // ks has advanced by the first batch
-            while (ks_next2 >= KT) ks_next2 -= KT;
             if (x + 2 * U < xb) {
-                S.load_a(S.a0, W, pa + 2u * U * NPL * 64u, x + 2 * U, xb);
-                load_b(b0, x + 2 * U, ks_next2);
+                S.load_a(S.a0, W, base, x + 2 * U, x_ok);
+                load_b(b0, x + 2 * U, ks_b);
+                ks_b = wrap(ks_b + U);
             }
-            if (x + U < xb) mma(S.a1, b1, x + U);
-            pa += 2u * U * NPL * 64u;
+            mma(S.a1, b1, x + U);
+            if (x + 3 * U < xb) {
+                S.load_a(S.a1, W, base, x + 3 * U, x_ok);
+                load_b(b1, x + 3 * U, ks_b);
+                ks_b = wrap(ks_b + U);
+            }
         }
         if (ks != 0) *(f32x4 *)(L.slots + (wave + tile) * 256 + (lane & 15) * 16 + (lane >> 4) * 4) = acc;
         __builtin_amdgcn_sched_barrier(0);  // keep the tail's loads out of the stream's register live ranges
