@@ -473,9 +473,22 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
                 if ((t - t0) % kTilesPerRound == kTilesPerRound - 1 && t + 1 < t1) finish_round(t + 1);
             }
         };
+        // chunks c and c+1 are in a0 and a1 (in flight or landed); each buffer is refilled as soon as it is consumed.
+        // While four chunks remain the refills are unconditional, so that the number of loads behind a chunk is
+        // known where it is multiplied and only its own loads are waited for (with a refill under a condition the
+        // wait has to allow for its absence, and then also covers the refill just issued: one chunk in flight, not two).
+        int c = 0;
 #pragma nounroll
-        for (int c = 0; c < total; c += 2) {
-            // chunks c and c+1 are in a0 and a1 (in flight or landed); refill each buffer as soon as it is consumed
+        for (; c + 4 <= total; c += 2) {
+            mma_chunk(S.a0, c);
+            load_chunk<NPL, CH>(S.a0, S.W, S.chunk_ptr(c + 2), S.chunk_len(c + 2));
+            tile_done(c);
+            mma_chunk(S.a1, c + 1);
+            load_chunk<NPL, CH>(S.a1, S.W, S.chunk_ptr(c + 3), S.chunk_len(c + 3));
+            tile_done(c + 1);
+        }
+#pragma nounroll
+        for (; c < total; c += 2) {
             mma_chunk(S.a0, c);
             if (c + 2 < total) load_chunk<NPL, CH>(S.a0, S.W, S.chunk_ptr(c + 2), S.chunk_len(c + 2));
             tile_done(c);
