@@ -5,6 +5,7 @@
  * The library runs, on one GPU and at batch 1, the three operations Algorithm 1 is made of, plus the
  * loop itself:
  *   ad_layer_step   "update KV cache at layer l by processing all tokens in P[l] in parallel"
+ *                   (ad_layer_steps: a range of consecutive layers over the same rows)
  *   ad_exit_head    Eq. 1 at temperature 0: greedy token of an intermediate-layer head and its probability
  *   ad_verify       Eq. 2 at temperature 0: accept the early predictions that equal the final layer's
  *                   greedy tokens, replace the first that does not
@@ -111,7 +112,15 @@ ad_status ad_embed(const ad_model *, const int32_t *tokens, int32_t m, void *hid
 ad_status ad_layer_step(const ad_model *, ad_kv *, int32_t layer, void *hidden, const int32_t *pos, int32_t m,
                         void *stream);
 
-/* How ad_layer_step runs.  AD_LAYER_KERNELS (the default): one kernel per phase (QKV, attention, fold, Wo,
+/* The same rows through layers first_layer .. first_layer + n_layers - 1 one after the other: the stretch of
+ * Algorithm 1's layer loop between two points where the set of pending rows can change (an exit head, or the layer at
+ * which earlier tokens' deferred rows join).  Equivalent to n_layers calls of ad_layer_step with the same hidden, pos
+ * and m (so pos[0] must equal the cache length of every layer in the range); in AD_LAYER_FUSED mode the whole range
+ * is one kernel launch.  Errors as ad_layer_step; a range that leaves 1..n_layers is AD_ERANGE. */
+ad_status ad_layer_steps(const ad_model *, ad_kv *, int32_t first_layer, int32_t n_layers, void *hidden, const int32_t *pos,
+                         int32_t m, void *stream);
+
+/* How ad_layer_step and ad_layer_steps run.  AD_LAYER_KERNELS (the default): one kernel per phase (QKV, attention, fold, Wo,
  * gate/up, down).  AD_LAYER_FUSED (bf16 models with d_model <= 5120 only): one persistent kernel with one workgroup per compute unit
  * and grid barriers between the phases; it needs the device to itself while it runs (no other kernel of this
  * process may occupy compute units at the same time, or a barrier wait can time out; the call after such a

@@ -24,7 +24,7 @@ AD_LAYER_KERNELS, AD_LAYER_FUSED = 0, 1
 AD_PROF_GEMM, AD_PROF_LAYER = 0, 1
 
 EXPORTS = ["ad_workspace_bytes", "ad_model_create", "ad_model_destroy", "ad_kv_bytes", "ad_kv_create", "ad_kv_destroy",
-           "ad_kv_len", "ad_kv_set_len", "ad_kv_truncate", "ad_embed", "ad_layer_step", "ad_set_layer_mode", "ad_exit_head", "ad_verify",
+           "ad_kv_len", "ad_kv_set_len", "ad_kv_truncate", "ad_embed", "ad_layer_step", "ad_layer_steps", "ad_set_layer_mode", "ad_exit_head", "ad_verify",
            "ad_head_logits", "ad_sample_logits", "ad_verify_sampled", "ad_generate", "ad_layer_trace", "ad_profile_start", "ad_profile_stop", "ad_last_error", "ad_version"]
 
 
@@ -95,6 +95,7 @@ def lib() -> C.CDLL:
         L.ad_kv_truncate.argtypes = [P, i32]
         L.ad_embed.argtypes = [P, P, i32, P, P]
         L.ad_layer_step.argtypes = [P, P, i32, P, P, i32, P]
+        L.ad_layer_steps.argtypes = [P, P, i32, i32, P, P, i32, P]
         L.ad_exit_head.argtypes = [P, i32, P, P, P, P]
         L.ad_verify.argtypes = [P, P, P, i32, P, P, P, P]
         L.ad_head_logits.argtypes = [P, i32, P, i32, P, P]
@@ -261,6 +262,15 @@ class Model:
         assert hidden.dtype == torch.float32 and hidden.is_contiguous() and hidden.device == self.device
         assert hidden.shape == (p.size, self.shape.d_model)
         _check(self.L.ad_layer_step(self.model, self.kv, layer, C.c_void_p(hidden.data_ptr()), p.ctypes.data, p.size, _stream_ptr(torch)))
+
+    def ad_layer_steps(self, first_layer: int, n_layers: int, hidden, pos: Sequence[int]) -> None:
+        """Layers first_layer .. first_layer + n_layers - 1 over the same rows, in place on `hidden`."""
+        torch = self.torch
+        p = np.ascontiguousarray(pos, dtype=np.int32)
+        assert hidden.dtype == torch.float32 and hidden.is_contiguous() and hidden.device == self.device
+        assert hidden.shape == (p.size, self.shape.d_model)
+        _check(self.L.ad_layer_steps(self.model, self.kv, first_layer, n_layers, C.c_void_p(hidden.data_ptr()), p.ctypes.data, p.size,
+                                     _stream_ptr(torch)))
 
     def ad_exit_head(self, layer: int, hidden_row):
         torch = self.torch

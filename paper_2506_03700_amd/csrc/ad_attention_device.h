@@ -47,9 +47,9 @@ struct AttnKv {
 // Loads wavefront (tid >> 6) & 3's block of 32 cached positions of work item `item` (nothing if the block is
 // empty or the wavefront has no query rows).  Does not depend on the queries, so it can be issued early.
 template <int DH, int NTHREADS>
-__device__ __forceinline__ void attn_load_kv(const AttnArgs &a, int item, AttnKv<DH> &kv) {
+__device__ __forceinline__ void attn_load_kv(const AttnArgs &a, int item, AttnKv<DH> &kv, long long kv_off = 0) {
     constexpr int KS = DH / 32, DT = DH / 16;
-    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, rh = tid >> 8;
+    const int tid = thread_index(), lane = tid & 63, wave = (tid >> 6) & 3, rh = tid >> 8;
     const int n = lane & 15, gq = lane >> 4;
     if (item >= a.Hkv * a.S) return;
     const int g = item / a.S, s = item % a.S;
@@ -57,8 +57,8 @@ __device__ __forceinline__ void attn_load_kv(const AttnArgs &a, int item, AttnKv
     const int nbc = (c1 > c0) ? (c1 - c0 + 31) / 32 : 0;
     const int R = (a.Hq / a.Hkv) * a.m;
     if (wave >= nbc || R <= rh * 8) return;
-    const uint16_t *Kg = (const uint16_t *)a.Kc + (size_t)g * a.stride * DH;
-    const uint16_t *Vg = (const uint16_t *)a.Vc + (size_t)g * DH * a.stride;
+    const uint16_t *Kg = (const uint16_t *)((const char *)a.Kc + kv_off) + (size_t)g * a.stride * DH;
+    const uint16_t *Vg = (const uint16_t *)((const char *)a.Vc + kv_off) + (size_t)g * DH * a.stride;
     const int kb0 = c0 + wave * 32;
 #pragma unroll
     for (int aa = 0; aa < 2; ++aa) {
@@ -75,10 +75,11 @@ __device__ __forceinline__ void attn_load_kv(const AttnArgs &a, int item, AttnKv
 // first item, wg.
 // F16: the cache, and the 16-bit halves of the queries and probabilities, are fp16 (else bf16).
 template <int DH, int NTHREADS, class Io, bool F16>
-__device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<DH> &L, int wg, int nwg, AttnKv<DH> &kv, bool preloaded) {
+__device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<DH> &L, int wg, int nwg, AttnKv<DH> &kv, bool preloaded,
+                                                long long kv_off = 0) {
     constexpr int KS = DH / 32, DT = DH / 16, half = DH / 2, PR = DH + 2, PL = DH + 4;
     constexpr int NRH = NTHREADS / 256;      // wavefronts per key block
-    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, rh = tid >> 8;
+    const int tid = thread_index(), lane = tid & 63, wave = (tid >> 6) & 3, rh = tid >> 8;
     const int n = lane & 15, gq = lane >> 4;
     const int G = a.Hq / a.Hkv, R = G * a.m;
     const int n_items = a.Hkv * a.S;
@@ -90,8 +91,8 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
         const int nc = (c1 > c0) ? c1 - c0 : 0;
         const bool last = (s == a.S - 1);
         const int nbc = (nc + 31) / 32;
-        uint16_t *Kg = (uint16_t *)a.Kc + (size_t)g * a.stride * DH;
-        uint16_t *Vg = (uint16_t *)a.Vc + (size_t)g * DH * a.stride;
+        uint16_t *Kg = (uint16_t *)((char *)a.Kc + kv_off) + (size_t)g * a.stride * DH;
+        uint16_t *Vg = (uint16_t *)((char *)a.Vc + kv_off) + (size_t)g * DH * a.stride;
 
         if (last) {
             // the call's own rows: rotate k, round to bf16, append to the cache, keep a copy in LDS
@@ -122,7 +123,7 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
             const int nblk = (nr + 7) / 8;
             // this wavefront's cached block goes in flight first: it does not depend on the queries (a later pass
             // over more rows loads it again, from L2: the registers are reused for the call's own rows below)
-            if (!(preloaded && item == wg && r0 == 0)) attn_load_kv<DH, NTHREADS>(a, item, kv);
+            if (!(preloaded && item == wg && r0 == 0)) attn_load_kv<DH, NTHREADS>(a, item, kv, kv_off);
             // queries: rotate, scale, split hi/lo, store in B-operand order.  Each thread first issues the loads of
             // all its elements (at most 8 for 32 rows of 128 dims), then does the arithmetic.
             constexpr int QIT = (kAttnRowsPerPass * half + NTHREADS - 1) / NTHREADS;
@@ -319,7 +320,7 @@ __device__ __forceinline__ void attn_combine_row(const AttnArgs &a, int row /* 0
     constexpr int NB = 32;                             // splits whose rows are in flight together
     const int DH = a.dh, PR = DH + 2, S = a.S;
     const int G = a.Hq / a.Hkv, R = G * a.m;
-    const int lane = threadIdx.x & 63;
+    const int lane = thread_index() & 63;
     const int g = row / R, r = row % R, t = r / G, hq = g * G + r % G;
     const float *base = a.part + ((size_t)g * S * R + r) * PR;
     const size_t sstride = (size_t)R * PR;

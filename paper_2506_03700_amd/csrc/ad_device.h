@@ -33,6 +33,29 @@ __device__ __forceinline__ uint16_t f32_to_f16_bits(float x) { return __builtin_
 // come one after the other on the path to the kernel's first useful load.  Reading one word of every line of the
 // block at the kernel's entry (and waiting for them together) overlaps them all: later argument loads hit in the
 // scalar cache.  BYTES: the size of the kernel's explicit arguments; nothing beyond them is read.
+// threadIdx.x as a value the compiler computes afresh at every call.  The phases of a kernel that loops over layers
+// derive their lane-dependent addresses from it: derived from threadIdx.x itself they would all count as loop
+// invariants, be computed ahead of the loop and be kept in registers (spilled, there are hundreds) through every phase.
+__device__ __forceinline__ int thread_index() {
+    int t = (int)threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
+}
+
+// Declares the registers of an array to hold nothing that is still needed (no instruction is emitted).  Inside a
+// loop, an array that is only filled under a condition would otherwise carry its contents of the previous turn
+// all the way round the loop.
+template <class T, int A>
+__device__ __forceinline__ void forget(T (&r)[A]) {
+#pragma unroll
+    for (int i = 0; i < A; ++i) asm volatile("" : "=v"(r[i]));
+}
+template <class T, int A, int B>
+__device__ __forceinline__ void forget(T (&r)[A][B]) {
+#pragma unroll
+    for (int i = 0; i < A; ++i) forget(r[i]);
+}
+
 template <int BYTES>
 __device__ __forceinline__ void warm_kernel_args() {
     typedef const __attribute__((address_space(4))) uint32_t *kptr;

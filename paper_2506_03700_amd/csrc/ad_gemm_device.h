@@ -217,8 +217,8 @@ struct StatStream {
     unsigned wbase, tstride;       // 16-byte units
     int t0, t1, ks0, nks, nch, total;
 
-    __device__ __forceinline__ void init(const GemmArgs &g, int wg, int nwg) {
-        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __device__ __forceinline__ void init(const GemmArgs &g, int wg, int nwg, long long w_off = 0) {
+        const int tid_ = thread_index(), lane = tid_ & 63, wave = tid_ >> 6;
         t0 = wg * g.tq + (wg < g.tr ? wg : g.tr);
         t1 = t0 + g.tq + (wg < g.tr ? 1 : 0);
         if (wg >= nwg) t0 = t1 = 0;                // not one of this GEMM's workgroups
@@ -226,7 +226,7 @@ struct StatStream {
         nks = part_start(g.KT, wave + 1, kStatWaves) - ks0;
         nch = (nks + CH - 1) / CH;                 // chunks per tile (0 if this wavefront has no K slice)
         total = (t1 - t0) * nch;                   // chunks in this wavefront's stream
-        W = (const bf16x8 *)g.W;
+        W = (const bf16x8 *)((const char *)g.W + w_off);
         wbase = (unsigned)(((size_t)t0 * g.KT + ks0) * NPL * 64 + lane);
         tstride = (unsigned)g.KT * NPL * 64u;
     }
@@ -239,7 +239,7 @@ struct StatStream {
         // the address arithmetic of these loads stays here (behind an opaque copy of the base offset) instead of
         // being hoisted to where the caller's own stream needs the registers
         asm volatile("" : "+v"(wbase));
-        const unsigned lane = threadIdx.x & 63;
+        const unsigned lane = (unsigned)thread_index() & 63;
         const unsigned p0 = total > 0 ? chunk_ptr(0) : lane, p1 = total > 1 ? chunk_ptr(1) : lane;
         const int n0 = total > 0 ? chunk_len(0) : 1, n1 = total > 1 ? chunk_len(1) : 1;
         load_chunk_clamped(a0, p0, n0);
@@ -266,10 +266,10 @@ struct StatStream {
 // NCHMAX: most chunks per tile and wavefront this instance covers (the B slice takes NCHMAX * CH registers x 4).
 // F16: the weights and the 16-bit halves of the activations are fp16 (else bf16).
 template <int NPL, int CH, int NCHMAX, class Io, int EPI, bool F16, bool PREFETCHED, class Tail>
-__device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NPL, CH> &S, GemmLds &L, Tail tail) {
+__device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NPL, CH> &S, GemmLds &L, Tail tail, long long w_off = 0) {
     constexpr int KSB = NCHMAX * CH;   // B registers cover whole chunks
     constexpr int kWaves = kStatWaves, kThreads = kStatThreads;         // this mode's workgroup shape
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = thread_index(), lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, gq = lane >> 4, t_lane = n & 7;
     const int t0 = S.t0, t1 = S.t1, ks0 = S.ks0, nks = S.nks, nch = S.nch, total = S.total;
     const int epi = EPI >= 0 ? EPI : g.epi;
@@ -298,7 +298,7 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
         f32x4 xr[2][8];
         u32x4 wraw[2];
         const bool w16 = g.norm_elem != ELEM_F32;
-        const char *wsrc = g.norm_w ? (const char *)g.norm_w : (const char *)g.x;     // without a norm vector: any valid address
+        const char *wsrc = g.norm_w ? (const char *)g.norm_w + w_off : (const char *)g.x;     // without a norm vector: any valid address
         auto load_pass = [&](f32x4 (&xp)[8], u32x4 &wp, int p) {
             const int k = (ks0 + p * 8) * 32 + lane * 4;
             const int kc = (k > g.K - 4) ? g.K - 4 : k;              // clamped address, masked result
@@ -541,16 +541,17 @@ struct StreamStream {
     }
     static __device__ __forceinline__ int valid_pair(int xa, int xb, int tot) { return xb > xa ? xb - 1 : (xa < tot ? xa : tot - 1); }
     // the A tiles of the first two batches of the first round go in flight
-    __device__ __forceinline__ void prefetch(const GemmArgs &g) {
-        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __device__ __forceinline__ void prefetch(const GemmArgs &g, long long w_off = 0) {
+        const int tid_ = thread_index(), lane = tid_ & 63, wave = tid_ >> 6;
         if (t0 < t1) {
             const int tb = (t1 < t0 + 8) ? t1 : t0 + 8, tot = (tb - t0) * g.KT;
             const int xa = part_start(tot, wave, NW), xb = part_start(tot, wave + 1, NW);
             unsigned base = (unsigned)((size_t)t0 * g.KT * NPL * 64 + lane);
             asm volatile("" : "+v"(base));     // keep the address arithmetic of these loads here (see StatStream)
             const int x_ok = valid_pair(xa, xb, tot);
-            load_a(a0, (const bf16x8 *)g.W, base, xa, x_ok);
-            load_a(a1, (const bf16x8 *)g.W, base, xa + U, x_ok);
+            const bf16x8 *W = (const bf16x8 *)((const char *)g.W + w_off);
+            load_a(a0, W, base, xa, x_ok);
+            load_a(a1, W, base, xa + U, x_ok);
         }
         primed = true;
     }
@@ -559,10 +560,10 @@ struct StreamStream {
 // ONE_ROUND: the caller guarantees at most 8 row tiles per workgroup (then there is no loop over rounds, and the
 // tail runs with the stream's buffers dead).
 template <int NPL, int U, int NW, class Io, int EPI, bool ONE_ROUND, bool F16, class Tail>
-__device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NPL, U, NW> &S, GemmLds &L, Tail tail) {
+__device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NPL, U, NW> &S, GemmLds &L, Tail tail, long long w_off = 0) {
     constexpr int NTHREADS = NW * 64;
     constexpr int RP = (kTilesPerRound * 128 + NTHREADS - 1) / NTHREADS;   // residual entries per thread and round
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = thread_index(), lane = tid & 63, wave = tid >> 6;
     const int t0 = S.t0, t1 = S.t1;
     const int epi = EPI >= 0 ? EPI : g.epi;
     if (tid < 8) L.scale[tid] = 1.0f;
@@ -576,7 +577,7 @@ __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NP
         const int xa = part_start(tot, wave, NW), xb = part_start(tot, wave + 1, NW);
         int tile = xa / KT, ks = xa % KT;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        const bf16x8 *W = (const bf16x8 *)g.W;
+        const bf16x8 *W = (const bf16x8 *)((const char *)g.W + w_off);
         const unsigned base = (unsigned)((size_t)ta * KT * NPL * 64 + lane);
         const int x_ok = StreamStream<NPL, U, NW>::valid_pair(xa, xb, tot);
         bf16x8 b0[U], b1[U];
@@ -618,7 +619,7 @@ __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NP
                 const int idx = tid + j * NTHREADS, T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15, n = (ta + T) * 16 + i;
                 const bool on = idx < nt * 128 && t < g.m && n < g.N;
                 rpre[j] = on ? Io::ld(g.resid + (size_t)t * g.ld + n) : 0.f;
-                npre[j] = (on && g.Bnext) ? load_w(g.next_norm_w, g.next_norm_elem, (size_t)n) : 0.f;
+                npre[j] = (on && g.Bnext) ? load_w((const char *)g.next_norm_w + w_off, g.next_norm_elem, (size_t)n) : 0.f;
             }
         }
         // Two batches are in flight while a third is multiplied: a0/b0 hold batch x, a1/b1 batch x + U.  While four

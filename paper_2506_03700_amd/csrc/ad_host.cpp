@@ -415,17 +415,28 @@ static int64_t layer_step_bytes(const ad_config &c, int32_t ctx, int32_t m) {
     return w + 2 * dkv * s * ((int64_t)ctx + m) + 2 * dkv * s * m;
 }
 
-ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidden, const int32_t *pos, int32_t n, void *stream) {
-    if (!m || !kv || !hidden || !pos) return (ad_status)fail(AD_EINVAL, "ad_layer_step: null argument");
-    if (kv->model != m) return (ad_status)fail(AD_EINVAL, "ad_layer_step: cache belongs to another model");
+// Layers layer .. layer + count - 1 over the same rows.  The fused mode runs them in one launch (the layers' weights
+// and caches are laid out at a constant distance from one layer to the next); otherwise one layer at a time.
+static int layer_steps(const ad_model *m, ad_kv *kv, int32_t layer, int32_t count, void *hidden, const int32_t *pos, int32_t n,
+                       void *stream, const char *who) {
+    if (!m || !kv || !hidden || !pos) return fail(AD_EINVAL, "%s: null argument", who);
+    if (kv->model != m) return fail(AD_EINVAL, "%s: cache belongs to another model", who);
     const ad_config &c = m->cfg;
-    if (layer < 1 || layer > c.n_layers) return (ad_status)fail(AD_ERANGE, "ad_layer_step: layer %d outside 1..%d", layer, c.n_layers);
-    if (n < 1 || n > c.m_max) return (ad_status)fail(AD_ERANGE, "ad_layer_step: m = %d outside 1..%d", n, c.m_max);
+    if (count < 1 || layer < 1 || layer > c.n_layers - (count - 1))
+        return fail(AD_ERANGE, "%s: layers %d..%d outside 1..%d", who, layer, layer + count - 1, c.n_layers);
+    if (n < 1 || n > c.m_max) return fail(AD_ERANGE, "%s: m = %d outside 1..%d", who, n, c.m_max);
     for (int i = 1; i < n; ++i)
-        if (pos[i] != pos[0] + i) return (ad_status)fail(AD_ESTATE, "ad_layer_step: positions are not consecutive");
-    if (pos[0] != kv->len[layer - 1])
-        return (ad_status)fail(AD_ESTATE, "ad_layer_step: pos[0] = %d but layer %d's cache ends at %d", pos[0], layer, kv->len[layer - 1]);
-    if (pos[0] < 0 || pos[n - 1] >= kv->max_pos) return (ad_status)fail(AD_ERANGE, "ad_layer_step: position %d beyond max_pos %d", pos[n - 1], kv->max_pos);
+        if (pos[i] != pos[0] + i) return fail(AD_ESTATE, "%s: positions are not consecutive", who);
+    for (int32_t l = layer; l < layer + count; ++l)
+        if (pos[0] != kv->len[l - 1]) return fail(AD_ESTATE, "%s: pos[0] = %d but layer %d's cache ends at %d", who, pos[0], l, kv->len[l - 1]);
+    if (pos[0] < 0 || pos[n - 1] >= kv->max_pos) return fail(AD_ERANGE, "%s: position %d beyond max_pos %d", who, pos[n - 1], kv->max_pos);
+    if (count > 1 && m->layer_mode != AD_LAYER_FUSED) {
+        for (int32_t l = layer; l < layer + count; ++l) {
+            const int rc1 = layer_steps(m, kv, l, 1, hidden, pos, n, stream, who);
+            if (rc1) return rc1;
+        }
+        return AD_OK;
+    }
 
     const Layout &L = m->lay;
     const LayerPacked &lp = m->layers[layer - 1];
@@ -472,28 +483,46 @@ ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidde
 
     if (m->layer_mode == AD_LAYER_FUSED) {
         // all five steps in one persistent kernel
-        if ((rc = fused_health(m, stream))) return (ad_status)rc;
+        if ((rc = fused_health(m, stream))) return rc;
         FusedArgs f;
         f.qkv = gq; f.wo = go; f.gu = gg; f.down = gd; f.attn = a;
+        f.n_layers = count;
+        f.w_stride = count > 1 ? (long long)(m->layers[layer].wqkv - lp.wqkv) : 0;
+        f.kv_stride = (long long)kv->layer_bytes;
+        for (int32_t l = layer; l < layer + count - 1; ++l) {   // layers l and l + 1 (1-based): records at one distance
+            const LayerPacked &p0 = m->layers[l - 1], &p1 = m->layers[l];
+            if (p1.wqkv - p0.wqkv != f.w_stride || p1.wo - p0.wo != f.w_stride || p1.wgu - p0.wgu != f.w_stride || p1.wd - p0.wd != f.w_stride ||
+                p1.attn_norm - p0.attn_norm != f.w_stride || p1.ffn_norm - p0.ffn_norm != f.w_stride)
+                return fail(AD_ESTATE, "%s: layer weights are not laid out at a constant distance", who);
+        }
         f.nwg_qkv = fused_phase_workgroups(gq.NT, m->n_wg);
         f.nwg_wo = fused_phase_workgroups(go.NT, m->n_wg);
         f.nwg_gu = fused_phase_workgroups(gg.NT, m->n_wg);
         f.nwg_down = fused_phase_workgroups(gd.NT, m->n_wg);
         f.ctr = m->bar_ctr; f.round0 = m->bar_round; f.abort_flag = m->bar_abort; f.trace = m->layer_trace;
-        const bool sample = profile_begin(m->prof, AD_PROF_LAYER, layer_step_bytes(c, pos[0], n), stream);
+        const bool sample = profile_begin(m->prof, AD_PROF_LAYER, count * layer_step_bytes(c, pos[0], n), stream);
         rc = launch_layer_fused(f, ctx);
         if (sample) (void)event_record(m->prof.stop.back(), stream);
-        if (rc) return (ad_status)hip_fail(rc, "ad_layer_step: fused kernel");
-        m->bar_round += kFusedBarriers;
+        if (rc) return hip_fail(rc, "layer step: fused kernel");
+        m->bar_round += fused_barriers(count);
     } else {
-        if ((rc = gemm(m, gq, L.nqkv, L.d, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: qkv");
-        if ((rc = launch_attn(a, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: attention");
-        if ((rc = gemm(m, go, L.d, L.dq, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: wo");
-        if ((rc = gemm(m, gg, 2 * (int64_t)L.f, L.d, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: gate/up");
-        if ((rc = gemm(m, gd, L.d, L.f, ctx))) return (ad_status)hip_fail(rc, "ad_layer_step: down");
+        if ((rc = gemm(m, gq, L.nqkv, L.d, ctx))) return hip_fail(rc, "layer step: qkv");
+        if ((rc = launch_attn(a, ctx))) return hip_fail(rc, "layer step: attention");
+        if ((rc = gemm(m, go, L.d, L.dq, ctx))) return hip_fail(rc, "layer step: wo");
+        if ((rc = gemm(m, gg, 2 * (int64_t)L.f, L.d, ctx))) return hip_fail(rc, "layer step: gate/up");
+        if ((rc = gemm(m, gd, L.d, L.f, ctx))) return hip_fail(rc, "layer step: down");
     }
-    kv->len[layer - 1] += n;
+    for (int32_t l = layer; l < layer + count; ++l) kv->len[l - 1] += n;
     return AD_OK;
+}
+
+ad_status ad_layer_step(const ad_model *m, ad_kv *kv, int32_t layer, void *hidden, const int32_t *pos, int32_t n, void *stream) {
+    return (ad_status)layer_steps(m, kv, layer, 1, hidden, pos, n, stream, "ad_layer_step");
+}
+
+ad_status ad_layer_steps(const ad_model *m, ad_kv *kv, int32_t first_layer, int32_t n_layers, void *hidden, const int32_t *pos, int32_t n,
+                         void *stream) {
+    return (ad_status)layer_steps(m, kv, first_layer, n_layers, hidden, pos, n, stream, "ad_layer_steps");
 }
 
 // Head at `layer` over n rows; shared by ad_exit_head, ad_verify and ad_head_logits.
@@ -662,10 +691,11 @@ struct GpuBackend : Backend {
 
     float *row(int32_t r) const { return m->rows + (size_t)r * m->cfg.d_model; }
 
-    int layer_step(int32_t layer, int32_t row0, int32_t n, int32_t pos0) override {
+    int layer_step(int32_t layer, int32_t row0, int32_t n, int32_t pos0) override { return layer_steps(layer, 1, row0, n, pos0); }
+    int layer_steps(int32_t first_layer, int32_t count, int32_t row0, int32_t n, int32_t pos0) override {
         for (int i = 0; i < n; ++i) pos_buf[i] = pos0 + i;
-        if (!in_prefill) bytes += layer_step_bytes(m->cfg, pos0, n);
-        return ad_layer_step(m, kv, layer, row(row0), pos_buf, n, stream);
+        if (!in_prefill) bytes += count * layer_step_bytes(m->cfg, pos0, n);
+        return ad_layer_steps(m, kv, first_layer, count, row(row0), pos_buf, n, stream);
     }
     int prefill(const int32_t *tokens, int32_t n) override {
         const int32_t chunk = m->cfg.m_max;
@@ -674,7 +704,7 @@ struct GpuBackend : Backend {
         for (int32_t s = 0; s < n && rc == AD_OK; s += chunk) {
             const int32_t k = (n - s < chunk) ? n - s : chunk;
             rc = ad_embed(m, tokens + s, k, row(0), stream);
-            for (int32_t l = 1; l <= m->cfg.n_layers && rc == AD_OK; ++l) rc = layer_step(l, 0, k, s);
+            if (rc == AD_OK) rc = layer_steps(1, m->cfg.n_layers, 0, k, s);
         }
         in_prefill = false;
         return rc;

@@ -112,20 +112,24 @@ struct AttnArgs {
     int kv_elem;          // ElemKind of the cache (and of the 16-bit operands of the MFMA kernel)
 };
 
-// One decoder-layer step as a single persistent kernel (bf16 models): the four GEMMs and the attention phase
-// with their usual arguments, the number of workgroups that own row tiles in each GEMM, and the grid barrier.
+// n_layers consecutive decoder-layer steps over the same rows as a single persistent kernel (bf16 models): the four
+// GEMMs and the attention phase of the first of these layers with their usual arguments, the distance in bytes from
+// one layer's weights (and norm weights) and cache to the next layer's, the number of workgroups that own row tiles in
+// each GEMM, and the grid barrier.
 struct FusedArgs {
     GemmArgs qkv, wo, gu, down;
     AttnArgs attn;
+    int n_layers;
+    long long w_stride, kv_stride;
     int nwg_qkv, nwg_wo, nwg_gu, nwg_down;
     unsigned *ctr;          // barrier counters: kBarrierWords zero-initialised words, owned by the model
     unsigned round0;        // barriers completed by earlier launches on these counters
     unsigned *abort_flag;   // pinned host word, set when a barrier wait timed out
     long long *trace;       // null, or [workgroups][kFusedTraceStamps] wall-clock ticks (100 MHz) at the phase boundaries
 };
-constexpr int kFusedTraceStamps = 12;      // start, before and after each of the 5 barriers, end
+constexpr int kFusedTraceStamps = 12;      // of the launch's last layer: start, before and after each of its 5 barriers, end
 constexpr int kBarrierWords = 32 * 9;      // one 128-byte line for the global counter and for each of 8 groups
-constexpr int kFusedBarriers = 5;          // barriers per launch
+inline unsigned fused_barriers(int n_layers) { return 6u * (unsigned)n_layers - 1u; }   // barriers per launch
 
 struct EmbedArgs {
     const void *table; int elem; int d; int m; int32_t tok[8]; float *out;

@@ -48,8 +48,9 @@ struct GridBarrier {
         __builtin_amdgcn_s_waitcnt(0);     // this wavefront's stores have completed
         __syncthreads();
         ++round;
-        if (threadIdx.x >= 64) pre();
-        if (threadIdx.x == 0) {
+        const int tid = thread_index();
+        if (tid >= 64) pre();
+        if (tid == 0) {
             const unsigned nwg = gridDim.x, g = blockIdx.x & 7, n_groups = nwg < 8 ? nwg : 8, per = (nwg - g + 7) >> 3;
             const unsigned old = __hip_atomic_fetch_add(ctr + 32 * (1 + g), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (old + 1 == round * per) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -68,7 +69,7 @@ struct GridBarrier {
             if (acquire) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         }
         __syncthreads();
-        if (threadIdx.x < 64) pre();
+        if (tid < 64) pre();
         return *ok != 0;
     }
 };
@@ -81,68 +82,108 @@ union FusedLds {
 
 // NCHMAX: see gemm_stationary (2 covers d_model <= 4096, 3 covers d_model <= 5120)
 template <int DH, int NCHMAX>
-__global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f) {
+__global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f0) {
     warm_kernel_args<sizeof(FusedArgs)>();
     constexpr int CH = 8, U = 8, NW = kFusedThreads / 64;
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     FusedLds<DH> &L = *reinterpret_cast<FusedLds<DH> *>(lds_raw);
     __shared__ int bar_ok;
-    const int wg = blockIdx.x, nwg = gridDim.x, wave = threadIdx.x >> 6;
+    const int wg = blockIdx.x, nwg = gridDim.x;
     if (threadIdx.x == 0) bar_ok = 1;
-    GridBarrier bar{f.ctr, f.round0, f.abort_flag, &bar_ok};
+    GridBarrier bar{f0.ctr, f0.round0, f0.abort_flag, &bar_ok};
     // optional trace: wall-clock ticks of this workgroup at the start, and before and after every barrier
     int n_stamp = 0;
     auto stamp = [&]() {
-        if (f.trace && threadIdx.x == 0) f.trace[(size_t)wg * kFusedTraceStamps + n_stamp] = wall_clock64();
+        if (f0.trace && threadIdx.x == 0) f0.trace[(size_t)wg * kFusedTraceStamps + n_stamp] = wall_clock64();
         ++n_stamp;
     };
-    stamp();
 
-    StatStream<1, CH> s_qkv, s_gu;
-    StreamStream<1, U, NW> s_wo, s_down;
+    StatStream<1, CH> s_qkv;   // the only weight stream that is in flight from one layer to the next
+    // the layer's weights, norm weights and cache: those of the first layer moved on by these many bytes
+    long long w_off = 0, kv_off = 0;
+    s_qkv.init(f0.qkv, wg, f0.nwg_qkv);
+    // The arguments are read through a pointer to the argument block that is renewed in every turn of the layer loop:
+    // each phase then fetches the fields it needs where it needs them, as in straight-line code (fetched once ahead
+    // of the loop, the few hundred words would have to be kept in registers across all phases).
+    typedef const __attribute__((address_space(4))) FusedArgs *ArgBlock;
+    ArgBlock fp = (ArgBlock)__builtin_amdgcn_kernarg_segment_ptr();   // f0 is the only argument: it starts the block
 
-    // ---- 1. q, k, v = W (RMSNorm(x)) ---------------------------------------------------------------------
-    s_qkv.init(f.qkv, wg, f.nwg_qkv);
-    AttnKv<DH> kv;
-    auto pre_attn = [&]() { attn_load_kv<DH, kFusedThreads>(f.attn, wg, kv); };   // the cached K/V block of the first item
-    if (wg < f.nwg_qkv) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_STORE, false, false>(f.qkv, s_qkv, L.gemm, NoTail());   // x was written before the launch: ordinary loads
-    stamp();
-    if (!bar.sync(false, pre_attn)) return;
-    stamp();
+    for (int l = 0;; ++l) {
+        asm volatile("" : "+s"(fp));
+        const FusedArgs &f = *(const FusedArgs *)fp;
+        StatStream<1, CH> s_gu;
+        StreamStream<1, U, NW> s_wo, s_down;
+        n_stamp = 0;
+        stamp();
+        // ---- 1. q, k, v = W (RMSNorm(x)) -----------------------------------------------------------------
+        AttnKv<DH> kv;
+        auto pre_attn = [&]() { attn_load_kv<DH, kFusedThreads>(f.attn, wg, kv, kv_off); };   // the cached K/V block of the first item
+        if (wg < f.nwg_qkv) {
+            // first layer: x was written before the launch and is requested ahead of the weights; later layers: the
+            // weights went in flight at the barrier that made x visible
+            if (l == 0) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_STORE, false, false>(f.qkv, s_qkv, L.gemm, NoTail(), w_off);
+            else gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_STORE, false, true>(f.qkv, s_qkv, L.gemm, NoTail(), w_off);
+        }
+        stamp();
+        forget(kv.k);
+        forget(kv.v);
+        if (!bar.sync(false, pre_attn)) return;
+        stamp();
 
-    // ---- 2. rotary embedding, KV append, attention partials ------------------------------------------------
-    attn_mfma_items<DH, kFusedThreads, IoAgent, false>(f.attn, L.attn, wg, nwg, kv, true);
-    stamp();
-    if (!bar.sync(false, NoTail())) return;
-    stamp();
+        // ---- 2. rotary embedding, KV append, attention partials ----------------------------------------------
+        attn_mfma_items<DH, kFusedThreads, IoAgent, false>(f.attn, L.attn, wg, nwg, kv, true, kv_off);
+        stamp();
+        if (!bar.sync(false, NoTail())) return;
+        stamp();
 
-    // ---- 3. fold the splits of each query row (one wavefront per row), packed for Wo -------------------------
-    for (int row = wave * nwg + wg; row < f.attn.Hq * f.attn.m; row += NW * nwg) attn_combine_row<IoAgent, false>(f.attn, row);
-    s_wo.init(f.wo, wg, f.nwg_wo);
-    auto pre_wo = [&]() { s_wo.prefetch(f.wo); };
-    stamp();
-    if (!bar.sync(true, pre_wo)) return;
-    stamp();
+        // ---- 3. fold the splits of each query row (one wavefront per row), packed for Wo -----------------------
+        for (int row = (thread_index() >> 6) * nwg + wg; row < f.attn.Hq * f.attn.m; row += NW * nwg) attn_combine_row<IoAgent, false>(f.attn, row);
+        s_wo.init(f.wo, wg, f.nwg_wo);
+        auto pre_wo = [&]() { s_wo.prefetch(f.wo, w_off); };
+        stamp();
+        forget(s_wo.a0);
+        forget(s_wo.a1);
+        if (!bar.sync(true, pre_wo)) return;
+        stamp();
 
-    // ---- 4. x' = x + Wo o ------------------------------------------------------------------------------------
-    s_gu.init(f.gu, wg, f.nwg_gu);
-    auto pre_gu = [&]() { s_gu.prefetch(); };
-    if (wg < f.nwg_wo) gemm_streamed<1, U, NW, IoAcquired, EPI_RESID, true, false>(f.wo, s_wo, L.gemm, NoTail());
-    stamp();
-    if (!bar.sync(true, pre_gu)) return;
-    stamp();
+        // ---- 4. x' = x + Wo o ----------------------------------------------------------------------------------
+        s_gu.init(f.gu, wg, f.nwg_gu, w_off);
+        auto pre_gu = [&]() { s_gu.prefetch(); };
+        if (wg < f.nwg_wo) gemm_streamed<1, U, NW, IoAcquired, EPI_RESID, true, false>(f.wo, s_wo, L.gemm, NoTail(), w_off);
+        stamp();
+        forget(s_gu.a0);
+        forget(s_gu.a1);
+        if (!bar.sync(true, pre_gu)) return;
+        stamp();
 
-    // ---- 5. g = silu(Wg b) * (Wu b), b = RMSNorm(x') -----------------------------------------------------------
-    s_down.init(f.down, wg, f.nwg_down);
-    auto pre_down = [&]() { s_down.prefetch(f.down); };
-    if (wg < f.nwg_gu) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_SWIGLU, false, true>(f.gu, s_gu, L.gemm, NoTail());
-    stamp();
-    if (!bar.sync(true, pre_down)) return;
-    stamp();
+        // ---- 5. g = silu(Wg b) * (Wu b), b = RMSNorm(x') ---------------------------------------------------------
+        s_down.init(f.down, wg, f.nwg_down);
+        auto pre_down = [&]() { s_down.prefetch(f.down, w_off); };
+        if (wg < f.nwg_gu) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_SWIGLU, false, true>(f.gu, s_gu, L.gemm, NoTail(), w_off);
+        stamp();
+        forget(s_down.a0);
+        forget(s_down.a1);
+        if (!bar.sync(true, pre_down)) return;
+        stamp();
 
-    // ---- 6. y = x' + Wd g ----------------------------------------------------------------------------------------
-    if (wg < f.nwg_down) gemm_streamed<1, U, NW, IoAcquired, EPI_RESID, true, false>(f.down, s_down, L.gemm, NoTail());
-    stamp();
+        // ---- 6. y = x' + Wd g --------------------------------------------------------------------------------------
+        if (wg < f.nwg_down) gemm_streamed<1, U, NW, IoAcquired, EPI_RESID, true, false>(f.down, s_down, L.gemm, NoTail(), w_off);
+        stamp();
+        if (l + 1 == f.n_layers) break;
+
+        // ---- next layer: same rows, the next layer's weights and cache ------------------------------------------------
+        w_off += f.w_stride;
+        kv_off += f.kv_stride;
+        // (a stream object of its own: filled under conditions, s_qkv itself would have to keep its old registers
+        // alive through all phases)
+        StatStream<1, CH> s_next;
+        s_next.init(f.qkv, wg, f.nwg_qkv, w_off);
+        auto pre_qkv = [&]() { s_next.prefetch(); };
+        forget(s_next.a0);
+        forget(s_next.a1);
+        if (!bar.sync(true, pre_qkv)) return;
+        s_qkv = s_next;
+    }
 }
 
 template <int DH, int NCHMAX>
@@ -173,7 +214,7 @@ int launch_layer_fused(const FusedArgs &f_in, const LaunchCtx &c) {
     // the streamed phases run a single round of at most 8 row tiles per workgroup
     if (f.wo.NT > 8 * f.nwg_wo || f.down.NT > 8 * f.nwg_down) return (int)hipErrorInvalidValue;
     if ((f.qkv.KT + kStatWaves - 1) / kStatWaves > kKsMax || f.qkv.K < 8) return (int)hipErrorInvalidValue;
-    if (f.attn.kv_elem != kElemBF16 || f.qkv.elem != kElemBF16 || c.n_wg < 1) return (int)hipErrorInvalidValue;
+    if (f.attn.kv_elem != kElemBF16 || f.qkv.elem != kElemBF16 || c.n_wg < 1 || f.n_layers < 1) return (int)hipErrorInvalidValue;
     const bool small = (f.qkv.KT + kStatWaves - 1) / kStatWaves <= 16;
     if (f.attn.dh == 128) return small ? launch_fused_dh<128, 2>(f, c) : launch_fused_dh<128, 3>(f, c);
     if (f.attn.dh == 64) return small ? launch_fused_dh<64, 2>(f, c) : launch_fused_dh<64, 3>(f, c);

@@ -82,20 +82,31 @@ int run_algorithm1(Backend &be, const SchedConfig &cfg, const ad_gen_params &gp,
         const bool may_exit = (n_open - 1 < gp.max_pending) && (n_emitted + 1 < gp.max_new);
         bool exited = false;
 
+        // an exit head is evaluated after layer ll
+        auto head_due = [&](int32_t ll) {
+            const int32_t sl = head_slot(cfg, ll);
+            const bool on = sl >= 0 && (gp.head_mask == 0 || ((gp.head_mask >> sl) & 1));
+            return ll < L && may_exit && on && (!gp.forced_exit || gp.forced_exit[pos] == ll);
+        };
         for (int32_t l = 1; l <= L && !exited; ++l) {
             int32_t first = n_open - 1;
             while (first > 0 && open_depth[first - 1] == l - 1) --first;
             const int32_t m = n_open - first;
-            if ((rc = be.layer_step(l, first, m, open_pos[first])) != AD_OK) return rc;
+            // the same rows go through the following layers too, up to the layer after which a head is evaluated or the
+            // deferred rows of an earlier token join: the backend gets that stretch of layers as one call
+            const int32_t l0 = l;
+            while (l < L && !head_due(l) && !(first > 0 && open_depth[first - 1] == l)) ++l;
+            if ((rc = be.layer_steps(l0, l - l0 + 1, first, m, open_pos[first])) != AD_OK) return rc;
             for (int32_t k = first; k < n_open; ++k) open_depth[k] = l;
-            ++st.layer_steps;
-            st.layer_step_rows += m;
-            ++st.steps_by_m[m];
-            tr.add(AD_EV_LAYER_STEP, l, open_pos[first], m, 0, 0, 0.0f);
+            for (int32_t ll = l0; ll <= l; ++ll) {
+                ++st.layer_steps;
+                st.layer_step_rows += m;
+                ++st.steps_by_m[m];
+                tr.add(AD_EV_LAYER_STEP, ll, open_pos[first], m, 0, 0, 0.0f);
+            }
 
             const int32_t slot = head_slot(cfg, l);
-            const bool head_on = slot >= 0 && (gp.head_mask == 0 || ((gp.head_mask >> slot) & 1));
-            if (l < L && may_exit && head_on && (!gp.forced_exit || gp.forced_exit[pos] == l)) {
+            if (head_due(l)) {
                 int32_t tok = -1;
                 float conf = 0.0f;
                 if (sampled)

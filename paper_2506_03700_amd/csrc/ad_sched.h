@@ -17,6 +17,14 @@ struct Backend {
     virtual int embed(int32_t token, int32_t row) = 0;
     // layer `layer` over hidden rows [row0, row0 + m) at positions pos0 .. pos0 + m - 1
     virtual int layer_step(int32_t layer, int32_t row0, int32_t m, int32_t pos0) = 0;
+    // the same rows through layers first_layer .. first_layer + count - 1, one after the other
+    virtual int layer_steps(int32_t first_layer, int32_t count, int32_t row0, int32_t m, int32_t pos0) {
+        for (int32_t l = first_layer; l < first_layer + count; ++l) {
+            const int rc = layer_step(l, row0, m, pos0);
+            if (rc != AD_OK) return rc;
+        }
+        return AD_OK;
+    }
     // Eq. 1 at temperature 0 on one row; the result must be final when the call returns
     virtual int exit_head(int32_t layer, int32_t row, int32_t pos, int32_t *token, float *conf) = 0;
     // Eq. 2 at temperature 0 on rows [0, m)

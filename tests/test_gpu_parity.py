@@ -94,6 +94,58 @@ def test_layer_steps_ragged_small_models(ad, shape, mode):
     g.close()
 
 
+DEEP = synth.TINY_BF16.with_(name="tiny-bf16-6-layers", n_layers=6, exit_layers=(2, 4))
+
+
+@pytest.mark.parametrize("shape,mode", with_modes([DEEP, synth.TINY_GQA, ODD.with_(name="tiny-odd-bf16", dtype=synth.BF16), synth.TINY]))
+def test_layer_ranges_match_oracle(ad, shape, mode):
+    """ad_layer_steps: the same rows through a stretch of consecutive layers in one call (one launch in the fused
+    mode), for stretches of every length, against the oracle taken layer by layer."""
+    print(f"case {shape.name} layer mode {mode}", flush=True)
+    w = synth.make_weights(shape, seed=13, norm_jitter=0.2)
+    L = shape.n_layers
+    o = orc.Oracle(shape, w, max_pos=64)
+    g = ad.Model(shape, w, max_pos=64, layer_mode=mode)
+    tol = TOL[shape.dtype]
+    toks = synth.make_prompt(shape, seed=6, n=40)
+    # every way of cutting 1..L into at most two or three stretches gets its turn, row counts vary
+    cuts = [[L], [1, L - 1], [L - 1, 1], [2, L - 2], [1, 1, L - 2], [L], [1] * L, [L]]
+    start = 0
+    for case, (m, cut) in enumerate(zip([1, 3, 8, 2, 5, 7, 4, 6], cuts)):
+        pos = np.arange(start, start + m)
+        ho = o.embed(toks[start:start + m])
+        hg = g.ad_embed(toks[start:start + m])
+        first = 1
+        for n in cut:
+            for l in range(first, first + n):
+                ho = o.layer_step(l, ho, pos)
+            g.ad_layer_steps(first, n, hg, pos)
+            e = rel_err(hg.cpu().numpy(), ho)
+            assert e <= tol, f"case {case}: layers {first}..{first + n - 1}, rows {start}..{start + m - 1}: rel err {e}"
+            first += n
+        assert first == L + 1
+        start += m
+    assert g.kv_lens() == o.kv_lens() == [start] * L
+    for l in range(1, L + 1):
+        ko, vo = o.kv_read(l, 0, start)
+        kg, vg = gpu_kv(g, l, start)
+        assert rel_err(kg, ko) <= tol and rel_err(vg, vo) <= tol
+    # error paths: a stretch that leaves the model, and one whose layers' caches end at different positions
+    h = g.ad_embed(toks[:2])
+    with pytest.raises(ad.AdError) as ei:
+        g.ad_layer_steps(2, L, h, np.arange(start, start + 2))
+    assert ei.value.status == ad.AD_ERANGE
+    with pytest.raises(ad.AdError) as ei:
+        g.ad_layer_steps(1, 0, h, np.arange(start, start + 2))
+    assert ei.value.status == ad.AD_ERANGE
+    g.ad_layer_steps(1, 1, h, np.arange(start, start + 2))
+    with pytest.raises(ad.AdError) as ei:
+        g.ad_layer_steps(1, 2, h, np.arange(start, start + 2))
+    assert ei.value.status == ad.AD_ESTATE
+    assert g.kv_lens() == [start + 2] + [start] * (L - 1)      # a refused call appends nothing
+    g.close()
+
+
 L13 = synth.LLAMA13B.with_(name="13b-layer", n_layers=1, exit_layers=(), vocab=256)
 L8_F16 = synth.LLAMA8B_LAYER.with_(name="8b-layer-f16", dtype=synth.F16)
 L13_F16 = L13.with_(name="13b-layer-f16", dtype=synth.F16)
