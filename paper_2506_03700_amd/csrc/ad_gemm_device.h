@@ -668,32 +668,28 @@ __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NP
         if (tb == t1) tail();
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        // sum the slots of each tile in wavefront order
-        for (int idx = tid; idx < nt * 128; idx += NTHREADS) {
-            const int T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15;
+        // The sum of a tile's slots, in wavefront order: wavefronts w0 .. w1 hold pairs of tile T (pairs [T * KT, T * KT + KT)
+        // of the round; wavefront w holds pairs [tot * w / NW, tot * (w + 1) / NW)), those without pairs are skipped.
+        auto tile_sum = [&](int T, int t, int i) {
+            const int x0 = T * KT, x1 = x0 + KT - 1;
+            int w0 = 0, w1 = NW - 1;
+            while (w0 + 1 < NW && part_start(tot, w0 + 1, NW) <= x0) ++w0;
+            while (w1 > 0 && part_start(tot, w1, NW) > x1) --w1;
             float v = 0.f;
-            if (t < g.m) {
-                const int x0 = T * KT, x1 = x0 + KT - 1;
-                int w0 = (int)(((long)x0 * NW) / tot), w1 = (int)(((long)x1 * NW) / tot);
-                while (w0 + 1 < NW && part_start(tot, w0 + 1, NW) <= x0) ++w0;
-                while (part_start(tot, w0, NW) > x0) --w0;
-                while (w1 + 1 < NW && part_start(tot, w1 + 1, NW) <= x1) ++w1;
-                while (part_start(tot, w1, NW) > x1) --w1;
-                for (int w = w0; w <= w1; ++w) {
-                    if (part_start(tot, w, NW) == part_start(tot, w + 1, NW)) continue;   // wavefront had no work
-                    const float *s = L.slots + (w + T) * 256;
-                    v += s[t * 16 + i] + s[(t + 8) * 16 + i];
-                }
+            for (int w = w0; w <= w1; ++w) {
+                if (part_start(tot, w, NW) == part_start(tot, w + 1, NW)) continue;   // wavefront had no work
+                const float *s = L.slots + (w + T) * 256;
+                v += s[t * 16 + i] + s[(t + 8) * 16 + i];
             }
-            L.red[idx] = v;
-        }
-        __syncthreads();
+            return v;
+        };
         if (epi == EPI_RESID) {
+            // each thread sums its own output entries and finishes them
 #pragma unroll
             for (int j = 0; j < RP; ++j) {
                 const int idx = tid + j * NTHREADS, T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15, n = (ta + T) * 16 + i;
                 const bool on = idx < nt * 128 && t < g.m && n < g.N;
-                const float y = on ? rpre[j] + L.red[idx] : 0.f;
+                const float y = on ? rpre[j] + tile_sum(T, t, i) : 0.f;
                 if (on) Io::st(g.out + (size_t)t * g.ld + n, y);
                 if (g.Bnext) {
                     // input of the next GEMM: y * norm weight, packed; and this tile's share of sum(y^2) per token
@@ -708,9 +704,15 @@ __device__ __forceinline__ void gemm_streamed(const GemmArgs &g, StreamStream<NP
                 }
             }
         } else {
+            for (int idx = tid; idx < nt * 128; idx += NTHREADS) {
+                const int T = idx >> 7, t = (idx >> 4) & 7, i = idx & 15;
+                L.red[idx] = t < g.m ? tile_sum(T, t, i) : 0.f;
+            }
+            __syncthreads();
             epilogue<Io, EPI, F16>(g, L, ta, nt, tid, lane, wave, NTHREADS);
         }
         __syncthreads();
+        if (ONE_ROUND) break;     // (said here as well, so that the body is not compiled as a loop)
     }
     if (t1 == t0) tail();
 }
