@@ -107,6 +107,8 @@ void make_layout(const ad_config &c, Layout &L) {
     s += align_up(act_packed_bytes(L.f));                      // Bg (SwiGLU output)
     s += align_up(act_packed_bytes(L.d));                      // Bx (x' * ffn norm weight, packed by the Wo epilogue)
     s += align_up((size_t)(L.d / 16) * 8 * 4);                 // per-tile sums of squares of x'
+    s += align_up(act_packed_bytes(L.d));                      // Bq (y * next layer's attention norm weight, packed by the down epilogue)
+    s += align_up((size_t)(L.d / 16) * 8 * 4);                 // per-tile sums of squares of y
     s += align_up((size_t)8 * L.nqkv * 4);                     // qkv
     s += 2 * align_up((size_t)8 * L.d * 4);                    // x1, rows
     s += align_up((size_t)4096 * 8 * 4 * 4);                   // head partials (up to 4096 workgroups)
@@ -137,8 +139,8 @@ struct ad_model {
     std::vector<LayerPacked> layers;
     char *embed, *final_norm, *head, *T[AD_MAX_EXIT];
     // scratch
-    char *B1, *Bo, *Bg, *Bx;
-    float *ssq;
+    char *B1, *Bo, *Bg, *Bx, *Bq;
+    float *ssq, *ssq_q;
     float *qkv, *x1, *rows, *head_part;
     float *samp_stats, *draft_logits, *final_logits;   // sampled decoding
     // pinned host results for ad_generate
@@ -248,6 +250,8 @@ ad_status ad_model_create(const ad_config *cfg, const ad_layer_weights *layers, 
     m->Bg = take(act_packed_bytes(L.f));
     m->Bx = take(act_packed_bytes(L.d));
     m->ssq = (float *)take((size_t)(L.d / 16) * 8 * 4);
+    m->Bq = take(act_packed_bytes(L.d));
+    m->ssq_q = (float *)take((size_t)(L.d / 16) * 8 * 4);
     m->qkv = (float *)take((size_t)8 * L.nqkv * 4);
     m->x1 = (float *)take((size_t)8 * L.d * 4);
     m->rows = (float *)take((size_t)8 * L.d * 4);
@@ -430,62 +434,80 @@ static int layer_steps(const ad_model *m, ad_kv *kv, int32_t layer, int32_t coun
     for (int32_t l = layer; l < layer + count; ++l)
         if (pos[0] != kv->len[l - 1]) return fail(AD_ESTATE, "%s: pos[0] = %d but layer %d's cache ends at %d", who, pos[0], l, kv->len[l - 1]);
     if (pos[0] < 0 || pos[n - 1] >= kv->max_pos) return fail(AD_ERANGE, "%s: position %d beyond max_pos %d", who, pos[n - 1], kv->max_pos);
-    if (count > 1 && m->layer_mode != AD_LAYER_FUSED) {
-        for (int32_t l = layer; l < layer + count; ++l) {
-            const int rc1 = layer_steps(m, kv, l, 1, hidden, pos, n, stream, who);
-            if (rc1) return rc1;
-        }
-        return AD_OK;
-    }
-
     const Layout &L = m->lay;
-    const LayerPacked &lp = m->layers[layer - 1];
     const LaunchCtx ctx{stream, m->n_wg};
     const int ek = elem_kind(c);
+    const bool fused = m->layer_mode == AD_LAYER_FUSED;
     int rc;
-    // 1. q, k, v = W (RMSNorm(x)): the norm is fused into the GEMM (B operand built from x in its prologue)
-    GemmArgs gq;
-    memset(&gq, 0, sizeof gq);
-    gq.elem = ek;
-    gq.W = lp.wqkv; gq.NT = L.nqkv / 16; gq.KT = L.kt_d; gq.N = L.nqkv; gq.K = L.d; gq.m = n; gq.mode = GEMM_STATIONARY;
-    gq.x = (const float *)hidden; gq.ldx = L.d; gq.norm_w = lp.attn_norm; gq.norm_elem = ek; gq.inv_dim = 1.0f / (float)L.d; gq.eps = c.rms_eps;
-    gq.epi = EPI_STORE; gq.out = m->qkv; gq.ld = L.nqkv;
-    // 2. rotary embedding, KV append, attention (partials + combine)
+    // The arguments of layer ly's five steps.  from_prev: the layer before it ran in this same call and its down
+    // projection left this layer's QKV input behind (see step 5); feeds_next: this layer's down projection does
+    // that for the layer after it.
+    GemmArgs gq, go, gg, gd;
     AttnArgs a;
-    memset(&a, 0, sizeof a);
-    a.qkv = m->qkv; a.ld = L.nqkv; a.rope = kv->rope + (size_t)pos[0] * (L.dh / 2) * 2;
-    a.Kc = kv->storage + (size_t)(layer - 1) * kv->layer_bytes; a.Vc = (char *)a.Kc + kv->half_bytes;
-    a.stride = kv->stride; a.pos0 = pos[0]; a.m = n; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = L.dh;
-    a.C = attn_chunk(ek, L.dh);
-    a.S = pos[0] > 0 ? (pos[0] + a.C - 1) / a.C : 1;
-    a.part = kv->part; a.Bo = m->Bo; a.Bo_KT = L.kt_q; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_elem = ek;
-    // 3. x' = x + Wo o
-    GemmArgs go;
-    memset(&go, 0, sizeof go);
-    go.elem = ek;
-    go.W = lp.wo; go.B = m->Bo; go.NT = L.d / 16; go.KT = L.kt_q; go.N = L.d; go.K = L.dq; go.m = n; go.mode = GEMM_STREAMED;
-    go.epi = EPI_RESID; go.resid = (const float *)hidden; go.out = m->x1; go.ld = L.d;
-    // ... and the Wo epilogue already prepares the gate/up GEMM's input: x' * ffn norm weight packed, sum(x'^2) per tile
-    go.Bnext = m->Bx; go.Bnext_KT = L.kt_d; go.next_norm_w = lp.ffn_norm; go.next_norm_elem = ek; go.ssq_out = m->ssq;
-    // 4. g = silu(Wg b) * (Wu b), b = RMSNorm(x') fused as in step 1
-    GemmArgs gg;
-    memset(&gg, 0, sizeof gg);
-    gg.elem = ek;
-    gg.W = lp.wgu; gg.NT = (2 * L.f) / 16; gg.KT = L.kt_d; gg.N = 2 * L.f; gg.K = L.d; gg.m = n; gg.mode = GEMM_STATIONARY;
-    gg.B = m->Bx; gg.ssq_in = m->ssq; gg.ssq_tiles = go.NT; gg.inv_dim = 1.0f / (float)L.d; gg.eps = c.rms_eps;
-    gg.epi = EPI_SWIGLU; gg.Bnext = m->Bg; gg.Bnext_KT = L.kt_f;
-    // 5. y = x' + Wd g
-    GemmArgs gd;
-    memset(&gd, 0, sizeof gd);
-    gd.elem = ek;
-    gd.W = lp.wd; gd.B = m->Bg; gd.NT = L.d / 16; gd.KT = L.kt_f; gd.N = L.d; gd.K = L.f; gd.m = n; gd.mode = GEMM_STREAMED;
-    gd.epi = EPI_RESID; gd.resid = m->x1; gd.out = (float *)hidden; gd.ld = L.d;
+    auto build = [&](int32_t ly, bool from_prev, bool feeds_next) {
+        const LayerPacked &lp = m->layers[ly - 1];
+        // 1. q, k, v = W (RMSNorm(x)): the norm is fused into the GEMM (B operand built from x in its prologue, or taken
+        //    packed, with the sums of squares, from the previous layer's last step)
+        memset(&gq, 0, sizeof gq);
+        gq.elem = ek;
+        gq.W = lp.wqkv; gq.NT = L.nqkv / 16; gq.KT = L.kt_d; gq.N = L.nqkv; gq.K = L.d; gq.m = n; gq.mode = GEMM_STATIONARY;
+        gq.inv_dim = 1.0f / (float)L.d; gq.eps = c.rms_eps;
+        if (from_prev) { gq.B = m->Bq; gq.ssq_in = m->ssq_q; gq.ssq_tiles = L.d / 16; }
+        else { gq.x = (const float *)hidden; gq.ldx = L.d; gq.norm_w = lp.attn_norm; gq.norm_elem = ek; }
+        gq.epi = EPI_STORE; gq.out = m->qkv; gq.ld = L.nqkv;
+        // 2. rotary embedding, KV append, attention (partials + combine)
+        memset(&a, 0, sizeof a);
+        a.qkv = m->qkv; a.ld = L.nqkv; a.rope = kv->rope + (size_t)pos[0] * (L.dh / 2) * 2;
+        a.Kc = kv->storage + (size_t)(ly - 1) * kv->layer_bytes; a.Vc = (char *)a.Kc + kv->half_bytes;
+        a.stride = kv->stride; a.pos0 = pos[0]; a.m = n; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.dh = L.dh;
+        a.C = attn_chunk(ek, L.dh);
+        a.S = pos[0] > 0 ? (pos[0] + a.C - 1) / a.C : 1;
+        a.part = kv->part; a.Bo = m->Bo; a.Bo_KT = L.kt_q; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_elem = ek;
+        // 3. x' = x + Wo o
+        memset(&go, 0, sizeof go);
+        go.elem = ek;
+        go.W = lp.wo; go.B = m->Bo; go.NT = L.d / 16; go.KT = L.kt_q; go.N = L.d; go.K = L.dq; go.m = n; go.mode = GEMM_STREAMED;
+        go.epi = EPI_RESID; go.resid = (const float *)hidden; go.out = m->x1; go.ld = L.d;
+        // ... and the Wo epilogue already prepares the gate/up GEMM's input: x' * ffn norm weight packed, sum(x'^2) per tile
+        go.Bnext = m->Bx; go.Bnext_KT = L.kt_d; go.next_norm_w = lp.ffn_norm; go.next_norm_elem = ek; go.ssq_out = m->ssq;
+        // 4. g = silu(Wg b) * (Wu b), b = RMSNorm(x') fused as in step 1
+        memset(&gg, 0, sizeof gg);
+        gg.elem = ek;
+        gg.W = lp.wgu; gg.NT = (2 * L.f) / 16; gg.KT = L.kt_d; gg.N = 2 * L.f; gg.K = L.d; gg.m = n; gg.mode = GEMM_STATIONARY;
+        gg.B = m->Bx; gg.ssq_in = m->ssq; gg.ssq_tiles = go.NT; gg.inv_dim = 1.0f / (float)L.d; gg.eps = c.rms_eps;
+        gg.epi = EPI_SWIGLU; gg.Bnext = m->Bg; gg.Bnext_KT = L.kt_f;
+        // 5. y = x' + Wd g
+        memset(&gd, 0, sizeof gd);
+        gd.elem = ek;
+        gd.W = lp.wd; gd.B = m->Bg; gd.NT = L.d / 16; gd.KT = L.kt_f; gd.N = L.d; gd.K = L.f; gd.m = n; gd.mode = GEMM_STREAMED;
+        gd.epi = EPI_RESID; gd.resid = m->x1; gd.out = (float *)hidden; gd.ld = L.d;
+        // ... and, like step 3 for step 4, prepares the next layer's QKV input: y * its attention norm weight packed, sum(y^2) per tile
+        if (feeds_next) {
+            gd.Bnext = m->Bq; gd.Bnext_KT = L.kt_d; gd.next_norm_w = m->layers[ly].attn_norm; gd.next_norm_elem = ek; gd.ssq_out = m->ssq_q;
+        }
+    };
 
-    if (m->layer_mode == AD_LAYER_FUSED) {
-        // all five steps in one persistent kernel
+    if (!fused) {
+        // one kernel per phase, layer after layer
+        for (int32_t ly = layer; ly < layer + count; ++ly) {
+            build(ly, ly > layer, ly + 1 < layer + count);
+            if ((rc = gemm(m, gq, L.nqkv, L.d, ctx))) return hip_fail(rc, "layer step: qkv");
+            if ((rc = launch_attn(a, ctx))) return hip_fail(rc, "layer step: attention");
+            if ((rc = gemm(m, go, L.d, L.dq, ctx))) return hip_fail(rc, "layer step: wo");
+            if ((rc = gemm(m, gg, 2 * (int64_t)L.f, L.d, ctx))) return hip_fail(rc, "layer step: gate/up");
+            if ((rc = gemm(m, gd, L.d, L.f, ctx))) return hip_fail(rc, "layer step: down");
+        }
+    } else {
+        // the whole stretch in one persistent kernel
+        const LayerPacked &lp = m->layers[layer - 1];
         if ((rc = fused_health(m, stream))) return rc;
+        // the stretch's first layer as it runs when it is also the last (nothing handed on), then the two variants
+        // that differ for the layers that follow / are followed by another
         FusedArgs f;
-        f.qkv = gq; f.wo = go; f.gu = gg; f.down = gd; f.attn = a;
+        build(layer, false, false);
+        f.qkv = gq; f.wo = go; f.gu = gg; f.down_last = gd; f.attn = a;
+        build(layer, true, count > 1);
+        f.qkv_next = gq; f.down = gd;
         f.n_layers = count;
         f.w_stride = count > 1 ? (long long)(m->layers[layer].wqkv - lp.wqkv) : 0;
         f.kv_stride = (long long)kv->layer_bytes;
@@ -505,12 +527,6 @@ static int layer_steps(const ad_model *m, ad_kv *kv, int32_t layer, int32_t coun
         if (sample) (void)event_record(m->prof.stop.back(), stream);
         if (rc) return hip_fail(rc, "layer step: fused kernel");
         m->bar_round += fused_barriers(count);
-    } else {
-        if ((rc = gemm(m, gq, L.nqkv, L.d, ctx))) return hip_fail(rc, "layer step: qkv");
-        if ((rc = launch_attn(a, ctx))) return hip_fail(rc, "layer step: attention");
-        if ((rc = gemm(m, go, L.d, L.dq, ctx))) return hip_fail(rc, "layer step: wo");
-        if ((rc = gemm(m, gg, 2 * (int64_t)L.f, L.d, ctx))) return hip_fail(rc, "layer step: gate/up");
-        if ((rc = gemm(m, gd, L.d, L.f, ctx))) return hip_fail(rc, "layer step: down");
     }
     for (int32_t l = layer; l < layer + count; ++l) kv->len[l - 1] += n;
     return AD_OK;

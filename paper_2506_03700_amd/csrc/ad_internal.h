@@ -115,9 +115,10 @@ struct AttnArgs {
 // n_layers consecutive decoder-layer steps over the same rows as a single persistent kernel (bf16 models): the four
 // GEMMs and the attention phase of the first of these layers with their usual arguments, the distance in bytes from
 // one layer's weights (and norm weights) and cache to the next layer's, the number of workgroups that own row tiles in
-// each GEMM, and the grid barrier.
+// each GEMM, and the grid barrier.  qkv reads the caller's rows (first layer); qkv_next reads what the down projection
+// of the layer before left packed (`down`: a layer that is followed by another; down_last: the last one).
 struct FusedArgs {
-    GemmArgs qkv, wo, gu, down;
+    GemmArgs qkv, qkv_next, wo, gu, down, down_last;
     AttnArgs attn;
     int n_layers;
     long long w_stride, kv_stride;

@@ -122,7 +122,7 @@ __global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f0) {
             // first layer: x was written before the launch and is requested ahead of the weights; later layers: the
             // weights went in flight at the barrier that made x visible
             if (l == 0) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_STORE, false, false>(f.qkv, s_qkv, L.gemm, NoTail(), w_off);
-            else gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_STORE, false, true>(f.qkv, s_qkv, L.gemm, NoTail(), w_off);
+            else gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_STORE, false, true>(f.qkv_next, s_qkv, L.gemm, NoTail(), w_off);
         }
         stamp();
         forget(kv.k);
@@ -157,8 +157,8 @@ __global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f0) {
         stamp();
 
         // ---- 5. g = silu(Wg b) * (Wu b), b = RMSNorm(x') ---------------------------------------------------------
-        s_down.init(f.down, wg, f.nwg_down);
-        auto pre_down = [&]() { s_down.prefetch(f.down, w_off); };
+        s_down.init(f.down_last, wg, f.nwg_down);
+        auto pre_down = [&]() { s_down.prefetch(f.down_last, w_off); };
         if (wg < f.nwg_gu) gemm_stationary<1, CH, NCHMAX, IoAcquired, EPI_SWIGLU, false, true>(f.gu, s_gu, L.gemm, NoTail(), w_off);
         stamp();
         forget(s_down.a0);
@@ -167,9 +167,11 @@ __global__ void __launch_bounds__(kFusedThreads) k_layer_fused(FusedArgs f0) {
         stamp();
 
         // ---- 6. y = x' + Wd g --------------------------------------------------------------------------------------
-        if (wg < f.nwg_down) gemm_streamed<1, U, NW, IoAcquired, EPI_RESID, true, false>(f.down, s_down, L.gemm, NoTail(), w_off);
+        // (a layer that is followed by another also leaves that layer's QKV input behind, packed)
+        const bool more = l + 1 < f.n_layers;
+        if (wg < f.nwg_down) gemm_streamed<1, U, NW, IoAcquired, EPI_RESID, true, false>(more ? f.down : f.down_last, s_down, L.gemm, NoTail(), w_off);
         stamp();
-        if (l + 1 == f.n_layers) break;
+        if (!more) break;
 
         // ---- next layer: same rows, the next layer's weights and cache ------------------------------------------------
         w_off += f.w_stride;
@@ -207,6 +209,8 @@ int fused_phase_workgroups(int n_tiles, int n_wg) {
 int launch_layer_fused(const FusedArgs &f_in, const LaunchCtx &c) {
     FusedArgs f = f_in;
     set_tile_partition(f.qkv, f.nwg_qkv);
+    set_tile_partition(f.qkv_next, f.nwg_qkv);
+    set_tile_partition(f.down_last, f.nwg_down);
     set_tile_partition(f.wo, f.nwg_wo);
     set_tile_partition(f.gu, f.nwg_gu);
     set_tile_partition(f.down, f.nwg_down);
