@@ -402,8 +402,20 @@ def sched_test_lib() -> C.CDLL:
         L.ad_sched_test_run.restype = C.c_int
         L.ad_sched_test_run.argtypes = [i32, i32, P, i32, i32, i32, i32, i32, P, P, P, C.POINTER(GenParams), P, i32, P, P,
                                         C.POINTER(Stats), P, C.c_int64, P, P]
+        L.ad_sched_test_stretches.restype = C.c_int64
+        L.ad_sched_test_stretches.argtypes = [P, C.c_int64]
         _sched = L
     return _sched
+
+
+def sched_test_stretches() -> np.ndarray:
+    """The layer stretches the scheduler handed to the scripted backend in the last sched_test_run:
+    rows of (first layer, layers, first row, rows, first position)."""
+    L = sched_test_lib()
+    n = L.ad_sched_test_stretches(None, 0)
+    out = np.zeros((max(int(n), 1), 5), dtype=np.int32)
+    L.ad_sched_test_stretches(out.ctypes.data, n)
+    return out[:n]
 
 
 def sched_test_run(n_layers: int, exit_layers: Sequence[int], m_max: int, head_tok: np.ndarray, head_conf: np.ndarray,

@@ -4,9 +4,14 @@
 // product library.
 #include <string.h>
 
+#include <vector>
+
 #include "ad_sched.h"
 
 namespace {
+
+// the calls of Backend::layer_steps of the last run: (first layer, layers, first row, rows, first position)
+std::vector<int32_t> g_stretches;
 
 struct Scripted : ad::Backend {
     int32_t n_layers, n_exit, max_pos;
@@ -37,6 +42,11 @@ struct Scripted : ad::Backend {
         for (int i = 0; i < m; ++i) row_pos[row0 + i] = pos0 + i;
         len[layer - 1] += m;
         return AD_OK;
+    }
+    int layer_steps(int32_t first_layer, int32_t count, int32_t row0, int32_t m, int32_t pos0) override {
+        const int32_t rec[5] = {first_layer, count, row0, m, pos0};
+        g_stretches.insert(g_stretches.end(), rec, rec + 5);
+        return ad::Backend::layer_steps(first_layer, count, row0, m, pos0);
     }
     int exit_head(int32_t layer, int32_t row, int32_t pos, int32_t *token, float *conf) override {
         if (layer == n_layers && !seq_mode) {
@@ -117,6 +127,7 @@ extern "C" int ad_sched_test_run(int32_t n_layers, int32_t n_exit, const int32_t
                                  float *last_draws /* NULL, or [4]: the head, final, first-acceptance and first-replacement
                                                       draws the backend saw last in a sampled run */) {
     if (n_layers < 1 || n_layers > 256 || n_exit < 0 || n_exit > AD_MAX_EXIT) return AD_EINVAL;
+    g_stretches.clear();
     Scripted be;
     be.n_layers = n_layers; be.n_exit = n_exit; be.max_pos = max_pos; be.exit_layers = exit_layers;
     be.head_tok = head_tok; be.head_conf = head_conf; be.final_tok = final_tok;
@@ -131,4 +142,14 @@ extern "C" int ad_sched_test_run(int32_t n_layers, int32_t n_exit, const int32_t
         last_draws[0] = be.last_u_head; last_draws[1] = be.last_u_final; last_draws[2] = be.last_u_accept0; last_draws[3] = be.last_u_resample0;
     }
     return rc;
+}
+
+// The stretches of layers the scheduler handed to the backend in the last ad_sched_test_run of this process:
+// copies up to max_records records of 5 int32 (first layer, layers, first row, rows, first position) and returns
+// how many there were.
+extern "C" int64_t ad_sched_test_stretches(int32_t *out, int64_t max_records) {
+    const int64_t n = (int64_t)(g_stretches.size() / 5);
+    for (int64_t i = 0; i < n && i < max_records; ++i)
+        for (int k = 0; k < 5; ++k) out[i * 5 + k] = g_stretches[(size_t)i * 5 + k];
+    return n;
 }

@@ -81,6 +81,68 @@ def test_fig2_left_schedule():
     assert st["steps_by_m"][1:4] == [4, 1, 1]
 
 
+def _check_stretches(ev, n_layers):
+    """The backend gets the layer steps as stretches: expanded, they are the run's layer steps in order; a stretch ends
+    at the last layer, at a layer after which a head was evaluated, or where the next layer's step has other rows."""
+    evs = _events(ev)
+    steps = [(l, p, m) for k, l, p, m, _, _ in evs if k == ad.EV_LAYER_STEP]
+    st = ad.sched_test_stretches()
+    expanded = [(int(f) + i, int(p0), int(m)) for f, c, r0, m, p0 in st for i in range(int(c))]
+    assert expanded == steps
+    # the event that follows each stretch's last layer step
+    idx = [i for i, e in enumerate(evs) if e[0] == ad.EV_LAYER_STEP]
+    at = 0
+    for f, c, r0, m, p0 in st:
+        last = idx[at + int(c) - 1]
+        at += int(c)
+        layer = int(f) + int(c) - 1
+        nxt = evs[last + 1] if last + 1 < len(evs) else None
+        if layer == n_layers:
+            continue
+        assert nxt is not None
+        if nxt[0] == ad.EV_LAYER_STEP:
+            # no head in between: the next step must be this token's next layer with more rows (deferred rows join)
+            assert nxt[1] == layer + 1 and nxt[3] > int(m)
+        else:
+            assert nxt[0] == ad.EV_HEAD and nxt[1] == layer
+    return st
+
+
+def test_layer_steps_reach_the_backend_as_maximal_stretches():
+    # 12 layers, heads at 4 and 8: a token that goes to full depth alone is three stretches (1-4, 5-8, 9-12); after an
+    # exit at layer 4 the next token runs 1-4 alone, then both rows 5-8 and 9-12
+    n_pos = 32
+    head_tok = np.zeros((n_pos, 2), dtype=np.int32)
+    head_conf = np.zeros((n_pos, 2), dtype=np.float32)
+    final_tok = np.arange(100, 100 + n_pos, dtype=np.int32)
+    head_tok[3] = [103, 0]; head_conf[3] = [0.99, 0.0]          # position 3 exits at layer 4 with the right token
+    head_tok[5] = [0, 105]; head_conf[5] = [0.0, 0.99]          # position 5 exits at layer 8
+    rc, out, stt, ev = ad.sched_test_run(12, [4, 8], 8, head_tok, head_conf, final_tok, prompt=[1, 2, 3, 4], max_new=6,
+                                         gamma=0.9, max_pending=5)
+    assert rc == ad.AD_OK and list(out) == [103, 104, 105, 106, 107, 108]
+    st = _check_stretches(ev, 12)
+    assert [tuple(int(v) for v in r) for r in st[:7]] == [
+        (1, 4, 0, 1, 3),            # position 3 alone up to the head at 4: exits
+        (1, 4, 1, 1, 4),            # position 4 alone up to the head at 4 (stays)
+        (5, 4, 0, 2, 3),            # both rows, layers 5-8 (head at 8: stays)
+        (9, 4, 0, 2, 3),            # both rows to the last layer: verified
+        (1, 4, 0, 1, 5), (5, 4, 0, 1, 5),    # position 5 exits at layer 8
+        (1, 4, 1, 1, 6)]
+    # with the exits switched off (gamma 1 never fires but the heads are still evaluated) the stretches are the same
+    # three per token; with no heads in the schedule at all (head_mask cannot be empty, so: a cap of 0) one per token
+    rc, out, stt, ev = ad.sched_test_run(12, [4, 8], 8, head_tok, head_conf, final_tok, prompt=[1, 2, 3, 4], max_new=3,
+                                         gamma=0.9, max_pending=0)
+    assert rc == ad.AD_OK
+    st = _check_stretches(ev, 12)
+    assert [tuple(int(v) for v in r) for r in st] == [(1, 12, 0, 1, 3), (1, 12, 0, 1, 4), (1, 12, 0, 1, 5)]
+    # a single head (the fixed-layer variant): stretches 1-8 and 9-12
+    rc, out, stt, ev = ad.sched_test_run(12, [4, 8], 8, head_tok, head_conf, final_tok, prompt=[1, 2, 3, 4], max_new=2,
+                                         gamma=0.9, max_pending=5, head_mask=2)
+    assert rc == ad.AD_OK
+    st = _check_stretches(ev, 12)
+    assert [tuple(int(v) for v in r) for r in st[:2]] == [(1, 8, 0, 1, 3), (9, 4, 0, 1, 3)]
+
+
 def test_threshold_is_strict_and_cap_and_budget():
     n_pos, L = 64, 4
     final_tok = (np.arange(n_pos) * 7 % 50).astype(np.int32)
@@ -161,6 +223,7 @@ def test_scheduler_replays_the_oracle_run(shape, gamma, cap, forced_seed):
                                         rows["token"], p, 40, gamma, cap, forced_exit=forced, scripted_draft=script,
                                         max_pos=128, sequence=True)
     assert rc == ad.AD_OK
+    _check_stretches(ev, shape.n_layers)
     np.testing.assert_array_equal(out, toks)
     for k in ("tokens", "layer_steps", "layer_step_rows", "head_evals", "verifies", "early_preds", "rejections", "rolled_back"):
         assert st[k] == st_o[k], k
