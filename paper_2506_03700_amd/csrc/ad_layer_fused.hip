@@ -2,9 +2,11 @@
 // persistent kernel for bf16 models: one workgroup of 8 wavefronts per compute unit runs the six phases
 //   QKV projection (RMSNorm fused) | attention items | fold of the splits | Wo + residual |
 //   gate/up (RMSNorm fused) + SwiGLU | down + residual
-// separated by five grid barriers.  Compared with one kernel per phase this removes the launch gaps and lets every
-// workgroup put the first weight batches of the next phase in flight *while* it waits at the barrier (weights do
-// not depend on the previous phase), so the HBM stream hardly stops at a phase boundary.
+// separated by five grid barriers.  A launch runs a stretch of consecutive layers over the same rows, with a sixth
+// barrier from each layer to the next.  Compared with one kernel per phase this removes the launch gaps and lets
+// every workgroup put the first weight batches of the next phase (or of the next layer's first phase) in flight
+// *while* it waits at the barrier (weights do not depend on the previous phase), so the HBM stream hardly stops at
+// a phase boundary.
 //
 // Data handed from one phase to the next (q/k/v rows, attention partials, packed activations, x') is written
 // and read with relaxed agent-scope atomics (see IoAgent): the stores go through to memory, a wavefront waits
