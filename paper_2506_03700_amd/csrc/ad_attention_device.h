@@ -27,12 +27,13 @@ constexpr int kAttnWaves = 4;            // key blocks of an item that are proce
 constexpr int kAttnRowsPerPass = 32;
 constexpr int kAttnSlots = 5;   // 4 cached blocks + the call's own rows
 
-template <int DH>
+// RP: query rows per pass (a multiple of 8; more rows take more passes)
+template <int DH, int RP = kAttnRowsPerPass>
 struct AttnMfmaLds {
-    bf16x8 qb[4 * (DH / 32) * 64];                       // [row block][k-step][lane]
+    bf16x8 qb[(RP / 8) * (DH / 32) * 64];                // [row block][k-step][lane]
     uint16_t knew[8 * DH];                               // the call's own K rows, cache type: [row][dim]
     uint16_t vnewT[DH * 8];                              // the call's own V rows, transposed: [dim][row]
-    float part[kAttnSlots * kAttnRowsPerPass * (DH + 4)];   // rows padded to 16 bytes for 128-bit LDS stores
+    float part[kAttnSlots * RP * (DH + 4)];              // rows padded to 16 bytes for 128-bit LDS stores
 };
 
 // Work items wg, wg + nwg, ... of the attention phase.  NTHREADS is 256 (4 wavefronts: wavefront w takes key
@@ -74,8 +75,8 @@ __device__ __forceinline__ void attn_load_kv(const AttnArgs &a, int item, AttnKv
 // `kv`: register block for the cached K/V; if `preloaded`, it already holds (or has in flight) the block of the
 // first item, wg.
 // F16: the cache, and the 16-bit halves of the queries and probabilities, are fp16 (else bf16).
-template <int DH, int NTHREADS, class Io, bool F16>
-__device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<DH> &L, int wg, int nwg, AttnKv<DH> &kv, bool preloaded,
+template <int DH, int NTHREADS, class Io, bool F16, int RP = kAttnRowsPerPass>
+__device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<DH, RP> &L, int wg, int nwg, AttnKv<DH> &kv, bool preloaded,
                                                 long long kv_off = 0) {
     constexpr int KS = DH / 32, DT = DH / 16, half = DH / 2, PR = DH + 2, PL = DH + 4;
     constexpr int NRH = NTHREADS / 256;      // wavefronts per key block
@@ -118,15 +119,15 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
         const int kb0 = c0 + wave * 32;           // first cached position of this wavefront's block
         const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
         const bool has_rows = R > rh * 8;         // this wavefront has a row block in the first pass at least
-        for (int r0 = 0; r0 < R; r0 += kAttnRowsPerPass) {
-            const int nr = (R - r0 < kAttnRowsPerPass) ? R - r0 : kAttnRowsPerPass;
+        for (int r0 = 0; r0 < R; r0 += RP) {
+            const int nr = (R - r0 < RP) ? R - r0 : RP;
             const int nblk = (nr + 7) / 8;
             // this wavefront's cached block goes in flight first: it does not depend on the queries (a later pass
             // over more rows loads it again, from L2: the registers are reused for the call's own rows below)
             if (!(preloaded && item == wg && r0 == 0)) attn_load_kv<DH, NTHREADS>(a, item, kv, kv_off);
             // queries: rotate, scale, split hi/lo, store in B-operand order.  Each thread first issues the loads of
             // all its elements (at most 8 for 32 rows of 128 dims), then does the arithmetic.
-            constexpr int QIT = (kAttnRowsPerPass * half + NTHREADS - 1) / NTHREADS;
+            constexpr int QIT = (RP * half + NTHREADS - 1) / NTHREADS;
             float qx[QIT], qy[QIT], qc[QIT], qs_[QIT];
 #pragma unroll
             for (int it = 0; it < QIT; ++it) {
@@ -243,7 +244,7 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
                     }
                     sum += __shfl_xor(sum, 16);
                     sum += __shfl_xor(sum, 32);
-                    float *prow = L.part + ((size_t)slot * kAttnRowsPerPass + rr) * PL;
+                    float *prow = L.part + ((size_t)slot * RP + rr) * PL;
                     f32x4 o[DT];
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
@@ -271,7 +272,7 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
 #pragma unroll
                 for (int p = 0; p < kAttnSlots; ++p) {
                     const bool on = p < 4 ? p < nbc : last;
-                    mp[p] = on ? L.part[((size_t)p * kAttnRowsPerPass + tid) * PL + DH] : -INFINITY;
+                    mp[p] = on ? L.part[((size_t)p * RP + tid) * PL + DH] : -INFINITY;
                     M = fmaxf(M, mp[p]);
                 }
                 float den = 0.f;
@@ -279,7 +280,7 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
                 for (int p = 0; p < kAttnSlots; ++p) {
                     const float w = (mp[p] == -INFINITY) ? 0.f : __expf(mp[p] - M);
                     wts[tid * 8 + p] = w;
-                    if (w != 0.f) den += w * L.part[((size_t)p * kAttnRowsPerPass + tid) * PL + DH + 1];
+                    if (w != 0.f) den += w * L.part[((size_t)p * RP + tid) * PL + DH + 1];
                 }
                 wts[tid * 8 + 5] = M;
                 wts[tid * 8 + 6] = den;
@@ -291,7 +292,7 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
 #pragma unroll
                 for (int p = 0; p < kAttnSlots; ++p) {
                     w[p] = wts[rr * 8 + p];
-                    v[p] = L.part[((size_t)p * kAttnRowsPerPass + rr) * PL + e];    // slots without data have weight 0
+                    v[p] = L.part[((size_t)p * RP + rr) * PL + e];    // slots without data have weight 0
                 }
                 float num = 0.f;
 #pragma unroll

@@ -156,10 +156,14 @@ D6144 = synth.WIDE_LAYER.with_(name="d6144-layer", d_model=6144, n_q_heads=40, n
 
 @pytest.mark.parametrize("shape,ctx,mode", [(synth.LLAMA8B_LAYER, 4096, 0), (synth.LLAMA8B_LAYER, 4096, 1), (L13, 1000, 0), (L13, 1000, 1),
                                             (L8_F16, 4096, 0), (L13_F16, 1000, 0), (L13_F32, 300, 0),
-                                            (synth.WIDE_LAYER, 2048, 0), (WIDE_BF16, 500, 0), (D6144, 300, 0)],
+                                            (synth.WIDE_LAYER, 2048, 0), (WIDE_BF16, 500, 0), (D6144, 300, 0),
+                                            # more attention work items than compute units: the attention variant with
+                                            # small workgroups (all m for 40 kv heads; m <= 4, two passes from m = 3, for the 8B shape)
+                                            (L13, 2100, 0), (synth.LLAMA8B_LAYER, 8300, 0)],
                          ids=["8b-layer-kernels", "8b-layer-fused", "13b-layer-kernels", "13b-layer-fused",
                               "8b-layer-f16-kernels", "13b-layer-f16-kernels", "13b-layer-f32-kernels",
-                              "wide-layer-f16-kernels", "wide-layer-bf16-kernels", "d6144-layer-bf16-kernels"])
+                              "wide-layer-f16-kernels", "wide-layer-bf16-kernels", "d6144-layer-bf16-kernels",
+                              "13b-layer-many-items", "8b-layer-ctx8300"])
 def test_layer_step_full_width_shapes(ad, shape, ctx, mode):
     """The single-layer microbenchmark workload: prefilled N(0,1) cache, N(0,1) hidden rows, m in {1,2,3,4,6,8}
     at positions ctx .. ctx+m-1, cache length reset before each call."""
