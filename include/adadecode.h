@@ -114,9 +114,11 @@ ad_status ad_layer_step(const ad_model *, ad_kv *, int32_t layer, void *hidden, 
 
 /* The same rows through layers first_layer .. first_layer + n_layers - 1 one after the other: the stretch of
  * Algorithm 1's layer loop between two points where the set of pending rows can change (an exit head, or the layer at
- * which earlier tokens' deferred rows join).  Equivalent to n_layers calls of ad_layer_step with the same hidden, pos
- * and m (so pos[0] must equal the cache length of every layer in the range); in AD_LAYER_FUSED mode the whole range
- * is one kernel launch.  Errors as ad_layer_step; a range that leaves 1..n_layers is AD_ERANGE. */
+ * which earlier tokens' deferred rows join).  Computes what n_layers calls of ad_layer_step with the same hidden, pos
+ * and m compute (so pos[0] must equal the cache length of every layer in the range); results may differ from those
+ * calls in the last bits, because inside a range a layer hands its output to the next layer's QKV projection already
+ * normalised and packed.  In AD_LAYER_FUSED mode the whole range is one kernel launch.  Errors as ad_layer_step; a
+ * range that leaves 1..n_layers is AD_ERANGE. */
 ad_status ad_layer_steps(const ad_model *, ad_kv *, int32_t first_layer, int32_t n_layers, void *hidden, const int32_t *pos,
                          int32_t m, void *stream);
 
