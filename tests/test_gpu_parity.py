@@ -97,7 +97,8 @@ def test_layer_steps_ragged_small_models(ad, shape, mode):
 DEEP = synth.TINY_BF16.with_(name="tiny-bf16-6-layers", n_layers=6, exit_layers=(2, 4))
 
 
-@pytest.mark.parametrize("shape,mode", with_modes([DEEP, synth.TINY_GQA, ODD.with_(name="tiny-odd-bf16", dtype=synth.BF16), synth.TINY]))
+@pytest.mark.parametrize("shape,mode", with_modes([DEEP, synth.TINY_GQA, ODD.with_(name="tiny-odd-bf16", dtype=synth.BF16), synth.TINY,
+                                                    DEEP.with_(name="tiny-f16-6-layers", dtype=synth.F16)]))
 def test_layer_ranges_match_oracle(ad, shape, mode):
     """ad_layer_steps: the same rows through a stretch of consecutive layers in one call (one launch in the fused
     mode), for stretches of every length, against the oracle taken layer by layer."""
