@@ -227,6 +227,18 @@ def main():
                 torch.cuda.synchronize()
                 us1, _ = timed_batches(same, calls)
                 micro[str(m)]["us_single_weight_copy_cache_assisted"] = round(us1, 2)
+            if m in (1, 8) and L % 8 == 0:
+                # the same layers as stretches of 8 per call (what ad_generate issues between two exit heads)
+                def stretch(i):
+                    first = (i * 8) % L + 1
+                    for layer in range(first, first + 8):
+                        g.kv_set_len(layer, ctx_micro)
+                    g.ad_layer_steps(first, 8, h, pos)
+                for i in range(8):
+                    stretch(i)
+                torch.cuda.synchronize()
+                us8, _ = timed_batches(stretch, max(10, calls // 8))
+                micro[str(m)]["us_per_layer_in_stretches_of_8"] = round(us8 / 8, 2)
             log(f"[bench] layer step m={m}: {us:.2f} us (median of batches {us_med:.2f}), {gbs:.1f} GB/s ({gbs / HBM_PEAK_GBS:.1%} of peak)")
         micro = {"ctx": ctx_micro, "calls_per_m": args.micro_calls, "distinct_weight_copies": L,
                  "algorithmic_bytes_m1": layer_step_bytes(shape, ctx_micro, 1), "by_m": micro}
