@@ -281,7 +281,7 @@ void orc_embed(const orc_model *model, const int32_t *tokens, int32_t m, double 
             hidden[(size_t)r * d + i] = weight_at(model->top.embed, model->cfg.wdtype, (size_t)tokens[r] * d + i);
 }
 
-/* Algorithm 1, "update KV cache at layer l by processing all tokens in P[l] in parallel": the rows are
+/* Algorithm 1, the layer-update step (one layer over all rows pending at it, their K/V joining its cache): the rows are
  * the pending tokens of this layer, at consecutive positions that continue the layer's cache.  Row r
  * attends to every cached position 0..pos[r], which includes the rows before it in the same call. */
 int orc_layer_step(const orc_model *model, orc_kv *kv, int32_t layer, double *hidden, const int32_t *pos,
@@ -429,15 +429,16 @@ void orc_verify(const orc_model *model, const double *hidden, const int32_t *dra
 
 /* ---- generation ----------------------------------------------------------------------------------- */
 
-/* "KV cache <- LM(x)": the prompt rows go through every layer, a chunk of rows at a time.  If last_h is
- * given it receives the final-layer hidden state of the last row. */
-static int prefill(const orc_model *model, orc_kv *kv, const int32_t *tokens, int32_t n, double *last_h) {
+/* Algorithm 1's initialisation of the cache from the prompt: the rows of positions first .. n-1 go through every
+ * layer, a chunk of rows at a time (the cache holds the rows before `first` already).  If last_h is given it
+ * receives the final-layer hidden state of the last row. */
+static int prefill(const orc_model *model, orc_kv *kv, const int32_t *tokens, int32_t first, int32_t n, double *last_h) {
     const orc_config *c = &model->cfg;
     const int32_t chunk = 64, d = c->d_model;
     double *h = (double *)malloc(sizeof(double) * (size_t)chunk * d);
     int32_t *pos = (int32_t *)malloc(sizeof(int32_t) * (size_t)chunk);
     int rc = 0;
-    for (int32_t s = 0; s < n && rc == 0; s += chunk) {
+    for (int32_t s = first; s < n && rc == 0; s += chunk) {
         const int32_t m = (n - s < chunk) ? n - s : chunk;
         orc_embed(model, tokens + s, m, h);
         for (int32_t r = 0; r < m; ++r) pos[r] = s + r;
@@ -455,7 +456,7 @@ int orc_generate_greedy(const orc_model *model, orc_kv *kv, const int32_t *promp
     const orc_config *c = &model->cfg;
     double *h = (double *)malloc(sizeof(double) * (size_t)c->d_model);
     orc_kv_truncate(kv, 0);
-    int rc = prefill(model, kv, prompt, n_prompt, h);
+    int rc = prefill(model, kv, prompt, 0, n_prompt, h);
     int32_t n = 0, pos = n_prompt;
     while (rc == 0 && n < max_new) {
         int32_t tok;
@@ -540,8 +541,15 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
     memset(&st, 0, sizeof st);
     int64_t n_events = 0;
 
-    orc_kv_truncate(kv, 0);
-    int rc = prefill(model, kv, prompt, n_prompt - 1, NULL);
+    /* the cache starts from the prompt without its last token; the rows of the first keep_cache positions may be taken
+     * over from an earlier run on a prompt that began with the same tokens (a row depends on the tokens up to its
+     * position only), the rest is computed */
+    const int32_t keep = gp->keep_cache;
+    if (keep < 0 || keep > n_prompt - 1) return -1;
+    for (int32_t l = 1; l <= L; ++l)
+        if (orc_kv_len(kv, l) < keep) return -1;
+    orc_kv_truncate(kv, keep);
+    int rc = prefill(model, kv, prompt, keep, n_prompt - 1, NULL);
     int32_t cur = prompt[n_prompt - 1], pos = n_prompt - 1;
     int32_t n_rows = 0, n_y = 0, n_verified = 0, done = 0;
 

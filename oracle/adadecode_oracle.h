@@ -141,6 +141,10 @@ typedef struct {
     int32_t no_verify;              /* 1: no verification -- every early prediction is kept as emitted, and the last
                                        layer only produces the next token from the newest row (the output may then
                                        differ from plain decoding) */
+    int32_t keep_cache;             /* 0, or the number of leading prompt positions (at most n_prompt - 1) whose rows the
+                                       cache already holds at every layer from an earlier run on a prompt with the same
+                                       leading tokens: they are kept instead of being computed again (a time saver for
+                                       tests that restart a run from a longer prompt; the result is the same) */
 } orc_gen_params;
 
 typedef struct {

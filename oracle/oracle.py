@@ -46,7 +46,8 @@ assert EVENT_DTYPE.itemsize == C.sizeof(Event)
 class GenParams(C.Structure):
     _fields_ = [("gamma", C.c_double), ("max_pending", C.c_int32), ("max_new", C.c_int32), ("eos_id", C.c_int32),
                 ("forced_exit", C.c_void_p), ("scripted_draft", C.c_void_p),
-                ("temperature", C.c_double), ("uniforms", C.c_void_p), ("head_mask", C.c_int32), ("no_verify", C.c_int32)]
+                ("temperature", C.c_double), ("uniforms", C.c_void_p), ("head_mask", C.c_int32), ("no_verify", C.c_int32),
+                ("keep_cache", C.c_int32)]
 
 
 class Stats(C.Structure):
@@ -146,7 +147,9 @@ def confidence(z) -> Tuple[int, float, float]:
 class Oracle:
     """A model instance of the oracle over a synth.ModelShape and its weight dict."""
 
-    def __init__(self, shape, weights: Dict[str, np.ndarray], max_pos: int):
+    def __init__(self, shape, weights: Dict[str, np.ndarray], max_pos: int, kv_dtype: Optional[int] = None):
+        """kv_dtype: storage type of the oracle's KV cache (0 fp32 = unrounded fp64 values, 1 bf16, 2 fp16); by default
+        the model's own type, as the workloads define it."""
         self.shape = shape
         self.weights = weights            # keeps the buffers alive
         self.L = lib()
@@ -154,7 +157,7 @@ class Oracle:
                      shape.vocab, shape.rope_base, shape.rms_eps, shape.dtype, len(shape.exit_layers))
         for i, l in enumerate(shape.exit_layers):
             cfg.exit_layers[i] = l
-        cfg.kv_dtype = shape.dtype        # a 16-bit workload keeps a KV cache of its type
+        cfg.kv_dtype = shape.dtype if kv_dtype is None else kv_dtype   # a 16-bit workload keeps a KV cache of its type
         want = (np.float32, np.uint16, np.float16)[shape.dtype]
         for k, v in weights.items():
             assert v.dtype == want and v.flags["C_CONTIGUOUS"], k
@@ -261,9 +264,10 @@ class Oracle:
     def generate_ada(self, prompt, max_new: int, gamma: float, max_pending: int = 5, eos_id: int = -1,
                      forced_exit: Optional[np.ndarray] = None, scripted_draft: Optional[np.ndarray] = None,
                      max_events: int = 1 << 20, temperature: float = 0.0, uniforms: Optional[np.ndarray] = None,
-                     head_mask: int = 0, no_verify: bool = False):
+                     head_mask: int = 0, no_verify: bool = False, keep_cache: int = 0):
         """temperature > 0: sampled decoding with the draws `uniforms`, float32 [max_pos, n_exit + 3].
-        head_mask / no_verify: the ablation switches (bit i enables exit head i; drafts are kept unchecked)."""
+        head_mask / no_verify: the ablation switches (bit i enables exit head i; drafts are kept unchecked).
+        keep_cache: leading prompt positions whose cache rows an earlier run on the same leading tokens left behind."""
         p = _i32(prompt)
         if temperature > 0:
             uniforms = np.ascontiguousarray(uniforms, dtype=np.float32)
@@ -275,7 +279,7 @@ class Oracle:
             scripted_draft = _i32(scripted_draft)
             assert scripted_draft.size >= self.max_pos
         gp = GenParams(gamma, max_pending, max_new, eos_id, _ptr(forced_exit), _ptr(scripted_draft), temperature,
-                       _ptr(uniforms) if temperature > 0 else None, head_mask, int(no_verify))
+                       _ptr(uniforms) if temperature > 0 else None, head_mask, int(no_verify), int(keep_cache))
         out = np.empty(max_new + max_pending + 2, dtype=np.int32)
         ev = np.zeros(max_events, dtype=EVENT_DTYPE)
         n, nev, st = C.c_int32(), C.c_int64(), Stats()

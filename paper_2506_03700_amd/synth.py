@@ -195,6 +195,16 @@ def make_hidden(shape: ModelShape, seed: int, m: int) -> np.ndarray:
     return _tensor_seed(seed, "hidden").standard_normal((m, shape.d_model), dtype=np.float32)
 
 
+# The single-layer microbenchmark: row counts, calls per row count, and the seed of call number `call` with m rows
+# (every call draws its own hidden rows).
+MICRO_M = (1, 2, 3, 4, 6, 8)
+MICRO_CALLS = 1000
+
+
+def micro_call_seed(m: int, call: int) -> int:
+    return 100000 + 1000 * m + call
+
+
 def make_kv_prefill(shape: ModelShape, seed: int, layer: int, n_pos: int) -> Tuple[np.ndarray, np.ndarray]:
     """K and V values for positions [0, n_pos) of one layer, each [n_pos, n_kv_heads, head_dim], N(0,1).
 

@@ -1,28 +1,29 @@
 """GPU parity at the benchmark's full model sizes (8B: 32 layers, vocabulary 128256; 13B: 40 layers), in the
-launch configuration bench.py times.
+launch configuration bench.py times, and at the long-generation workload's context lengths.
 
 The oracle cannot decode a thousand tokens of an 8B model in test time, so each full-size model is checked two
-ways: (a) a free-run comparison of decisions and tokens against the oracle on a shorter prompt / generation
-length (every kernel runs at its real shape: real d, heads, FFN, vocabulary, depth), and (b) a property that
-holds at any size and that the paper guarantees (Sec. 4.2): the tokens AdaDecode emits under a forced exit
-schedule -- ragged layer steps, deferred layers, rejections and rollbacks included -- equal the tokens of
-plain greedy decoding (gamma = 1) by the same kernels, over the benchmark's full generation length.
+ways: (a) a free-run comparison of every decision and token against the oracle over a window at the start of the
+workload (8B: the workload's own 256-token prompt and its first 128 generated tokens; 13B: a 64-token prompt and
+the first 64 generated tokens), once at the workload's threshold and once under a forced exit schedule with
+scripted wrong drafts, so that ragged layer steps, deferred layers, rejections and rollbacks all occur in the
+window; every kernel runs at its real shape (real d, heads, FFN, vocabulary, depth); and (b) a property that holds
+at any size and that the paper guarantees (Sec. 4.2): the tokens AdaDecode emits under a forced exit schedule
+equal the tokens of plain greedy decoding (gamma = 1) by the same kernels, over the benchmark's full generation
+length.  The long-generation workload (context up to 9216) is checked against the oracle on a 4-layer model of
+the 8B layer shape whose caches are prefilled beyond position 8192, with the ragged catch-up pattern of Fig. 2
+(left) scaled up to 8 rows, followed by the verification.
 """
 import numpy as np
 import pytest
 
 from oracle import oracle as orc
 from paper_2506_03700_amd import synth
+from compare_runs import ResumingOracle
+from tolerances import NEAR_TIE, TOL, check_kv, check_rows
 
 pytestmark = pytest.mark.gpu
 
-NEAR_TIE = 1e-2
-TOL = 2e-2
-
-
-def _compare_with_oracle(shape, g, o, prompt, n_new, gamma, cap, **kw):
-    from compare_runs import compare_runs as cmp
-    return cmp(g, o, prompt, n_new, gamma, cap, TOL, **kw)
+BF16_TOL = TOL[synth.BF16]
 
 
 def _gpu_top2_after(g, tokens):
@@ -43,87 +44,190 @@ def _gpu_top2_after(g, tokens):
     return top.values.cpu().numpy(), top.indices.cpu().numpy()
 
 
-def _assert_same_or_near_tie(g, prompt, t_ada, t_ref):
-    """The two token sequences must be identical up to the first position where the GPU's own top-2 logit
-    margin is below the near-tie threshold (there, the two runs may pick either of the two tokens: a row computed
-    inside an m-row call and in a call of its own differs in the order of a few fp32 sums)."""
-    diff = np.nonzero(t_ada != t_ref)[0]
-    if diff.size == 0:
-        return len(t_ref)
-    i = int(diff[0])
-    vals, ids = _gpu_top2_after(g, np.concatenate([prompt, t_ref[:i]]))
-    assert vals[0] - vals[1] < NEAR_TIE, f"sequences differ at {i} but the margin is {vals[0] - vals[1]}"
-    assert {int(t_ada[i]), int(t_ref[i])} == {int(ids[0]), int(ids[1])}
-    return i
+def _forced_equals_greedy(g, prompt, n_new, sched, max_partings):
+    """Sec. 4.2 on the GPU's own runs: the forced-schedule run and the plain greedy run (gamma = 1) emit the same
+    tokens.  A row computed inside an m-row call and in a call of its own differs in the order of a few fp32 sums,
+    so at a near tie of the GPU's own logits (top-2 margin below NEAR_TIE) the two runs may pick either of the two
+    tokens; that is checked, both runs then continue from the greedy run's prefix, and the number of such partings
+    is bounded.  Returns (tokens covered, partings, statistics of the first forced run)."""
+    p = [int(t) for t in prompt]
+    remaining, partings, stats = n_new, 0, None
+    while remaining > 0:
+        pa = np.asarray(p, dtype=np.int32)
+        t_ada, s_ada, _ = g.ad_generate(pa, remaining, g.shape.gamma, 7, forced_exit=sched, want_events=False)
+        t_ref, s_ref, _ = g.ad_generate(pa, remaining, 1.0, 0, want_events=False)
+        assert s_ref["early_preds"] == 0 and s_ref["layer_steps"] == remaining * g.shape.n_layers
+        assert len(t_ada) == len(t_ref) == remaining
+        stats = stats or s_ada
+        diff = np.nonzero(t_ada != t_ref)[0]
+        if diff.size == 0:
+            remaining = 0
+            break
+        i = int(diff[0])
+        vals, ids = _gpu_top2_after(g, np.concatenate([pa, t_ref[:i]]))
+        assert vals[0] - vals[1] < NEAR_TIE, f"sequences differ {len(p) - len(prompt) + i} tokens in but the margin is {vals[0] - vals[1]}"
+        assert {int(t_ada[i]), int(t_ref[i])} == {int(ids[0]), int(ids[1])}
+        partings += 1
+        assert partings <= max_partings, f"more than {max_partings} near-tie partings"
+        p += [int(t) for t in t_ref[:i + 1]]
+        remaining -= i + 1
+    return n_new - remaining, partings, stats
 
 
-@pytest.mark.parametrize("name,n_prompt,n_new,mode", [("8b", 48, 20, 0), ("8b", 48, 20, 1), ("13b", 32, 12, 0)],
+_shared = {}
+
+
+def _weights_and_oracle(name, max_pos):
+    """Weights and (cached) oracle of a full-size model, shared by the test's layer modes."""
+    if name not in _shared:
+        _shared.clear()                  # one full-size model at a time in host memory
+        shape = synth.SHAPES[name]
+        print(f"case {name}: generating weights", flush=True)
+        w = synth.make_weights(shape, seed=0)
+        _shared[name] = (w, ResumingOracle(orc.Oracle(shape, w, max_pos=max_pos)))
+    return _shared[name]
+
+
+@pytest.mark.parametrize("name,n_prompt,n_new,mode", [("8b", 256, 128, 0), ("8b", 256, 128, 1), ("13b", 64, 64, 0)],
                          ids=["8b-kernels", "8b-fused", "13b-kernels"])
 def test_full_model_against_oracle_and_greedy_property(name, n_prompt, n_new, mode):
-    import torch
+    """Compared with the oracle: prompt positions 0 .. n_prompt-1 and generated tokens 0 .. n_new-1 (8B: 256 + 128,
+    13B: 64 + 64), every event of the two runs.  Compared with the GPU's own greedy run: all gen_len tokens."""
+    from compare_runs import compare_runs
     from paper_2506_03700_amd import binding as ad
     shape = synth.SHAPES[name]
-    print(f"case {name}: generating weights", flush=True)
-    w = synth.make_weights(shape, seed=0)
     max_pos = shape.prompt_len + shape.gen_len + 8
+    w, o = _weights_and_oracle(name, n_prompt + n_new + 8)
     g = ad.Model(shape, w, max_pos=max_pos, layer_mode=mode)    # 0: one kernel per phase, 1: fused persistent kernel
     prompt = synth.make_prompt(shape, 0)
 
-    # (a) against the oracle, shorter run, natural threshold and a forced schedule with scripted wrong drafts
-    o = orc.Oracle(shape, w, max_pos=n_prompt + n_new + 8)
-    print(f"case {name}: oracle comparison, gamma {shape.gamma}", flush=True)
-    n, st = _compare_with_oracle(shape, g, o, prompt[:n_prompt], n_new, shape.gamma, 7)
-    assert n > 0
+    # (a) against the oracle: the workload's threshold, then a forced schedule with scripted wrong drafts.  Every
+    # difference must be a near tie of the oracle's own logits (margin below 1e-2, against a logit error of about
+    # 3e-3 on these models); seen: none to two per run on the 8B model, up to five on the 13B model, whose smaller
+    # vocabulary and wider rows put its top-2 logits closer together
+    lim = 4 if name == "8b" else 8
+    print(f"case {name} mode {mode}: oracle comparison, gamma {shape.gamma}, {n_prompt} + {n_new} tokens", flush=True)
+    r = compare_runs(g, o, prompt[:n_prompt], n_new, shape.gamma, 7, BF16_TOL, max_resyncs=lim)
+    assert r.tokens == n_new and r.agreed >= r.total - lim, str(r)
     sched_small = synth.make_forced_schedule(shape, 3, max_pos, probs=[0.25, 0.25, 0.25])
     script = np.full(max_pos, -1, dtype=np.int32)
-    script[n_prompt + 3] = 7
-    print(f"case {name}: oracle comparison, forced schedule", flush=True)
-    n, st = _compare_with_oracle(shape, g, o, prompt[:n_prompt], n_new, shape.gamma, 7, forced_exit=sched_small, scripted_draft=script)
-    assert st["early_preds"] > 0
-    o.close()
+    script[[n_prompt + 3, n_prompt + 21, n_prompt + 40]] = [7, 8, 9]
+    print(f"case {name} mode {mode}: oracle comparison, forced schedule with scripted drafts", flush=True)
+    r = compare_runs(g, o, prompt[:n_prompt], n_new, shape.gamma, 7, BF16_TOL, max_resyncs=lim, forced_exit=sched_small, scripted_draft=script)
+    assert r.tokens == n_new and r.agreed >= r.total - lim, str(r)
+    assert r.stats["early_preds"] > n_new // 4 and r.stats["rejections"] >= 3
+    assert max(i for i, c in enumerate(r.stats["steps_by_m"]) if c) >= 4
 
     # (b) full benchmark length: forced schedule == plain greedy, by the same kernels
-    print(f"case {name}: full-length property run ({shape.prompt_len} + {shape.gen_len} tokens)", flush=True)
+    print(f"case {name} mode {mode}: full-length property run ({shape.prompt_len} + {shape.gen_len} tokens)", flush=True)
     sched = synth.make_forced_schedule(shape, 0, max_pos)
-    t_ada, s_ada, _ = g.ad_generate(prompt, shape.gen_len, shape.gamma, 7, forced_exit=sched, want_events=False)
-    t_ref, s_ref, _ = g.ad_generate(prompt, shape.gen_len, 1.0, 0, want_events=False)
-    assert s_ref["early_preds"] == 0 and s_ref["layer_steps"] == shape.gen_len * shape.n_layers
+    covered, partings, s_ada = _forced_equals_greedy(g, prompt, shape.gen_len, sched, max_partings=3)
+    print(f"case {name} mode {mode}: forced-schedule and greedy tokens agree over {covered} tokens, {partings} near-tie partings", flush=True)
+    assert covered == shape.gen_len
     assert s_ada["early_preds"] > shape.gen_len // 4 and max(i for i, c in enumerate(s_ada["steps_by_m"]) if c) >= 4
-    assert len(t_ada) == len(t_ref) == shape.gen_len
-    agreed = _assert_same_or_near_tie(g, prompt, t_ada, t_ref)
-    print(f"case {name}: forced-schedule and greedy tokens agree on the first {agreed} of {shape.gen_len}", flush=True)
-    assert agreed >= 32
     g.close()
+    if mode == 1 or name == "13b":
+        _shared.clear()
 
 
-def test_long_context_forced_schedule_property():
-    """The long-generation workload (prompt 1024, forced exits, context growing past 8192), shortened to a
-    generation length that keeps the test under a minute: AdaDecode's tokens equal greedy's, and the
-    attention kernel is checked against the oracle at a context beyond 8192 on one layer."""
+LONG4 = synth.LLAMA8B_LONG.with_(name="8b-long-4-layers", n_layers=4, exit_layers=(1, 2, 3), vocab=8192)
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["kernels", "fused"])
+def test_long_context_ragged_catch_up_against_oracle(mode):
+    """Deep-context window of the long-generation workload, against the oracle: 4 layers of the 8B layer shape, every
+    layer's cache prefilled with N(0,1) entries; at two places (positions 8188.., which straddle 8192, and 9200..)
+    eight tokens go through the layers in the order Algorithm 1 gives them when seven of them leave early (Fig. 2,
+    left, scaled up): the layers' caches have different lengths throughout, rows catch up in calls of 1 to 8 rows,
+    and the last call (8 rows at the last layer) is followed by the verification with one wrong draft.  Hidden rows,
+    appended K/V, row argmaxes and the verification's outcome are compared."""
     import torch
     from paper_2506_03700_amd import binding as ad
-    shape = synth.LLAMA8B_LAYER
-    ctx = 9000
+    shape = LONG4
+    L = shape.n_layers
+    n_pos = 9216
     w = synth.make_weights(shape, seed=0)
-    o = orc.Oracle(shape, w, max_pos=ctx + 8)
-    g = ad.Model(shape, w, max_pos=ctx + 8)
-    k, v = synth.make_kv_prefill(shape, 1, 0, ctx)
-    o.kv_write(1, 0, k.reshape(ctx, -1), v.reshape(ctx, -1))
-    g.kv_fill(1, k, v)
-    for m in (1, 5, 8):
-        print(f"case 8b-layer ctx={ctx} m={m}", flush=True)
-        o.kv_set_len(1, ctx)
-        g.kv_set_len(1, ctx)
-        h = synth.make_hidden(shape, 7 + m, m)
-        pos = np.arange(ctx, ctx + m)
-        ho = o.layer_step(1, h, pos)
-        hg = torch.from_numpy(h).to("cuda:0")
-        g.ad_layer_step(1, hg, pos)
-        err = float(np.max(np.abs((hg.cpu().numpy() - h) - (ho - h))) / np.max(np.abs(ho - h)))
-        assert err <= TOL, f"m={m}: branch rel err {err}"
+    o = orc.Oracle(shape, w, max_pos=n_pos)
+    g = ad.Model(shape, w, max_pos=n_pos, layer_mode=mode)
+    for l in range(1, L + 1):
+        k, v = synth.make_kv_prefill(shape, 1, l, n_pos - 8)
+        o.kv_write(l, 0, k.reshape(n_pos - 8, -1), v.reshape(n_pos - 8, -1))
+        g.kv_fill(l, k, v)
+    # exit layer of each of the eight tokens (0: runs to the last layer)
+    exits = [1, 2, 1, 3, 1, 2, 1, 0]
+    rng = np.random.default_rng(3)
+    for rnd, base in enumerate((8188, 9200)):
+        for l in range(1, L + 1):
+            o.kv_set_len(l, base)
+            g.kv_set_len(l, base)
+        toks = rng.integers(0, shape.vocab, size=8).astype(np.int32)
+        Ho = o.embed(toks)
+        Hg = g.ad_embed(toks)
+        depth = [0] * 8
+        calls = []
+        for i, ex in enumerate(exits):
+            l = 1
+            while l <= (ex if ex else L):
+                first = i
+                while first > 0 and depth[first - 1] == l - 1:
+                    first -= 1
+                m = i - first + 1
+                # the second round hands a stretch of layers over in one call where the rows stay the same
+                n = 1
+                if rnd == 1:
+                    while l + n <= (ex if ex else L) and not (first > 0 and depth[first - 1] == l + n - 1):
+                        n += 1
+                pos = np.arange(base + first, base + first + m)
+                print(f"case {shape.name} mode {mode} base={base} token {i}: layers {l}..{l + n - 1}, rows {first}..{i}", flush=True)
+                for ll in range(l, l + n):
+                    Ho[first:i + 1] = o.layer_step(ll, Ho[first:i + 1], pos)
+                rows = Hg[first:i + 1]
+                assert rows.is_contiguous()
+                if n == 1:
+                    g.ad_layer_step(l, rows, pos)
+                else:
+                    g.ad_layer_steps(l, n, rows, pos)
+                check_rows(shape.dtype, rows.cpu().numpy(), Ho[first:i + 1], f"base {base} layers {l}..{l + n - 1} rows {first}..{i}")
+                for k in range(first, i + 1):
+                    depth[k] = l + n - 1
+                calls.append(m)
+                l += n
+            lens = g.kv_lens()
+            assert lens == o.kv_lens()
+            if i < 7:
+                assert len(set(lens)) > 1          # ragged: the layers' caches end at different positions
+        assert depth == [L] * 8 and max(calls) == 8 and g.kv_lens() == [base + 8] * L
+        for l in range(1, L + 1):
+            ko, vo = o.kv_read(l, base, 8)
+            kg, vg = g.kv_read(l, base + 8)
+            check_kv(shape.dtype, kg[base:], ko, f"K of layer {l} at {base}")
+            check_kv(shape.dtype, vg[base:], vo, f"V of layer {l} at {base}")
+        # verification of the seven drafts: the oracle's own row argmaxes as drafts, one of them made wrong
+        _, _, arg, mar = o.verify(Ho, [0] * 7)
+        for bad in (None, 4):
+            draft = [int(x) for x in arg[:7]]
+            if bad is not None:
+                draft[bad] = (draft[bad] + 1) % shape.vocab
+            want = o.verify(Ho, draft)
+            got = g.ad_verify(Hg, draft)
+            if mar.min() >= NEAR_TIE:
+                assert (got[0], got[1]) == (want[0], want[1]) and list(got[2]) == list(want[2])
+            else:
+                ok = mar >= NEAR_TIE
+                assert list(np.asarray(got[2])[ok]) == list(np.asarray(want[2])[ok])
+        zo = np.stack([o.head(-1, Ho[r], want_logits=True)[3] for r in range(8)])
+        zg = g.ad_head_logits(L, Hg).cpu().numpy()
+        check_rows(shape.dtype, zg, zo, f"final logits at base {base}")
     g.close()
     o.close()
 
+
+def test_long_generation_forced_schedule_property():
+    """The long-generation workload (prompt 1024, forced exits, context growing past 8192) on 8 layers of the 8B
+    shape with a reduced vocabulary and a generation length that keeps the test under a minute: AdaDecode's tokens
+    equal greedy's over all of it (a property, GPU against GPU; the oracle comparison at this depth of context is
+    the test above)."""
+    from paper_2506_03700_amd import binding as ad
     shape = synth.LLAMA8B_LONG.with_(n_layers=8, exit_layers=(2, 4, 6), vocab=16384)
     w = synth.make_weights(shape, seed=0)
     n_prompt, n_new = 1024, 1536
@@ -131,10 +235,41 @@ def test_long_context_forced_schedule_property():
     prompt = synth.make_prompt(shape, 0, n=n_prompt)
     sched = synth.make_forced_schedule(shape, 0, n_prompt + n_new + 8)
     print("case 8b-long (8 layers): forced schedule vs greedy", flush=True)
-    t_ada, s_ada, _ = g.ad_generate(prompt, n_new, shape.gamma, 7, forced_exit=sched, want_events=False)
-    t_ref, _, _ = g.ad_generate(prompt, n_new, 1.0, 0, want_events=False)
-    agreed = _assert_same_or_near_tie(g, prompt, t_ada, t_ref)
-    print(f"case 8b-long: agree on the first {agreed} of {n_new}", flush=True)
-    assert agreed >= 32
+    covered, partings, s_ada = _forced_equals_greedy(g, prompt, n_new, sched, max_partings=3)
+    print(f"case 8b-long: agree over {covered} of {n_new} tokens, {partings} near-tie partings", flush=True)
+    assert covered == n_new
     assert s_ada["rejections"] > 0 and s_ada["early_preds"] > n_new // 4
     g.close()
+
+
+def test_lightweight_exit_head_at_full_width_and_vocabulary():
+    """Sec. 2.1's head E = E* T at the 8B model's width and vocabulary (d 4096, V 128256): the transform GEMM, its
+    packed hand-over to the vocabulary pass, and the two-pass argmax / log-sum-exp, against the oracle, for single
+    rows (the exit head's case) and for 8 rows at once."""
+    import torch
+    from paper_2506_03700_amd import binding as ad
+    shape = synth.LLAMA8B.with_(name="8b-head-T", n_layers=2, exit_layers=(1,))
+    w = synth.make_weights(shape, seed=4, with_T=True, T_std=0.02, norm_jitter=0.1)
+    o = orc.Oracle(shape, w, max_pos=8)
+    g = ad.Model(shape, w, max_pos=8)
+    h = synth.make_hidden(shape, seed=77, m=8)
+    hg = torch.from_numpy(h).to("cuda:0")
+    z = g.ad_head_logits(1, hg).cpu().numpy()
+    n_cmp = 0
+    for r in range(8):
+        tok_o, conf_o, margin, zo = o.head(0, h[r], want_logits=True)
+        check_rows(shape.dtype, z[r], zo, f"logits of E* T, row {r}")
+        if r < 3:
+            print(f"case {shape.name} row {r}", flush=True)
+            tok_g, conf_g = g.ad_exit_head(1, hg[r])
+            assert abs(conf_g - conf_o) <= 5 * BF16_TOL * conf_o
+            if margin >= NEAR_TIE:
+                assert tok_g == tok_o
+                n_cmp += 1
+    assert n_cmp >= 1
+    # T = I special case at this size: the head at the last layer (no transform) on the same rows gives E* norm(h)
+    zf = g.ad_head_logits(shape.n_layers, hg[:2].contiguous()).cpu().numpy()
+    for r in range(2):
+        check_rows(shape.dtype, zf[r], o.head(-1, h[r], want_logits=True)[3], f"logits of E*, row {r}")
+    g.close()
+    o.close()

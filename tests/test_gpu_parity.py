@@ -11,17 +11,9 @@ import pytest
 
 from oracle import oracle as orc
 from paper_2506_03700_amd import synth
+from tolerances import NEAR_TIE, REG, TOL, check_kv, check_rows, rel_err
 
 pytestmark = pytest.mark.gpu
-
-TOL = {synth.F32: 1e-4, synth.BF16: 2e-2, synth.F16: 2.5e-3}
-NEAR_TIE = 1e-2
-
-
-def rel_err(got, want):
-    want = np.asarray(want, dtype=np.float64)
-    got = np.asarray(got, dtype=np.float64)
-    return float(np.max(np.abs(got - want)) / max(np.max(np.abs(want)), 1e-30))
 
 
 @pytest.fixture(scope="module")
@@ -72,21 +64,21 @@ def test_layer_steps_ragged_small_models(ad, shape, mode):
         for l in range(1, shape.n_layers + 1):
             ho = o.layer_step(l, ho, pos)
             g.ad_layer_step(l, hg, pos)
-            e = rel_err(hg.cpu().numpy(), ho)
-            assert e <= tol, f"layer {l} rows {start}..{start + m - 1}: rel err {e}"
+            check_rows(shape.dtype, hg.cpu().numpy(), ho, f"layer {l} rows {start}..{start + m - 1}")
         start += m
     assert start == T and g.kv_lens() == o.kv_lens() == [T] * shape.n_layers
     for l in range(1, shape.n_layers + 1):
         ko, vo = o.kv_read(l, 0, T)
         kg, vg = gpu_kv(g, l, T)
-        assert rel_err(kg, ko) <= tol and rel_err(vg, vo) <= tol
+        check_kv(shape.dtype, kg, ko, f"K of layer {l}")
+        check_kv(shape.dtype, vg, vo, f"V of layer {l}")
     # heads on the last rows: logits, greedy token, confidence
     layers = list(shape.exit_layers) + [shape.n_layers]
     for hi, layer in enumerate(layers):
         z = g.ad_head_logits(layer, hg).cpu().numpy()
         for r in range(hg.shape[0]):
             tok_o, conf_o, margin, zo = o.head(hi if layer != shape.n_layers else -1, ho[r], want_logits=True)
-            assert rel_err(z[r], zo) <= tol
+            check_rows(shape.dtype, z[r], zo, f"logits of the head at layer {layer}, row {r}")
             tok_g, conf_g = g.ad_exit_head(layer, hg[r])
             if margin >= NEAR_TIE:
                 assert tok_g == tok_o
@@ -121,8 +113,7 @@ def test_layer_ranges_match_oracle(ad, shape, mode):
             for l in range(first, first + n):
                 ho = o.layer_step(l, ho, pos)
             g.ad_layer_steps(first, n, hg, pos)
-            e = rel_err(hg.cpu().numpy(), ho)
-            assert e <= tol, f"case {case}: layers {first}..{first + n - 1}, rows {start}..{start + m - 1}: rel err {e}"
+            check_rows(shape.dtype, hg.cpu().numpy(), ho, f"case {case}: layers {first}..{first + n - 1}, rows {start}..{start + m - 1}")
             first += n
         assert first == L + 1
         start += m
@@ -130,7 +121,8 @@ def test_layer_ranges_match_oracle(ad, shape, mode):
     for l in range(1, L + 1):
         ko, vo = o.kv_read(l, 0, start)
         kg, vg = gpu_kv(g, l, start)
-        assert rel_err(kg, ko) <= tol and rel_err(vg, vo) <= tol
+        check_kv(shape.dtype, kg, ko, f"K of layer {l}")
+        check_kv(shape.dtype, vg, vo, f"V of layer {l}")
     # error paths: a stretch that leaves the model, and one whose layers' caches end at different positions
     h = g.ad_embed(toks[:2])
     with pytest.raises(ad.AdError) as ei:
@@ -167,7 +159,9 @@ D6144 = synth.WIDE_LAYER.with_(name="d6144-layer", d_model=6144, n_q_heads=40, n
                               "13b-layer-many-items", "8b-layer-ctx8300"])
 def test_layer_step_full_width_shapes(ad, shape, ctx, mode):
     """The single-layer microbenchmark workload: prefilled N(0,1) cache, N(0,1) hidden rows, m in {1,2,3,4,6,8}
-    at positions ctx .. ctx+m-1, cache length reset before each call."""
+    at positions ctx .. ctx+m-1, cache length reset before each call, hidden rows drawn afresh (their own seed) for
+    every call.  The 8B shape, the one the benchmark times, gets the first 10 calls of every m; the other shapes 8
+    calls in all."""
     import torch
     w = synth.make_weights(shape, seed=0)
     o = orc.Oracle(shape, w, max_pos=ctx + 8)
@@ -175,23 +169,72 @@ def test_layer_step_full_width_shapes(ad, shape, ctx, mode):
     k, v = synth.make_kv_prefill(shape, 0, 0, ctx)
     o.kv_write(1, 0, k.reshape(ctx, -1), v.reshape(ctx, -1))
     g.kv_fill(1, k, v)
-    for call, m in enumerate([1, 2, 3, 4, 6, 8, 8, 1]):
+    if shape is synth.LLAMA8B_LAYER and ctx == 4096:
+        calls = [(m, c) for m in synth.MICRO_M for c in range(10)]
+    else:
+        calls = [(m, c) for c, m in enumerate([1, 2, 3, 4, 6, 8, 8, 1])]
+    worst = worst_branch = 0.0
+    for m, call in calls:
         print(f"case {shape.name} layer mode {mode} m={m} call={call}", flush=True)
         o.kv_set_len(1, ctx)
         g.kv_set_len(1, ctx)
-        h = synth.make_hidden(shape, seed=100 + call, m=m)
+        h = synth.make_hidden(shape, seed=synth.micro_call_seed(m, call), m=m)
         pos = np.arange(ctx, ctx + m)
         ho = o.layer_step(1, h, pos)
         hg = torch.from_numpy(h).to("cuda:0")
         g.ad_layer_step(1, hg, pos)
-        e = rel_err(hg.cpu().numpy(), ho)
-        assert e <= TOL[shape.dtype], f"m={m}: rel err {e}"
+        worst = max(worst, check_rows(shape.dtype, hg.cpu().numpy(), ho, f"m={m} call={call}"))
         # the branch outputs themselves (y - x), which the residual otherwise dwarfs
         e2 = rel_err(hg.cpu().numpy() - h, ho - h)
-        assert e2 <= TOL[shape.dtype], f"m={m}: branch rel err {e2}"
+        assert e2 <= TOL[shape.dtype] and e2 <= 4 * REG[shape.dtype], f"m={m}: branch rel err {e2}"
+        worst_branch = max(worst_branch, e2)
         ko, vo = o.kv_read(1, ctx, m)
         kg, vg = gpu_kv(g, 1, ctx + m)
-        assert rel_err(kg[ctx:], ko) <= TOL[shape.dtype] and rel_err(vg[ctx:], vo) <= TOL[shape.dtype]
+        check_kv(shape.dtype, kg[ctx:], ko, f"appended K, m={m}")
+        check_kv(shape.dtype, vg[ctx:], vo, f"appended V, m={m}")
+    print(f"    {shape.name} mode {mode}: {len(calls)} calls, largest rel err {worst:.3e}, of the branch output {worst_branch:.3e}", flush=True)
+    g.close()
+
+
+@pytest.mark.parametrize("shape,ctx", [(synth.LLAMA8B_LAYER, 4096), (synth.TINY_BF16.with_(name="tiny-bf16-6-layers", n_layers=6, exit_layers=(2, 4)), 0)],
+                         ids=["8b-layer", "tiny-bf16-6-layers"])
+def test_bf16_tensors_meet_the_stated_tolerance_against_an_unrounded_cache(ad, shape, ctx):
+    """The oracle rounds stored K/V to the cache's 16-bit type because that rounding decides tokens (a quantisation
+    step both sides must take alike).  The stated tensor tolerance does not depend on it: against an oracle that
+    keeps its cache unrounded, hidden rows and cache entries of the bf16 GPU path stay within 2e-2."""
+    import torch
+    w = synth.make_weights(shape, seed=0, norm_jitter=0.1)
+    T = 40
+    o = orc.Oracle(shape, w, max_pos=ctx + 64, kv_dtype=synth.F32)
+    g = ad.Model(shape, w, max_pos=ctx + 64)
+    if ctx:
+        k, v = synth.make_kv_prefill(shape, 0, 0, ctx)
+        o.kv_write(1, 0, k.reshape(ctx, -1), v.reshape(ctx, -1))
+        g.kv_fill(1, k, v)
+        o.kv_set_len(1, ctx)
+        g.kv_set_len(1, ctx)
+    worst = 0.0
+    start = ctx
+    for call, m in enumerate([1, 3, 8, 2, 5, 7, 4, 6, 4]):
+        h = synth.make_hidden(shape, seed=50 + call, m=m)
+        pos = np.arange(start, start + m)
+        ho = h.astype(np.float64)
+        hg = torch.from_numpy(h).to("cuda:0")
+        for l in range(1, shape.n_layers + 1):
+            ho = o.layer_step(l, ho, pos)
+            g.ad_layer_step(l, hg, pos)
+            e = rel_err(hg.cpu().numpy(), ho)
+            worst = max(worst, e)
+            assert e <= TOL[shape.dtype], f"call {call} layer {l}: rel err {e}"
+        start += m
+    assert start == ctx + T
+    for l in range(1, shape.n_layers + 1):
+        ko, vo = o.kv_read(l, ctx, T)
+        kg, vg = gpu_kv(g, l, ctx + T)
+        ek, ev = rel_err(kg[ctx:], ko), rel_err(vg[ctx:], vo)
+        worst = max(worst, ek, ev)
+        assert ek <= TOL[shape.dtype] and ev <= TOL[shape.dtype], (l, ek, ev)
+    print(f"    {shape.name}: largest rel err against the unrounded-cache oracle {worst:.3e}", flush=True)
     g.close()
 
 
@@ -244,9 +287,17 @@ def test_argmax_tie_takes_lowest_id(ad):
     g.close()
 
 
+# tolerated near-tie differences (each followed by a re-synchronisation on the oracle's output) per free run
+MAX_RESYNCS = {synth.F32: 0, synth.BF16: 4, synth.F16: 2}
+
+
 def compare_runs(shape, g, o, prompt, max_new, gamma, cap, **kw):
+    """Whole-run comparison of decisions with the oracle; the run must be covered to its last token and all but
+    the tolerated near ties (bounded in number, each checked against the oracle's margin) must agree."""
     from compare_runs import compare_runs as cmp
-    return cmp(g, o, prompt, max_new, gamma, cap, TOL[shape.dtype], **kw)[0]
+    r = cmp(g, o, prompt, max_new, gamma, cap, TOL[shape.dtype], max_resyncs=MAX_RESYNCS[shape.dtype], **kw)
+    assert r.tokens == max_new and r.agreed >= r.total - MAX_RESYNCS[shape.dtype] and r.agreed >= 0.97 * r.total, str(r)
+    return r
 
 
 @pytest.mark.parametrize("shape,mode", with_modes([synth.TINY, UNTIED, synth.TINY_GQA, UNTIED.with_(name="tiny-untied-bf16", dtype=synth.BF16),
@@ -259,10 +310,9 @@ def test_generate_matches_oracle_decisions(ad, shape, mode):
     p = synth.make_prompt(shape, 0)
     greedy, margins = o.generate_greedy(p, 64)
     # the workload as stated (gamma 0.9), then thresholds at which exits actually happen, then forced schedules
-    total = 0
     for gamma, cap in [(0.9, 7), (1.0, 5), (0.0, 5), (0.0045, 7), (0.05, 3)]:
         print(f"case {shape.name} layer mode {mode} gamma={gamma} cap={cap}", flush=True)
-        total += compare_runs(shape, g, o, p, 64, gamma, cap)
+        compare_runs(shape, g, o, p, 64, gamma, cap)
     for seed in (1, 2):
         k = len(shape.exit_layers)
         forced = synth.make_forced_schedule(shape, seed, max_pos, probs=[0.6 / k] * k)
@@ -303,7 +353,8 @@ def test_generate_full_width_reduced_depth(ad, shape, mode):
     for l in (1, shape.n_layers):
         ko, vo = o.kv_read(l, 0, n)
         kg, vg = gpu_kv(g, l, n)
-        assert rel_err(kg, ko) <= TOL[shape.dtype] and rel_err(vg, vo) <= TOL[shape.dtype]
+        check_kv(shape.dtype, kg, ko, f"K of layer {l}")
+        check_kv(shape.dtype, vg, vo, f"V of layer {l}")
     g.close()
 
 
@@ -402,8 +453,9 @@ def test_ablation_switches_match_oracle(ad, shape):
     assert sg["rejections"] == 0 and sg["rolled_back"] == 0
     u = synth.make_uniforms(shape, 4, max_pos)
     print(f"case {shape.name} sampled no_verify / head_mask", flush=True)
-    compare_sampled_runs(g, o, p, 48, 0.3, 7, TOL[shape.dtype], 0.05, u, no_verify=True)
-    compare_sampled_runs(g, o, p, 48, 0.3, 7, TOL[shape.dtype], 0.05, u, head_mask=0b010)
+    for kw in (dict(no_verify=True), dict(head_mask=0b010)):
+        r = compare_sampled_runs(g, o, p, 48, 0.3, 7, shape.dtype, 0.05, u, max_resyncs=4, **kw)
+        assert r.tokens == 48 and r.agreed >= 0.97 * r.total, str(r)
     g.close()
 
 

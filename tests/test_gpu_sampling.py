@@ -4,7 +4,8 @@ A sampled decision is a floating-point comparison that decides an integer: the d
 distribution, or against the ratio of Eq. 2.  The oracle reports how far each draw was from the nearest value
 that would change the decision (in probability units); decisions must agree except within a margin that covers
 the fp32 summation of the kernel (kernel-level tests, both sides start from the same fp32 logits: 1e-6) or the
-logit tolerance of the model (free runs: a logit error e moves a cumulative boundary by at most e / temperature).
+logit error of the model's storage type (free runs: compare_runs.sampled_tie; after a tolerated difference the
+comparison re-synchronises on the oracle's output and goes on, so whole runs are compared for every type).
 """
 import numpy as np
 import pytest
@@ -15,7 +16,8 @@ from paper_2506_03700_amd import synth
 pytestmark = pytest.mark.gpu
 
 KERNEL_MARGIN = 1e-6
-LOGIT_TOL = {synth.F32: 1e-4, synth.BF16: 2e-2, synth.F16: 2.5e-3}
+# tolerated differences (each a draw the oracle reports within the logit error of a boundary) per free run of 48 tokens
+MAX_RESYNCS = {synth.F32: 1, synth.BF16: 6, synth.F16: 3}
 
 
 @pytest.fixture(scope="module")
@@ -158,32 +160,37 @@ UNTIED = synth.TINY.with_(name="tiny-untied", tied_head=False, vocab=512, exit_l
                                    UNTIED.with_(name="tiny-untied-bf16", dtype=synth.BF16),
                                    UNTIED.with_(name="tiny-untied-f16", dtype=synth.F16)], ids=lambda s: s.name)
 def test_generate_sampled_matches_oracle_decisions(ad, shape):
-    """Free runs of sampled Algorithm 1 on the GPU and in the oracle with the same draws: every decision up to the
-    first one whose draw lies within the logit tolerance of a boundary must agree; exit heads with a random transform
-    make the exit and final distributions differ, so that Eq. 2 rejects often."""
+    """Free runs of sampled Algorithm 1 on the GPU and in the oracle with the same draws: every decision of the whole
+    run must agree, except draws that lie within the storage type's logit error of a boundary (the comparison then
+    re-synchronises and continues; their number is bounded); exit heads with a random transform make the exit and
+    final distributions differ, so that Eq. 2 rejects often."""
     from compare_runs import compare_sampled_runs
     w = synth.make_weights(shape, seed=0, with_T=True, T_std=0.03)
     max_pos = 128
     o = orc.Oracle(shape, w, max_pos=max_pos)
     g = ad.Model(shape, w, max_pos=max_pos)
     p = synth.make_prompt(shape, 0)
-    agreed = rejections = early = 0
+    agreed = total = tokens = rejections = early = 0
+    lim = MAX_RESYNCS[shape.dtype]
     for seed, T, gamma, cap in [(0, 0.05, 0.3, 7), (1, 0.05, 0.0, 5), (2, 0.02, 0.5, 7), (3, 0.1, 0.0, 3), (4, 1.0, 0.0, 7)]:
         u = synth.make_uniforms(shape, seed, max_pos)
         print(f"case {shape.name} seed={seed} T={T} gamma={gamma} cap={cap}", flush=True)
-        n, total, so = compare_sampled_runs(g, o, p, 48, gamma, cap, LOGIT_TOL[shape.dtype], T, u)
-        agreed += n
-        rejections += so["rejections"]
-        early += so["early_preds"]
+        r = compare_sampled_runs(g, o, p, 48, gamma, cap, shape.dtype, T, u, max_resyncs=lim)
+        agreed += r.agreed
+        total += r.total
+        tokens += r.tokens
+        rejections += r.stats["rejections"]
+        early += r.stats["early_preds"]
     assert early > 20 and rejections > 5
-    if shape.dtype == synth.F32:
-        assert agreed > 300          # fp32 logits leave few draws near a boundary: the runs agree almost to the end
+    # whole runs were compared (5 x 48 tokens), and all but the tolerated near-boundary draws agreed
+    assert tokens == 5 * 48 and agreed >= total - 5 * lim and agreed >= 0.97 * total, (agreed, total, tokens)
     # forced schedules and scripted drafts with sampling
     forced = synth.make_forced_schedule(shape, 1, max_pos, probs=[0.6 / len(shape.exit_layers)] * len(shape.exit_layers))
     script = np.full(max_pos, -1, dtype=np.int32)
     script[[40, 47, 61]] = [1, 2, 3]
     u = synth.make_uniforms(shape, 9, max_pos)
-    compare_sampled_runs(g, o, p, 48, 0.9, 5, LOGIT_TOL[shape.dtype], 0.05, u, forced_exit=forced, scripted_draft=script)
+    r = compare_sampled_runs(g, o, p, 48, 0.9, 5, shape.dtype, 0.05, u, max_resyncs=lim, forced_exit=forced, scripted_draft=script)
+    assert r.tokens == 48 and r.agreed >= 0.97 * r.total
     g.close()
 
 

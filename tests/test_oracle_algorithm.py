@@ -252,3 +252,37 @@ def test_no_verify_keeps_drafts_unchecked():
     a, st, ev = o.generate_ada(p, n, 0.9, 5, forced_exit=forced, scripted_draft=script)
     np.testing.assert_array_equal(a, g[:n])
     assert st["rejections"] == 1
+
+
+def test_restart_from_kept_cache_rows_equals_a_run_from_scratch():
+    # A cache row depends on the tokens up to its position only, so a run whose prompt extends an earlier run's
+    # prompt by that run's own verified tokens may take the shared rows over (keep_cache): every event, token and
+    # cache entry must equal those of the same call made on an empty cache.
+    shape = synth.TINY.with_(name="tiny-untied", tied_head=False, vocab=512, exit_layers=(1, 2, 3))
+    w = synth.make_weights(shape, seed=0)
+    p = synth.make_prompt(shape, 0)[:12]
+    forced = synth.make_forced_schedule(shape, 1, 96, probs=[0.2, 0.2, 0.2])
+    a, b = orc.Oracle(shape, w, max_pos=96), orc.Oracle(shape, w, max_pos=96)
+    t0, _, _ = a.generate_ada(p, 40, 0.9, 5, forced_exit=forced)
+    for j in (1, 7, 23):
+        p2 = np.concatenate([p, t0[:j]])
+        keep = len(p2) - 1                       # rows of every prompt position but the last are in a's cache
+        ta, sa, ea = a.generate_ada(p2, 40 - j, 0.9, 5, forced_exit=forced, keep_cache=keep)
+        tb, sb, eb = b.generate_ada(p2, 40 - j, 0.9, 5, forced_exit=forced)
+        np.testing.assert_array_equal(ta, tb)
+        np.testing.assert_array_equal(ta, t0[j:])
+        assert sa == sb and ea.tobytes() == eb.tobytes()
+        n = min(a.kv_lens())
+        assert a.kv_lens() == b.kv_lens()
+        for l in (1, shape.n_layers):
+            ka, va = a.kv_read(l, 0, n)
+            kb, vb = b.kv_read(l, 0, n)
+            np.testing.assert_array_equal(ka, kb)
+            np.testing.assert_array_equal(va, vb)
+        # what must be refused: more rows than the prompt's own, or more than the cache holds
+        a.generate_ada(p2, 40 - j, 0.9, 5, forced_exit=forced)
+    with pytest.raises(RuntimeError):
+        a.generate_ada(p, 8, 0.9, 5, keep_cache=len(p))
+    a.kv_truncate(3)
+    with pytest.raises(RuntimeError):
+        a.generate_ada(p, 8, 0.9, 5, keep_cache=5)

@@ -182,3 +182,32 @@ def test_verify_first_mismatch_rule():
     assert o.verify(hidden, [5, 0, 0, 0])[:2] == (1, 9)
     # one row, no drafts: plain next-token prediction
     assert o.verify(hidden[:1], [])[:2] == (0, 5)
+
+
+@pytest.mark.parametrize("shape", [synth.TINY, synth.TINY_GQA, synth.TINY_BF16,
+                                   synth.TINY.with_(name="tiny-untied", tied_head=False, vocab=512, exit_layers=(1, 2, 3))],
+                         ids=lambda s: s.name)
+def test_greedy_generation_is_the_argmax_chain_of_the_whole_sequence_forward(shape):
+    # Plain greedy decoding, pinned directly: feed prompt + output to the whole-sequence library forward (teacher
+    # forcing); the final-layer argmax at every position from the last prompt token on must be the token the oracle
+    # emitted next, and the margin it reports must be that position's top-2 logit gap.  Positions whose gap is within
+    # the two implementations' rounding of zero could legitimately differ and are not expected with these seeds.
+    w = synth.make_weights(shape, seed=0)
+    prompt = synth.make_prompt(shape, 0)[:20]
+    n_new = 24
+    o = orc.Oracle(shape, w, max_pos=64)
+    out, margins = o.generate_greedy(prompt, n_new)
+    assert len(out) == n_new
+    seq = np.concatenate([prompt, out])
+    logits = library_forward(shape, w, seq[:-1])[3]
+    M = len(prompt)
+    for j in range(n_new):
+        z = logits[M - 1 + j]
+        top2 = torch.topk(z, 2)
+        assert margins[j] > 1e-9, "an exact tie: pick another seed for this pin"
+        assert int(top2.indices[0]) == int(out[j]), f"token {j}"
+        assert abs(float(top2.values[0] - top2.values[1]) - margins[j]) < 1e-9
+    # the end-of-sequence rule: generation stops after emitting eos_id
+    out2, _ = o.generate_greedy(prompt, n_new, eos_id=int(out[5]))
+    first = int(np.nonzero(out == out[5])[0][0])
+    np.testing.assert_array_equal(out2, out[:first + 1])
