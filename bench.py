@@ -8,10 +8,15 @@ value = generated tokens / wall time of the timed steps (prefill of the prompt i
 
 The same JSON line also carries:
   roofline      the weight-streaming kernel sampled live with stream events during the timed steps
-  layer_step    the single-layer microbenchmark: ragged calls with m rows at context 4096, rotating over the
-                model's 32 distinct layers so that no cache can hold the weights
+  layer_step    the single-layer microbenchmark: 1000 ragged calls per row count m at context 4096, every call on
+                freshly drawn N(0,1) rows (pre-generated on the device), rotating over the model's 32 distinct
+                layers so that no cache can hold the weights
   forced        the same generation with exits forced from a seeded schedule (0.2/0.2/0.2 at layers 8/16/24)
-  cpu_baseline  the CPU oracle, as it stands, timed on a bounded sample on this machine's host cores
+  long          the long-generation workload: prompt 1024, 8192 generated tokens, the same kind of forced schedule,
+                verification on, context growing to 9216
+  cpu_baseline  the CPU oracle, as it stands, timed on bounded samples on this machine's host cores: Algorithm 1 on the
+                benchmark's model, the tiny fp32 workload in full, and ten layer steps per m of the microbenchmark,
+                at all cores and on one thread
   gamma_sweep   (only with --gamma-sweep) the threshold sweep of Fig. 5 and the schedule switches of Table 3, in shape
                 only: early-prediction rate, rejection rate and tokens/s per threshold, thresholds placed at quantiles
                 of the synthetic model's own head confidences (random-init heads are never 0.9-confident)
@@ -44,10 +49,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="8b", choices=["8b", "13b", "8b-mini", "tiny"])
+    ap.add_argument("--workload", default="8b", choices=["8b", "13b", "8b-long", "8b-mini", "tiny"],
+                    help="8b-long: the timed steps are the long-generation workload itself (forced schedule)")
     ap.add_argument("--gen-len", type=int, default=None)
     ap.add_argument("--prompt-len", type=int, default=None)
-    ap.add_argument("--micro-calls", type=int, default=320, help="layer-step calls per m in the microbenchmark")
+    ap.add_argument("--micro-calls", type=int, default=None, help="layer-step calls per m in the microbenchmark (default 1000)")
+    ap.add_argument("--skip-long", action="store_true")
+    ap.add_argument("--phase-trace", action="store_true",
+                    help="fused layer mode: also report where a layer step's time goes, phase by phase (the kernel's own timestamps)")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-micro", action="store_true")
     ap.add_argument("--skip-forced", action="store_true")
@@ -69,7 +78,12 @@ def main():
     prompt_len = args.prompt_len or shape.prompt_len
     cap = 7
     ctx_micro = 4096
-    max_pos = max(prompt_len + gen_len + 8, ctx_micro + 16)
+    micro_calls = args.micro_calls or synth.MICRO_CALLS
+    main_is_long = args.workload == "8b-long"
+    # the long-generation leg rides along with the 8B workload (same model); it needs the deeper cache
+    long_shape = synth.LLAMA8B_LONG
+    with_long = (args.workload == "8b" and not args.skip_long and args.gen_len is None and args.prompt_len is None)
+    max_pos = max(prompt_len + gen_len + 8, ctx_micro + 16, (long_shape.prompt_len + long_shape.gen_len + 8) if with_long else 0)
 
     t0 = time.time()
     w = synth.make_weights(shape, seed=0)
@@ -81,7 +95,11 @@ def main():
     fused = args.layer_mode == "fused" and shape.dtype == synth.BF16
     g.ad_set_layer_mode(binding.AD_LAYER_FUSED if fused else binding.AD_LAYER_KERNELS)
 
+    main_sched = synth.make_forced_schedule(shape, 0, max_pos) if main_is_long else None
+
     def run(**kw):
+        if main_is_long:
+            kw = dict(kw, forced_exit=main_sched)
         return g.ad_generate(prompt, gen_len, shape.gamma, cap, want_events=False, **kw)
 
     for _ in range(args.warmup):
@@ -116,6 +134,9 @@ def main():
              ("ad::k_gemm (weight-streaming skinny GEMM: every projection of the layer step and the vocabulary pass)")
     roofline = {"bound": "hbm", "kernel": kernel,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "time_base": "a pair of events on the launch stream around each sampled launch (every 7th), i.e. from the end of the "
+                             "previous kernel to the end of the sampled one: the dispatch gap ahead of the kernel is inside the "
+                             "figure; rocprofv3's own duration of the same kernel (profiles/) is shorter by that gap",
                 "traffic": None if traffic_ratio is None else int(avg_bytes * traffic_ratio),
                 "traffic_source": None if traffic_ratio is None else f"{traffic_src}: measured HBM bytes / algorithmic bytes = {traffic_ratio}",
                 "avg_launch_us": round(avg_ms * 1e3, 2), "avg_bytes_per_launch": int(avg_bytes),
@@ -124,10 +145,13 @@ def main():
     e2e = {"algorithmic_GB_per_step": round(decode_bytes / 1e9, 3),
            "achieved_GBps_whole_step": round(args.steps * decode_bytes / dt / 1e9, 1),
            "layer_steps_per_s": round(args.steps * stats["layer_steps"] / dt, 1),
-           "early_preds": stats["early_preds"], "rejections": stats["rejections"], "head_evals": stats["head_evals"]}
+           "early_preds": stats["early_preds"], "rejections": stats["rejections"], "head_evals": stats["head_evals"],
+           "note": "random-init exit heads are never 0.9-confident: at the workload's threshold no exit is taken, so `value` is plain "
+                   "decoding plus the head evaluations that never fire; the adaptive path (ragged steps, deferred layers, rejections) "
+                   "is timed in `forced` and `long`" if stats["early_preds"] == 0 else ""}
 
     forced = None
-    if not args.skip_forced and shape.exit_layers:
+    if not args.skip_forced and shape.exit_layers and not main_is_long:
         sched = synth.make_forced_schedule(shape, 0, max_pos)
         g.ad_generate(prompt, min(gen_len, 64), shape.gamma, cap, forced_exit=sched, want_events=False)
         torch.cuda.synchronize()
@@ -140,6 +164,27 @@ def main():
                   "early_preds": fst["early_preds"], "rejections": fst["rejections"],
                   "achieved_GBps": round(fst["bytes_algorithmic"] / fdt / 1e9, 1)}
         log(f"[bench] forced schedule: {forced}")
+
+    long = None
+    if with_long:
+        lp = synth.make_prompt(long_shape, 0, n=long_shape.prompt_len)
+        lsched = synth.make_forced_schedule(long_shape, 0, max_pos)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        _, lst, _ = g.ad_generate(lp, long_shape.gen_len, long_shape.gamma, cap, forced_exit=lsched, want_events=False)
+        torch.cuda.synchronize()
+        ldt = time.perf_counter() - t0
+        long = {"workload": f"prompt {long_shape.prompt_len}, {long_shape.gen_len} generated tokens, context to "
+                            f"{long_shape.prompt_len + long_shape.gen_len}; each token exits at an exit layer with probability 0.2 each, "
+                            "else full depth (seeded), verification on; one run, prefill included",
+                "tokens_per_s": round(long_shape.gen_len / ldt, 1), "seconds": round(ldt, 2),
+                "layer_steps_per_s": round(lst["layer_steps"] / ldt, 1), "layer_steps": lst["layer_steps"],
+                "steps_by_m": lst["steps_by_m"], "early_preds": lst["early_preds"], "rejections": lst["rejections"],
+                "head_evals": lst["head_evals"], "verifies": lst["verifies"],
+                "algorithmic_GB": round(lst["bytes_algorithmic"] / 1e9, 1),
+                "achieved_GBps": round(lst["bytes_algorithmic"] / ldt / 1e9, 1),
+                "frac_of_peak": round(lst["bytes_algorithmic"] / ldt / 1e9 / HBM_PEAK_GBS, 4)}
+        log(f"[bench] long generation: {long}")
 
     sweep = None
     if args.gamma_sweep and shape.exit_layers:
@@ -187,31 +232,44 @@ def main():
         K[:, :, :ctx_micro, :] = torch.randn(K[:, :, :ctx_micro, :].shape, generator=gen, device="cuda").to(K.dtype)
         V[:, :, :, :ctx_micro] = torch.randn(V[:, :, :, :ctx_micro].shape, generator=gen, device="cuda").to(V.dtype)
         L = shape.n_layers
-        for m in (1, 2, 3, 4, 6, 8):
-            h = torch.from_numpy(synth.make_hidden(shape, 1000 + m, m)).to("cuda")
-            pos = np.arange(ctx_micro, ctx_micro + m)
-            calls = args.micro_calls
+        dgen = torch.Generator(device="cuda")
 
-            def one(i):
+        def rows_for(m, n, first_from_synth=0):
+            """[n, m, d] N(0,1) rows, one slice per call: the first calls' rows are the ones the parity test checks
+            against the oracle (synth.micro_call_seed), the rest are drawn on the device from the next seed."""
+            dgen.manual_seed(synth.micro_call_seed(m, first_from_synth))
+            buf = torch.randn((n, m, shape.d_model), generator=dgen, device="cuda", dtype=torch.float32)
+            for c in range(min(first_from_synth, n)):
+                buf[c] = torch.from_numpy(synth.make_hidden(shape, synth.micro_call_seed(m, c), m)).to("cuda")
+            return buf
+
+        def timed_batches(fn, n_calls, n_batches=10):
+            """Mean over all calls and median over the batch means (events on the launch stream)."""
+            per = max(1, n_calls // n_batches)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_batches + 1)]
+            ev[0].record()
+            for b in range(n_batches):
+                for i in range(per):
+                    fn(b * per + i)
+                ev[b + 1].record()
+            torch.cuda.synchronize()
+            t = [ev[b].elapsed_time(ev[b + 1]) * 1e3 / per for b in range(n_batches)]
+            return float(np.mean(t)), float(np.median(t))
+
+        for m in synth.MICRO_M:
+            pos = np.arange(ctx_micro, ctx_micro + m)
+            calls = micro_calls
+            n_warm = 64
+            H = rows_for(m, calls, first_from_synth=10)
+            Hw = torch.randn((n_warm, m, shape.d_model), generator=dgen, device="cuda")     # warm-up rows
+
+            def one(i, buf=H):
                 layer = i % L + 1
                 g.kv_set_len(layer, ctx_micro)
-                g.ad_layer_step(layer, h, pos)
+                g.ad_layer_step(layer, buf[i], pos)
 
-            def timed_batches(fn, n_calls, n_batches=10):
-                """Mean over all calls and median over the batch means (events on the launch stream)."""
-                per = max(1, n_calls // n_batches)
-                ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_batches + 1)]
-                ev[0].record()
-                for b in range(n_batches):
-                    for i in range(per):
-                        fn(b * per + i)
-                    ev[b + 1].record()
-                torch.cuda.synchronize()
-                t = [ev[b].elapsed_time(ev[b + 1]) * 1e3 / per for b in range(n_batches)]
-                return float(np.mean(t)), float(np.median(t))
-
-            for i in range(min(64, calls)):
-                one(i)
+            for i in range(n_warm):
+                one(i, Hw)
             torch.cuda.synchronize()
             us, us_med = timed_batches(one, calls)
             gbs = layer_step_bytes(shape, ctx_micro, m) / (us * 1e-6) / 1e9
@@ -219,63 +277,137 @@ def main():
                              "frac": round(gbs / HBM_PEAK_GBS, 4)}
             if m == 1:
                 # the same call on ONE layer's weights over and over: the 256 MB memory-side cache may serve part of them
+                H1 = torch.randn((calls, m, shape.d_model), generator=dgen, device="cuda")
+
                 def same(i):
                     g.kv_set_len(1, ctx_micro)
-                    g.ad_layer_step(1, h, pos)
+                    g.ad_layer_step(1, H1[i], pos)
                 for i in range(16):
-                    same(i)
+                    one(i, Hw)
                 torch.cuda.synchronize()
                 us1, _ = timed_batches(same, calls)
                 micro[str(m)]["us_single_weight_copy_cache_assisted"] = round(us1, 2)
-            if m in (1, 8) and L % 8 == 0:
+            if L % 8 == 0:
                 # the same layers as stretches of 8 per call (what ad_generate issues between two exit heads)
-                def stretch(i):
+                n8 = max(10, calls // 8)
+                H8 = torch.randn((n8, m, shape.d_model), generator=dgen, device="cuda")
+
+                def stretch(i, buf=H8):
                     first = (i * 8) % L + 1
                     for layer in range(first, first + 8):
                         g.kv_set_len(layer, ctx_micro)
-                    g.ad_layer_steps(first, 8, h, pos)
+                    g.ad_layer_steps(first, 8, buf[i], pos)
                 for i in range(8):
-                    stretch(i)
+                    stretch(i, Hw)
                 torch.cuda.synchronize()
-                us8, _ = timed_batches(stretch, max(10, calls // 8))
+                us8, _ = timed_batches(stretch, n8)
+                gbs8 = layer_step_bytes(shape, ctx_micro, m) / (us8 / 8 * 1e-6) / 1e9
                 micro[str(m)]["us_per_layer_in_stretches_of_8"] = round(us8 / 8, 2)
-            log(f"[bench] layer step m={m}: {us:.2f} us (median of batches {us_med:.2f}), {gbs:.1f} GB/s ({gbs / HBM_PEAK_GBS:.1%} of peak)")
-        micro = {"ctx": ctx_micro, "calls_per_m": args.micro_calls, "distinct_weight_copies": L,
+                micro[str(m)]["frac_in_stretches_of_8"] = round(gbs8 / HBM_PEAK_GBS, 4)
+            if fused and args.phase_trace and L % 8 == 0:
+                # the fused kernel's own clock: per workgroup, ticks before and after each grid barrier of the last layer
+                # of a launch (a steady-state layer when the launch covers 8); a phase ends when its last workgroup is done
+                tr = g.ad_layer_trace(True)
+                acc = []
+                for i in range(16):
+                    stretch(i % n8)
+                    torch.cuda.synchronize()
+                    if i >= 4:
+                        acc.append(tr.cpu().numpy().copy())
+                g.ad_layer_trace(False)
+                a = np.stack(acc).astype(np.float64) * 0.01                       # us, [launch, workgroup, stamp]
+                a -= a[:, :, 0].max(axis=1)[:, None, None]                        # 0 = the last workgroup entering the layer
+                names = ["QKV", "barrier", "attention", "barrier", "fold", "barrier", "Wo", "barrier", "gate/up", "barrier", "down"]
+                ends = a.max(axis=1).mean(axis=0)
+                micro[str(m)]["fused_phase_end_us"] = {f"{j:02d} {nm}": round(float(ends[j + 1]), 2) for j, nm in enumerate(names)}
+                micro[str(m)]["fused_phase_mean_us_per_workgroup"] = {f"{j:02d} {nm}": round(float((a[:, :, j + 1] - a[:, :, j]).mean()), 2)
+                                                                      for j, nm in enumerate(names)}
+                log(f"[bench] fused layer step m={m}: phase ends (us after the layer's start) {micro[str(m)]['fused_phase_end_us']}")
+            log(f"[bench] layer step m={m}: {us:.2f} us (median of batches {us_med:.2f}), {gbs:.1f} GB/s ({gbs / HBM_PEAK_GBS:.1%} of peak)"
+                + (f"; {micro[str(m)]['us_per_layer_in_stretches_of_8']:.2f} us per layer in stretches of 8" if L % 8 == 0 else ""))
+            del H, Hw
+        micro = {"ctx": ctx_micro, "calls_per_m": micro_calls, "distinct_weight_copies": L,
+                 "rows": "N(0,1), drawn afresh for every call from a pre-generated device buffer (the first 10 calls of each m are the "
+                         "rows of the parity test)",
                  "algorithmic_bytes_m1": layer_step_bytes(shape, ctx_micro, 1), "by_m": micro}
+        roofline["layer_step_frac_by_m"] = {k: v["frac"] for k, v in micro["by_m"].items()}
 
     cpu = None
     if not args.skip_cpu:
         from oracle import oracle as orc
-        n_prompt, n_new = 17, 64          # about 10-15 s of oracle time on the 8B shape
+        cores = orc.num_threads()
+
+        def at_threads(n, fn):
+            orc.set_num_threads(n)
+            t0 = time.perf_counter()
+            r = fn()
+            dt_ = time.perf_counter() - t0
+            orc.set_num_threads(cores)
+            return dt_, r
+
+        # (a) Algorithm 1 on the benchmark's own model and weights: about 10 s of oracle time on the 8B shape
+        n_prompt, n_new = 17, 64
         o = orc.Oracle(shape, w, max_pos=n_prompt + n_new + 8)
-        t0 = time.perf_counter()
-        ot, ost, _ = o.generate_ada(prompt[:n_prompt], n_new, shape.gamma, cap)
-        cdt = time.perf_counter() - t0
-        cpu = {"value": round(n_new / cdt, 4), "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+        cdt, (ot, ost, _) = at_threads(cores, lambda: o.generate_ada(prompt[:n_prompt], n_new, shape.gamma, cap))
+        cpu = {"value": round(n_new / cdt, 4), "unit": "tokens/s", "cores": cores, "kind": "oracle",
                "sample": f"Algorithm 1 on the same model and weights, prompt {n_prompt} tokens, {n_new} generated tokens, "
                          f"gamma {shape.gamma}; {cdt:.1f}s wall, prefill included",
                "layer_steps_per_s": round((ost["layer_steps"] + (n_prompt - 1)) / cdt, 3)}
-        # the same oracle on one thread, on a shorter sample
         n_one = 2
-        orc.set_num_threads(1)
-        t0 = time.perf_counter()
-        o.generate_ada(prompt[:2], n_one, shape.gamma, cap)
-        cdt1 = time.perf_counter() - t0
-        orc.set_num_threads(cpu["cores"])
+        cdt1, _ = at_threads(1, lambda: o.generate_ada(prompt[:2], n_one, shape.gamma, cap))
         cpu["one_thread"] = {"value": round(n_one / cdt1, 4), "unit": "tokens/s",
                              "sample": f"prompt of 2 tokens, {n_one} generated tokens; {cdt1:.1f}s wall, prefill included"}
-        log(f"[bench] cpu oracle: {cpu}")
         o.close()
+        # (b) the tiny fp32 workload in full (prompt 32, 64 generated tokens, threshold 0.9)
+        ts = synth.TINY
+        tw = synth.make_weights(ts, seed=0)
+        tp = synth.make_prompt(ts, 0)
+        ot_ = orc.Oracle(ts, tw, max_pos=ts.prompt_len + ts.gen_len + 8)
+        tall, (_, tst, _) = at_threads(cores, lambda: ot_.generate_ada(tp, ts.gen_len, ts.gamma, cap))
+        tone, _ = at_threads(1, lambda: ot_.generate_ada(tp, ts.gen_len, ts.gamma, cap))
+        ot_.close()
+        cpu["tiny_workload"] = {"sample": f"tiny fp32 model, prompt {ts.prompt_len}, {ts.gen_len} generated tokens, in full",
+                                "tokens_per_s": round(ts.gen_len / tall, 1), "tokens_per_s_one_thread": round(ts.gen_len / tone, 1),
+                                "layer_steps_per_s": round(tst["layer_steps"] / tall, 1)}
+        # (c) the layer-step microbenchmark: ten calls per m on one layer of the benchmark's shape at context 4096
+        if shape.d_model == synth.LLAMA8B.d_model and shape.dtype == synth.BF16 and not args.skip_micro:
+            ls = synth.LLAMA8B_LAYER
+            lw = {k: v for k, v in w.items() if k.startswith("layers.0.") or k in ("final_norm",)}
+            lw["embed"] = w["embed"][:ls.vocab]
+            lw["lm_head"] = w["lm_head"][:ls.vocab]
+            ol = orc.Oracle(ls, lw, max_pos=ctx_micro + 8)
+            kk, vv = synth.make_kv_prefill(ls, 0, 0, ctx_micro)
+            ol.kv_write(1, 0, kk.reshape(ctx_micro, -1), vv.reshape(ctx_micro, -1))
+            by_m = {}
+
+            def ten(m):
+                for c in range(10):
+                    ol.kv_set_len(1, ctx_micro)
+                    ol.layer_step(1, synth.make_hidden(ls, synth.micro_call_seed(m, c), m), np.arange(ctx_micro, ctx_micro + m))
+
+            for m in synth.MICRO_M:
+                d_all, _ = at_threads(cores, lambda: ten(m))
+                by_m[str(m)] = {"ms_per_call": round(d_all * 100, 2),
+                                "GBps": round(layer_step_bytes(ls, ctx_micro, m) / (d_all / 10) / 1e9, 2)}
+            for m in (1, 8):
+                d_one, _ = at_threads(1, lambda: ten(m))
+                by_m[str(m)]["ms_per_call_one_thread"] = round(d_one * 100, 2)
+            ol.close()
+            cpu["layer_step"] = {"sample": "ten oracle layer steps per m on one layer of the 8B shape, cache of 4096 positions, the "
+                                           "rows of the microbenchmark's first ten calls; one thread for m = 1 and 8 only",
+                                 "by_m": by_m}
+        log(f"[bench] cpu oracle: {cpu}")
 
     out = {"metric": "decoded tokens/sec @batch1 (8B-shape bf16); layer-step HBM GB/s vs peak",
            "value": round(tokens_per_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(dt / args.steps * 1e3, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "bf16" if shape.dtype == synth.BF16 else "f32", "data": "synthetic",
+           "dtype": {synth.F32: "f32", synth.BF16: "bf16", synth.F16: "f16"}[shape.dtype], "data": "synthetic",
            "config": {"workload": f"{shape.name}: {shape.n_layers} layers d={shape.d_model} heads {shape.n_q_heads}/{shape.n_kv_heads}x{shape.head_dim} "
                                   f"ffn {shape.d_ffn} vocab {shape.vocab}, exit heads at {list(shape.exit_layers)}, gamma {shape.gamma}, "
-                                  f"cap {cap}, prompt {prompt_len}, generate {gen_len}, batch 1, random-init N(0,0.02)",
+                                  f"cap {cap}, prompt {prompt_len}, generate {gen_len}, batch 1, random-init N(0,0.02)"
+                                  + (", exits forced from a seeded 0.2/0.2/0.2 schedule, verification on" if main_is_long else ""),
                       "global_batch": 1, "seq_len": prompt_len + gen_len},
-           "roofline": roofline, "end_to_end": e2e, "forced": forced, "layer_step": micro, "cpu_baseline": cpu}
+           "roofline": roofline, "end_to_end": e2e, "forced": forced, "long": long, "layer_step": micro, "cpu_baseline": cpu}
     if sweep is not None:
         out["gamma_sweep"] = sweep
     print(json.dumps(out), flush=True)

@@ -1,11 +1,11 @@
 /*
  * adadecode.h -- C ABI of the MI355X (gfx950) implementation of AdaDecode's hot path
- * (arxiv 2506.03700, "Accelerating LLM Decoding with Adaptive Layer Parallelism").
+ * (arxiv 2506.03700, the AdaDecode paper).
  *
  * The library runs, on one GPU and at batch 1, the three operations Algorithm 1 is made of, plus the
  * loop itself:
- *   ad_layer_step   "update KV cache at layer l by processing all tokens in P[l] in parallel"
- *                   (ad_layer_steps: a range of consecutive layers over the same rows)
+ *   ad_layer_step   Algorithm 1's layer-update step: one decoder layer over all rows pending at that layer, whose
+ *                   K/V entries join the layer's cache (ad_layer_steps: a range of consecutive layers over the same rows)
  *   ad_exit_head    Eq. 1 at temperature 0: greedy token of an intermediate-layer head and its probability
  *   ad_verify       Eq. 2 at temperature 0: accept the early predictions that equal the final layer's
  *                   greedy tokens, replace the first that does not
@@ -69,7 +69,7 @@ typedef struct {
 
 /* embed [vocab, d], final_norm [d], lm_head [vocab, d] (may alias embed).  exit_T is NULL, or an array
  * of n_exit dev pointers, each NULL (identity) or a [d, d] transform T: the exit head is then
- * E = E* T as in Sec. 2.1 ("lightweight LM head"), applied after the shared final norm. */
+ * E = E* T, the lightweight head of Sec. 2.1, applied after the shared final norm. */
 typedef struct {
     const void *embed, *final_norm, *lm_head;   /* dev */
     const void *const *exit_T;                  /* host array of dev pointers, or NULL */
@@ -105,8 +105,7 @@ ad_status ad_kv_truncate(ad_kv *, int32_t new_len);
 /* hidden[r] = embedding row of tokens[r].  tokens: host [m]; hidden: dev [m, d] fp32. */
 ad_status ad_embed(const ad_model *, const int32_t *tokens, int32_t m, void *hidden, void *stream);
 
-/* One decoder layer over the m pending rows of that layer (Algorithm 1, the "update KV cache at layer l"
- * step; Sec. 2.2).  hidden: dev [m, d] fp32, updated in place.  pos: host [m], consecutive, and
+/* One decoder layer over the m pending rows of that layer (Algorithm 1, the layer-update step; Sec. 2.2).  hidden: dev [m, d] fp32, updated in place.  pos: host [m], consecutive, and
  * pos[0] must equal the layer's current cache length; the rows' K/V are appended and the length grows
  * by m.  Row r attends to positions 0..pos[r]. */
 ad_status ad_layer_step(const ad_model *, ad_kv *, int32_t layer, void *hidden, const int32_t *pos, int32_t m,
@@ -125,8 +124,11 @@ ad_status ad_layer_steps(const ad_model *, ad_kv *, int32_t first_layer, int32_t
 /* How ad_layer_step and ad_layer_steps run.  AD_LAYER_KERNELS (the default): one kernel per phase (QKV, attention, fold, Wo,
  * gate/up, down).  AD_LAYER_FUSED (bf16 models with d_model <= 5120 only): one persistent kernel with one workgroup per compute unit
  * and grid barriers between the phases; it needs the device to itself while it runs (no other kernel of this
- * process may occupy compute units at the same time, or a barrier wait can time out; the call after such a
- * time-out returns AD_EDEVICE).  Both modes compute the same function; results may differ in the last bits. */
+ * process may occupy compute units at the same time, or a barrier wait can time out).  A time-out is noticed by
+ * the next call on the model, which returns AD_EDEVICE and puts the barrier back in order: the layer-step call
+ * that timed out had already returned AD_OK and advanced the cache lengths of its layers by m, and the rows it
+ * appended are invalid, so the caller must take the cache back to its length before that call (ad_kv_truncate or
+ * ad_kv_set_len) before going on.  Both modes compute the same function; results may differ in the last bits. */
 enum { AD_LAYER_KERNELS = 0, AD_LAYER_FUSED = 1 };
 ad_status ad_set_layer_mode(ad_model *, int32_t mode);
 

@@ -53,10 +53,10 @@ __device__ __forceinline__ void attn_load_kv(const AttnArgs &a, int item, AttnKv
     const int tid = thread_index(), lane = tid & 63, wave = (tid >> 6) & 3, rh = tid >> 8;
     const int n = lane & 15, gq = lane >> 4;
     if (item >= a.Hkv * a.S) return;
-    const int g = item / a.S, s = item % a.S;
+    const int g = div_small(item, a.mul_S), s = item - g * a.S;
     const int c0 = s * a.C, c1 = (c0 + a.C < a.pos0) ? c0 + a.C : a.pos0;
     const int nbc = (c1 > c0) ? (c1 - c0 + 31) / 32 : 0;
-    const int R = (a.Hq / a.Hkv) * a.m;
+    const int R = a.R;
     if (wave >= nbc || R <= rh * 8) return;
     const uint16_t *Kg = (const uint16_t *)((const char *)a.Kc + kv_off) + (size_t)g * a.stride * DH;
     const uint16_t *Vg = (const uint16_t *)((const char *)a.Vc + kv_off) + (size_t)g * DH * a.stride;
@@ -82,12 +82,12 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
     constexpr int NRH = NTHREADS / 256;      // wavefronts per key block
     const int tid = thread_index(), lane = tid & 63, wave = (tid >> 6) & 3, rh = tid >> 8;
     const int n = lane & 15, gq = lane >> 4;
-    const int G = a.Hq / a.Hkv, R = G * a.m;
+    const int G = a.G, R = a.R;
     const int n_items = a.Hkv * a.S;
     uint16_t *qb16 = (uint16_t *)L.qb;
 
     for (int item = wg; item < n_items; item += nwg) {
-        const int g = item / a.S, s = item % a.S;
+        const int g = div_small(item, a.mul_S), s = item - g * a.S;
         const int c0 = s * a.C, c1 = (c0 + a.C < a.pos0) ? c0 + a.C : a.pos0;
         const int nc = (c1 > c0) ? c1 - c0 : 0;
         const bool last = (s == a.S - 1);
@@ -134,7 +134,7 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
                 const int idx = tid + it * NTHREADS, rr = idx / half, i = idx % half, r = r0 + rr;
                 qx[it] = qy[it] = qc[it] = qs_[it] = 0.f;
                 if (idx < nblk * 8 * half && rr < nr) {
-                    const int t = r / G, hq = g * G + r % G;
+                    const int t = div_small(r, a.mul_G), hq = g * G + (r - t * G);
                     const float *qp = a.qkv + (size_t)t * a.ld + (size_t)hq * DH;
                     qx[it] = Io::ld(qp + i);
                     qy[it] = Io::ld(qp + i + half);
@@ -221,7 +221,7 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
                         sc[c] = add_lane_xor8(s0[c]);
                         sc[4 + c] = add_lane_xor8(s1[c]);
                     }
-                    const int rr = b * 8 + (n & 7), t_row = (r0 + rr) / G;
+                    const int rr = b * 8 + (n & 7), t_row = div_small(r0 + rr, a.mul_G);
                     float mx = -INFINITY;
 #pragma unroll
                     for (int c = 0; c < 8; ++c) {
@@ -264,46 +264,40 @@ __device__ __forceinline__ void attn_mfma_items(const AttnArgs &a, AttnMfmaLds<D
                 }
             }
             __syncthreads();
-            // fold this item's (up to 5) block partials in block order and publish one partial per row:
-            // first the weights exp(max_p - M) of each row's blocks, then the weighted sums, all loads up front
-            float *wts = reinterpret_cast<float *>(L.qb);       // [row][8]: weights of the 5 slots, M, sum (queries are done)
-            if (tid < nr) {
+            // fold this item's (up to 5) block partials in block order and publish one partial per row: a thread takes two
+            // neighbouring dimensions of a row (DH / 2 threads, whole wavefronts, per row), derives the blocks' weights
+            // exp(max_p - M) itself from their (max, sum) pairs (the same LDS words for the whole wavefront), and stores
+            // eight bytes
+            for (int idx = tid; idx < nr * half; idx += NTHREADS) {
+                const int rr = idx / half, e = (idx % half) * 2;
                 float mp[kAttnSlots], M = -INFINITY;
 #pragma unroll
                 for (int p = 0; p < kAttnSlots; ++p) {
                     const bool on = p < 4 ? p < nbc : last;
-                    mp[p] = on ? L.part[((size_t)p * RP + tid) * PL + DH] : -INFINITY;
+                    mp[p] = on ? L.part[((size_t)p * RP + rr) * PL + DH] : -INFINITY;
                     M = fmaxf(M, mp[p]);
                 }
+                // (all slots are read, so that the reads go out together; what a slot without data holds is dropped)
+                float sm[kAttnSlots];
+                f32x2 v[kAttnSlots];
+#pragma unroll
+                for (int p = 0; p < kAttnSlots; ++p) {
+                    sm[p] = L.part[((size_t)p * RP + rr) * PL + DH + 1];
+                    v[p] = *(const f32x2 *)(L.part + ((size_t)p * RP + rr) * PL + e);
+                }
                 float den = 0.f;
+                f32x2 num = {0.f, 0.f};
 #pragma unroll
                 for (int p = 0; p < kAttnSlots; ++p) {
                     const float w = (mp[p] == -INFINITY) ? 0.f : __expf(mp[p] - M);
-                    wts[tid * 8 + p] = w;
-                    if (w != 0.f) den += w * L.part[((size_t)p * RP + tid) * PL + DH + 1];
+                    const bool on = w != 0.f;
+                    den += on ? w * sm[p] : 0.f;
+                    num[0] += on ? w * v[p][0] : 0.f;
+                    num[1] += on ? w * v[p][1] : 0.f;
                 }
-                wts[tid * 8 + 5] = M;
-                wts[tid * 8 + 6] = den;
-            }
-            __syncthreads();
-            for (int idx = tid; idx < nr * DH; idx += NTHREADS) {
-                const int rr = idx / DH, e = idx % DH;
-                float v[kAttnSlots], w[kAttnSlots];
-#pragma unroll
-                for (int p = 0; p < kAttnSlots; ++p) {
-                    w[p] = wts[rr * 8 + p];
-                    v[p] = L.part[((size_t)p * RP + rr) * PL + e];    // slots without data have weight 0
-                }
-                float num = 0.f;
-#pragma unroll
-                for (int p = 0; p < kAttnSlots; ++p)
-                    if (w[p] != 0.f) num += w[p] * v[p];
                 float *out = a.part + (((size_t)g * a.S + s) * R + (r0 + rr)) * PR;
-                Io::st(out + e, num);
-                if (e == 0) {
-                    Io::st(out + DH, wts[rr * 8 + 5]);
-                    Io::st(out + DH + 1, wts[rr * 8 + 6]);
-                }
+                Io::st2(out + e, num);
+                if (e == 0) Io::st2(out + DH, (f32x2){M, den});
             }
             __syncthreads();
         }
@@ -320,9 +314,9 @@ template <class Io, bool F16>
 __device__ __forceinline__ void attn_combine_row(const AttnArgs &a, int row /* 0 .. Hkv * R */) {
     constexpr int NB = 32;                             // splits whose rows are in flight together
     const int DH = a.dh, PR = DH + 2, S = a.S;
-    const int G = a.Hq / a.Hkv, R = G * a.m;
+    const int G = a.G, R = a.R;
     const int lane = thread_index() & 63;
-    const int g = row / R, r = row % R, t = r / G, hq = g * G + r % G;
+    const int g = div_small(row, a.mul_R), r = row - g * R, t = div_small(r, a.mul_G), hq = g * G + (r - t * G);
     const float *base = a.part + ((size_t)g * S * R + r) * PR;
     const size_t sstride = (size_t)R * PR;
     const int e = 2 * lane;                            // this lane's two dimensions

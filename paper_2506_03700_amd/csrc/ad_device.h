@@ -138,6 +138,10 @@ __device__ __forceinline__ float add_lane_xor8(float v) {
     return v + __int_as_float(o);
 }
 
+// x / d for small non-negative x and d, with the multiplier the host derived from d (div_multiplier in ad_internal.h)
+// (a multiplier of 0 stands for d == 1)
+__device__ __forceinline__ int div_small(int x, unsigned mul) { return mul ? (int)__umulhi((unsigned)x, mul) : x; }
+
 // index (in bf16 elements) of input k of column col (token col & 7, hi/lo part col >> 3) in a packed activation
 // block of KT k-steps (see ad_internal.h)
 __device__ __forceinline__ size_t act_index(int k, int col, int KT) {

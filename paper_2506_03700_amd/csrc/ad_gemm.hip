@@ -94,9 +94,7 @@ static int stationary16(const GemmArgs &g, int nks, int grid, hipStream_t s) {
 
 int launch_gemm(const GemmArgs &g, int planes, const LaunchCtx &c) {
     // equal numbers of row tiles per workgroup: with per = ceil(NT / n_wg) tiles each, ceil(NT / per) workgroups
-    const int per = (g.NT + c.n_wg - 1) / c.n_wg;
-    int grid = (g.NT + per - 1) / (per < 1 ? 1 : per);
-    if (grid < 1) grid = 1;
+    const int grid = head_grid(g.NT, c.n_wg);
     hipStream_t s = (hipStream_t)c.stream;
     const bool f16 = g.elem == kElemF16;
     if ((planes == 1) != (g.elem != kElemF32)) return (int)hipErrorInvalidValue;     // fp32 weights are three bf16 planes
@@ -119,6 +117,12 @@ int launch_gemm(const GemmArgs &g, int planes, const LaunchCtx &c) {
         rc = (int)hipGetLastError();
     }
     return rc;
+}
+
+int head_grid(int n_tiles, int n_wg) {
+    const int per = (n_tiles + n_wg - 1) / n_wg;
+    const int grid = (n_tiles + per - 1) / (per < 1 ? 1 : per);
+    return grid < 1 ? 1 : grid;
 }
 
 int gemm_max_stationary_k(int planes) { return (planes == 1 ? kKsMaxWide : kKsMax) * kStatWaves * 32; }

@@ -58,6 +58,7 @@ struct IoPlain {
     static __device__ __forceinline__ f32x4 ld4(const float *p) { return *(const f32x4 *)p; }
     static __device__ __forceinline__ bf16x8 ldb(const bf16x8 *p) { return *p; }
     static __device__ __forceinline__ void st(float *p, float v) { *p = v; }
+    static __device__ __forceinline__ void st2(float *p, f32x2 v) { *(f32x2 *)p = v; }
     static __device__ __forceinline__ void st16(uint16_t *p, uint16_t v) { *p = v; }
 };
 // Relaxed agent-scope atomics: stores go through to memory and loads do not use a stale copy in another
@@ -83,6 +84,11 @@ struct IoAgent {
         return c.v;
     }
     static __device__ __forceinline__ void st(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+    static __device__ __forceinline__ void st2(float *p, f32x2 v) {
+        union { uint64_t u; f32x2 v; } c;
+        c.v = v;
+        __hip_atomic_store((uint64_t *)p, c.u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     static __device__ __forceinline__ void st16(uint16_t *p, uint16_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 };
 
@@ -183,8 +189,8 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, GemmLds &L, int ta, 
 // The wavefront's weight stream is a sequence of chunks of CH k-steps: its K slice of tile t0, of tile t0+1, ...
 // (a slice of nks k-steps is NCH = ceil(nks / CH) chunks).  Two chunk buffers alternate, so one chunk is in
 // flight while the other is multiplied.
-// Weights are addressed as a uniform base pointer plus a 32-bit byte offset (the launchers reject a packed
-// matrix of 4 GiB or more), which costs one address register per load instead of two.  `unit` counts 16 bytes.
+// Weights are addressed as a uniform base pointer plus a 32-bit byte offset (a configuration with a packed
+// matrix of 4 GiB or more is refused when the model is created), which costs one address register per load instead of two.  `unit` counts 16 bytes.
 __device__ __forceinline__ bf16x8 load_tile(const bf16x8 *W, unsigned unit) {
     return __builtin_nontemporal_load((const bf16x8 *)((const char *)W + (unit << 4)));
 }
@@ -401,23 +407,30 @@ __device__ __forceinline__ void gemm_stationary(const GemmArgs &g, StatStream<NP
             if (lane == 0) L.ssq_part[t] = v;
         }
     }
-    __syncthreads();
-    if (tid < 8) {
-        float s = 1.0f;
-        if (g.x && g.norm_w) {
-            s = 0.f;
-            for (int w = 0; w < kWaves; ++w) s += L.ssq_part[w * 8 + tid];
-            s = 1.0f / sqrtf(s * g.inv_dim + g.eps);
-        } else if (!g.x && g.ssq_in) {
-            s = 1.0f / sqrtf(L.ssq_part[tid] * g.inv_dim + g.eps);
-        }
-        L.scale[tid] = s;
-    }
+    // The per-token factor 1 / rms is only needed by the epilogue: it is formed from the wavefronts' partial sums at the
+    // first reduction (after that reduction's barrier, which also orders the partial sums), not here on the way to the
+    // first product.  Only a B operand built through the strips needs a barrier now: the strips alias the slots.
+    if (g.x) __syncthreads();
+    bool scale_set = false;
 
     auto finish_round = [&](int done) {
         // tiles [ta, done) of this round are in the slots: sum them over the wavefronts, then the epilogue
         const int ta = t0 + ((done - t0 - 1) / kTilesPerRound) * kTilesPerRound, nt = done - ta;
         __syncthreads();
+        if (!scale_set) {
+            scale_set = true;
+            if (tid < 8) {
+                float s = 1.0f;
+                if (g.x && g.norm_w) {
+                    s = 0.f;
+                    for (int w = 0; w < kWaves; ++w) s += L.ssq_part[w * 8 + tid];
+                    s = 1.0f / sqrtf(s * g.inv_dim + g.eps);
+                } else if (!g.x && g.ssq_in) {
+                    s = 1.0f / sqrtf(L.ssq_part[tid] * g.inv_dim + g.eps);
+                }
+                L.scale[tid] = s;
+            }
+        }
         for (int idx = tid; idx < nt * 128; idx += kThreads) {
             const int T = idx >> 7, tt = (idx >> 4) & 7, i = idx & 15;
             float v = 0.f;

@@ -73,6 +73,17 @@ bool config_ok(const ad_config *c, const char **why) {
     }
     if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) { *why = "bad rope_base / rms_eps"; return false; }
     if (c->d_model > gemm_max_stationary_k(c->dtype == AD_F32 ? 3 : 1)) { *why = "d_model above 8192 (fp32 models: 5120) is not supported"; return false; }
+    {
+        // the kernels address a packed matrix with a 32-bit byte offset
+        const int planes = c->dtype == AD_F32 ? 3 : 1;
+        const int64_t d = c->d_model, dq = (int64_t)c->n_q_heads * c->head_dim, dkv = (int64_t)c->n_kv_heads * c->head_dim;
+        const size_t lim = (size_t)1 << 32;
+        if (packed_bytes(c->vocab, d, planes) >= lim || packed_bytes(2 * (int64_t)c->d_ffn, d, planes) >= lim ||
+            packed_bytes(d, c->d_ffn, planes) >= lim || packed_bytes(dq + 2 * dkv, d, planes) >= lim || packed_bytes(d, dq, planes) >= lim) {
+            *why = "a weight matrix would take 4 GiB or more in the library's layout (vocab x d_model, 2 d_ffn x d_model, ...)";
+            return false;
+        }
+    }
     return true;
 }
 
@@ -409,7 +420,8 @@ static int fused_health(const ad_model *m, void *stream) {
     *(volatile unsigned *)m->bar_abort = 0;
     m->bar_round = 0;
     if (rc) return hip_fail(rc, "fused layer step: resetting the grid barrier");
-    return fail(AD_EDEVICE, "fused layer step: a grid barrier timed out in an earlier call; its result and the KV cache rows it appended are invalid");
+    return fail(AD_EDEVICE, "fused layer step: a grid barrier timed out in an earlier call; its result and the KV cache rows it appended are "
+                            "invalid (take the cache back to its length before that call)");
 }
 
 static int64_t layer_step_bytes(const ad_config &c, int32_t ctx, int32_t m) {
@@ -463,6 +475,7 @@ static int layer_steps(const ad_model *m, ad_kv *kv, int32_t layer, int32_t coun
         a.C = attn_chunk(ek, L.dh);
         a.S = pos[0] > 0 ? (pos[0] + a.C - 1) / a.C : 1;
         a.part = kv->part; a.Bo = m->Bo; a.Bo_KT = L.kt_q; a.scale = 1.0f / sqrtf((float)L.dh); a.kv_elem = ek;
+        attn_finish(a);
         // 3. x' = x + Wo o
         memset(&go, 0, sizeof go);
         go.elem = ek;

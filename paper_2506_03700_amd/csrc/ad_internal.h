@@ -110,7 +110,22 @@ struct AttnArgs {
     int Bo_KT;            // k-steps of that block (n_q_heads * head_dim / 32)
     float scale;
     int kv_elem;          // ElemKind of the cache (and of the 16-bit operands of the MFMA kernel)
+    // derived by attn_finish() from the fields above, so that the kernels need no integer division on their way to the
+    // first load: query heads per kv head, query rows per kv head, and the multipliers of div_small() for S, G and R
+    int G, R;
+    unsigned mul_S, mul_G, mul_R;
 };
+// x / d == (x * div_multiplier(d)) >> 32 for 0 <= x < 65536 and 1 < d < 65536 (the error of the rounded-up reciprocal,
+// x / 2^32, stays below the 1 / d that separates x / d from the next integer); d == 1, whose multiplier would be
+// 2^32, is encoded as 0
+inline unsigned div_multiplier(int d) { return d <= 1 ? 0u : (unsigned)((0x100000000ull + (unsigned long long)d - 1) / (unsigned long long)d); }
+inline void attn_finish(AttnArgs &a) {
+    a.G = a.Hq / a.Hkv;
+    a.R = a.G * a.m;
+    a.mul_S = div_multiplier(a.S);
+    a.mul_G = div_multiplier(a.G);
+    a.mul_R = div_multiplier(a.R);
+}
 
 // n_layers consecutive decoder-layer steps over the same rows as a single persistent kernel (bf16 models): the four
 // GEMMs and the attention phase of the first of these layers with their usual arguments, the distance in bytes from
@@ -168,6 +183,7 @@ int launch_embed(const EmbedArgs &, void *stream);
 int launch_rope_table(const RopeArgs &, void *stream);
 int gemm_max_stationary_k(int planes);   // largest d_model the stationary GEMM variants cover
 int launch_gemm(const GemmArgs &, int planes, const LaunchCtx &);   // EPI_HEAD: also launches the vocabulary combine
+int head_grid(int n_tiles, int n_wg);                               // workgroups launch_gemm uses for n_tiles row tiles
 int launch_attn(const AttnArgs &, const LaunchCtx &);
 int launch_sample_row(const SampleArgs &, void *stream);
 int launch_verify_sampled(const VerifySampledArgs &, void *stream);

@@ -12,8 +12,13 @@
 // and read with relaxed agent-scope atomics (see IoAgent): the stores go through to memory, a wavefront waits
 // for its stores to complete before it arrives at the barrier, and the loads do not use a stale line of another
 // XCD's L2.  The barrier itself is two levels of relaxed agent-scope counters (eight groups, then one global
-// counter); no cache write-back or invalidate is issued anywhere.  Weights and the cached K/V rows were written
-// by earlier kernels and are read with ordinary loads.
+// counter); no cache write-back is issued anywhere (every exchanged value is stored write-through).  Where the
+// next phase reads a large block that all workgroups share (the packed B operands, x') with ordinary loads, the
+// barrier ends with one agent-scope acquire fence issued by thread 0 of each workgroup: it invalidates that compute
+// unit's L1 and the non-local lines of its XCD's L2, which is all an ordinary load can have stale; one thread is
+// enough because the invalidate acts on the caches, not on the issuing wavefront, and the workgroup's other
+// wavefronts are held at the workgroup barrier that follows it.  Weights and the cached K/V rows were written by
+// earlier kernels and are read with ordinary loads.
 //
 // Every wait is bounded: a workgroup that waits longer than kBarrierTimeoutTicks sets the host-visible abort
 // flag and the whole grid leaves the kernel (the host then reports an error and resets the counters).  The

@@ -294,3 +294,30 @@ def test_ablation_switches_in_the_scheduler():
     assert st["layer_step_rows"] == L * 12
     rows = [e for e in ev if e["kind"] == ad.EV_VERIFY_ROW]
     assert all(int(r["flag"]) == -1 for r in rows)
+
+
+def test_a_matrix_of_4_gib_or_more_is_refused():
+    """The kernels address a packed weight matrix with a 32-bit byte offset: a configuration whose LM head (or any
+    other matrix) would reach 4 GiB in the library's layout is an invalid configuration, not a silent wrap."""
+    import ctypes as C
+    from paper_2506_03700_amd import binding
+    L = binding.lib()
+    ok = synth.LLAMA8B
+    assert L.ad_workspace_bytes(C.byref(binding.make_config(ok))) > 0
+    big = ok.with_(d_model=8192, n_q_heads=64, vocab=262144)            # 262144 x 8192 x 2 B = 4 GiB
+    assert L.ad_workspace_bytes(C.byref(binding.make_config(big))) == 0
+    assert b"4 GiB" in L.ad_last_error()
+    f32 = ok.with_(dtype=synth.F32, d_model=5120, n_q_heads=40, n_kv_heads=40, vocab=152064)     # three planes
+    assert L.ad_workspace_bytes(C.byref(binding.make_config(f32))) == 0
+
+
+def test_small_division_multipliers_are_exact():
+    """The kernels divide small indices by multiplying with a rounded-up reciprocal the host derives
+    (x / d == (x * mul) >> 32, with 0 standing for d == 1): exact over the whole range the kernels use."""
+    def mul(d):
+        return 0 if d <= 1 else (2 ** 32 + d - 1) // d
+    x = np.arange(0, 65536, dtype=np.uint64)
+    for d in list(range(1, 300)) + [511, 512, 513, 1000, 4095, 4096, 9217, 65535]:
+        m = mul(d)
+        got = x if m == 0 else (x * np.uint64(m)) >> np.uint64(32)
+        np.testing.assert_array_equal(got, x // np.uint64(d), err_msg=f"d={d}")
