@@ -147,6 +147,18 @@ ad_status ad_exit_head(const ad_model *, int32_t layer, const void *hidden_row, 
 ad_status ad_verify(const ad_model *, const void *hidden, const int32_t *draft, int32_t m, int32_t *n_accept,
                     int32_t *next_token, int32_t *row_argmax, void *stream);
 
+/* ad_verify for callers that cannot allocate device memory and have no workspace to lend at that point: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result.  The
+ * per-workgroup partials of the vocabulary pass (the only scratch this call needs beyond the model's weights) are
+ * kept in a static device array inside the library (512 KiB per GPU, room for 4096 workgroups x 8 rows; a device
+ * whose vocabulary pass would use more workgroups gets AD_ERANGE) instead of the model's workspace, and the call
+ * performs no allocation of any kind: no hipMalloc / hipFree, no event creation (its launches are not sampled by
+ * ad_profile_start).  All models on one GPU share that array and it keeps the last call's contents (every slot
+ * that is read has been rewritten by the same call, nothing needs clearing): calls that overlap on one GPU race,
+ * so issue them on one stream or order them otherwise. */
+ad_status ad_verify_static(const ad_model *, const void *hidden, const int32_t *draft, int32_t m, int32_t *n_accept,
+                           int32_t *next_token, int32_t *row_argmax, void *stream);
+
 /* The logits the head at `layer` assigns to m rows (the distributions that sampled decoding draws from and
  * verifies against; also used by tests).  logits: dev [m, vocab] fp32. */
 ad_status ad_head_logits(const ad_model *, int32_t layer, const void *hidden, int32_t m, void *logits, void *stream);

@@ -25,6 +25,7 @@ AD_PROF_GEMM, AD_PROF_LAYER = 0, 1
 
 EXPORTS = ["ad_workspace_bytes", "ad_model_create", "ad_model_destroy", "ad_kv_bytes", "ad_kv_create", "ad_kv_destroy",
            "ad_kv_len", "ad_kv_set_len", "ad_kv_truncate", "ad_embed", "ad_layer_step", "ad_layer_steps", "ad_set_layer_mode", "ad_exit_head", "ad_verify",
+           "ad_verify_static",
            "ad_head_logits", "ad_sample_logits", "ad_verify_sampled", "ad_generate", "ad_layer_trace", "ad_profile_start", "ad_profile_stop", "ad_last_error", "ad_version"]
 
 
@@ -98,6 +99,7 @@ def lib() -> C.CDLL:
         L.ad_layer_steps.argtypes = [P, P, i32, i32, P, P, i32, P]
         L.ad_exit_head.argtypes = [P, i32, P, P, P, P]
         L.ad_verify.argtypes = [P, P, P, i32, P, P, P, P]
+        L.ad_verify_static.argtypes = [P, P, P, i32, P, P, P, P]
         L.ad_head_logits.argtypes = [P, i32, P, i32, P, P]
         L.ad_sample_logits.argtypes = [P, P, C.c_float, C.c_float, P, P, P]
         L.ad_verify_sampled.argtypes = [P, P, P, P, i32, C.c_float, P, P, C.c_float, P, P, P, P]
@@ -281,7 +283,8 @@ class Model:
         torch.cuda.current_stream().synchronize()
         return int(out[0]), float(out[1:2].view(torch.float32)[0])
 
-    def ad_verify(self, hidden, draft: Sequence[int]):
+    def ad_verify(self, hidden, draft: Sequence[int], static: bool = False):
+        """static: through ad_verify_static (the library's own static scratch, no allocation)."""
         torch = self.torch
         m = hidden.shape[0]
         assert hidden.dtype == torch.float32 and hidden.is_contiguous() and hidden.shape[1] == self.shape.d_model
@@ -289,8 +292,9 @@ class Model:
         assert d.size == m - 1
         dptr = d.ctypes.data if m > 1 else None
         out = self._pinned
-        _check(self.L.ad_verify(self.model, C.c_void_p(hidden.data_ptr()), dptr, m, C.c_void_p(out.data_ptr() + 32),
-                                C.c_void_p(out.data_ptr() + 36), C.c_void_p(out.data_ptr() + 64), _stream_ptr(torch)))
+        fn = self.L.ad_verify_static if static else self.L.ad_verify
+        _check(fn(self.model, C.c_void_p(hidden.data_ptr()), dptr, m, C.c_void_p(out.data_ptr() + 32),
+                  C.c_void_p(out.data_ptr() + 36), C.c_void_p(out.data_ptr() + 64), _stream_ptr(torch)))
         torch.cuda.current_stream().synchronize()
         return int(out[8]), int(out[9]), out[16:16 + m].numpy().copy()
 

@@ -5,6 +5,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "ad_device.h"
 #include "ad_gemm_device.h"
 #include "ad_internal.h"
@@ -117,6 +119,36 @@ int launch_gemm(const GemmArgs &g, int planes, const LaunchCtx &c) {
         rc = (int)hipGetLastError();
     }
     return rc;
+}
+
+// ---- scratch for callers that cannot allocate --------------------------------------------------------------
+// The vocabulary pass leaves one (max, sum of exp, argmax) partial per workgroup and token, which its second kernel
+// folds.  Normally they live in the model's workspace; the allocation-free entry point keeps them in this
+// file-scope array instead: kStaticHeadParts workgroups x 8 tokens x 4 floats = 512 KiB, held by every GPU the
+// library runs on until the process ends.  In host code the array's name is only a stand-in for the symbol: its
+// device address is asked for once per device (with that device current) and kept.
+static __device__ __align__(256) float scratch[(size_t)kStaticHeadParts * 8 * 4];
+
+int static_head_scratch(float **ptr) {
+    constexpr int kMaxDevices = 64;
+    static float *addr[kMaxDevices];
+    static bool have[kMaxDevices];
+    static std::mutex mu;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!have[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        addr[dev] = (float *)p;
+        have[dev] = true;
+    }
+    *ptr = addr[dev];
+    return 0;
 }
 
 int head_grid(int n_tiles, int n_wg) {

@@ -279,6 +279,10 @@ ad_status ad_model_create(const ad_config *cfg, const ad_layer_weights *layers, 
     *m->bar_abort = 0;
     m->layer_mode = AD_LAYER_KERNELS;
     m->layer_trace = nullptr;
+    {   // set-up for ad_verify_static on this device: the address of the library's static scratch
+        float *part = nullptr;
+        AD_TRY(static_head_scratch(&part), "address of the static scratch");
+    }
     AD_TRY(stream_sync(stream), "model creation");
 #undef AD_TRY
     *out = m;
@@ -554,8 +558,11 @@ ad_status ad_layer_steps(const ad_model *m, ad_kv *kv, int32_t first_layer, int3
     return (ad_status)layer_steps(m, kv, first_layer, n_layers, hidden, pos, n, stream, "ad_layer_steps");
 }
 
-// Head at `layer` over n rows; shared by ad_exit_head, ad_verify and ad_head_logits.
-static int run_head(const ad_model *m, int32_t layer, const void *hidden, int32_t n, GemmArgs &g, void *stream, const char *who) {
+// Head at `layer` over n rows; shared by ad_exit_head, ad_verify, ad_verify_static and ad_head_logits.
+// head_part: where the vocabulary pass keeps its per-workgroup partials (null: the model's workspace).
+// profiled: the launches take part in ad_profile_start's sampling (which creates events).
+static int run_head(const ad_model *m, int32_t layer, const void *hidden, int32_t n, GemmArgs &g, void *stream, const char *who,
+                    float *head_part = nullptr, bool profiled = true) {
     const ad_config &c = m->cfg;
     int slot = -1;
     if (layer != c.n_layers) {
@@ -569,7 +576,10 @@ static int run_head(const ad_model *m, int32_t layer, const void *hidden, int32_
     int rc;
     g.elem = ek;
     g.W = m->head; g.NT = (L.V + 15) / 16; g.KT = L.kt_d; g.N = L.V; g.K = L.d; g.m = n; g.mode = GEMM_STATIONARY;
-    g.epi = EPI_HEAD; g.head_part = m->head_part;
+    g.epi = EPI_HEAD; g.head_part = head_part ? head_part : m->head_part;
+    auto gemm = [&](const ad_model *mm, const GemmArgs &ga, int64_t rows, int64_t cols, const LaunchCtx &c) {
+        return profiled ? ::gemm(mm, ga, rows, cols, c) : launch_gemm(ga, mm->lay.planes, c);
+    };
     if (slot >= 0 && m->T[slot]) {
         // lightweight head of Sec. 2.1: E = E* T, applied as E* (T norm(h))
         GemmArgs t;
@@ -605,6 +615,24 @@ ad_status ad_verify(const ad_model *m, const void *hidden, const int32_t *draft,
     g.verify = 1; g.n_accept_out = n_accept; g.next_out = next_token; g.tok_out = row_argmax;
     for (int i = 0; i + 1 < n; ++i) g.draft[i] = draft[i];
     return (ad_status)run_head(m, m->cfg.n_layers, hidden, n, g, stream, "ad_verify");
+}
+
+ad_status ad_verify_static(const ad_model *m, const void *hidden, const int32_t *draft, int32_t n, int32_t *n_accept, int32_t *next_token,
+                           int32_t *row_argmax, void *stream) {
+    if (!m || !hidden || !n_accept || !next_token || (n > 1 && !draft)) return (ad_status)fail(AD_EINVAL, "ad_verify_static: null argument");
+    if (n < 1 || n > m->cfg.m_max) return (ad_status)fail(AD_ERANGE, "ad_verify_static: m = %d outside 1..%d", n, m->cfg.m_max);
+    const int parts = head_grid((m->lay.V + 15) / 16, m->n_wg);
+    if (parts > kStaticHeadParts)
+        return (ad_status)fail(AD_ERANGE, "ad_verify_static: the vocabulary pass would run on %d workgroups, the static scratch holds the partials of %d",
+                               parts, kStaticHeadParts);
+    float *part = nullptr;
+    const int rc = static_head_scratch(&part);
+    if (rc) return (ad_status)hip_fail(rc, "ad_verify_static: address of the static scratch");
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.verify = 1; g.n_accept_out = n_accept; g.next_out = next_token; g.tok_out = row_argmax;
+    for (int i = 0; i + 1 < n; ++i) g.draft[i] = draft[i];
+    return (ad_status)run_head(m, m->cfg.n_layers, hidden, n, g, stream, "ad_verify_static", part, false);
 }
 
 ad_status ad_head_logits(const ad_model *m, int32_t layer, const void *hidden, int32_t n, void *logits, void *stream) {

@@ -184,6 +184,10 @@ int launch_rope_table(const RopeArgs &, void *stream);
 int gemm_max_stationary_k(int planes);   // largest d_model the stationary GEMM variants cover
 int launch_gemm(const GemmArgs &, int planes, const LaunchCtx &);   // EPI_HEAD: also launches the vocabulary combine
 int head_grid(int n_tiles, int n_wg);                               // workgroups launch_gemm uses for n_tiles row tiles
+// The library's own static device array for the vocabulary pass's per-workgroup partials (room for kStaticHeadParts
+// workgroups): its address on the current device, resolved on first use per device.  Allocates nothing.
+constexpr int kStaticHeadParts = 4096;
+int static_head_scratch(float **ptr);
 int launch_attn(const AttnArgs &, const LaunchCtx &);
 int launch_sample_row(const SampleArgs &, void *stream);
 int launch_verify_sampled(const VerifySampledArgs &, void *stream);
