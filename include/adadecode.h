@@ -210,6 +210,12 @@ typedef struct {
                                     fixed-layer variant with one head) */
     int32_t no_verify;           /* 1: early predictions are kept unchecked; the last layer only produces the next
                                     token from the newest row (the output may then differ from plain decoding) */
+    int32_t no_issue_ahead;      /* 0: behind the kernels of a head evaluation the library already issues the first
+                                    kernel of what the schedule expects to do next (the QKV projection of the next
+                                    layer step, or the next token's embedding and its first QKV projection), so the
+                                    GPU has work while the host waits for the outcome and decides; work issued for
+                                    an outcome that did not occur is dropped.  1: nothing is issued before the
+                                    outcome is known.  Tokens, statistics and events are the same either way. */
 } ad_gen_params;
 
 typedef struct {

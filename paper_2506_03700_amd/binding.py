@@ -47,7 +47,7 @@ class TopWeights(C.Structure):
 class GenParams(C.Structure):
     _fields_ = [("gamma", C.c_float), ("max_pending", C.c_int32), ("max_new", C.c_int32), ("eos_id", C.c_int32),
                 ("forced_exit", C.c_void_p), ("scripted_draft", C.c_void_p), ("temperature", C.c_float), ("uniforms", C.c_void_p),
-                ("head_mask", C.c_int32), ("no_verify", C.c_int32)]
+                ("head_mask", C.c_int32), ("no_verify", C.c_int32), ("no_issue_ahead", C.c_int32)]
 
 
 class Stats(C.Structure):
@@ -341,9 +341,11 @@ class Model:
     def ad_generate(self, prompt, max_new: int, gamma: float, max_pending: int = 5, eos_id: int = -1,
                     forced_exit: Optional[np.ndarray] = None, scripted_draft: Optional[np.ndarray] = None,
                     max_events: int = 1 << 20, want_events: bool = True, temperature: float = 0.0,
-                    uniforms: Optional[np.ndarray] = None, head_mask: int = 0, no_verify: bool = False):
+                    uniforms: Optional[np.ndarray] = None, head_mask: int = 0, no_verify: bool = False,
+                    no_issue_ahead: bool = False):
         """temperature > 0: sampled decoding with the draws `uniforms`, float32 [max_pos, n_exit + 3].
-        head_mask / no_verify: ablation switches (bit i enables exit head i; drafts are kept unchecked)."""
+        head_mask / no_verify: ablation switches (bit i enables exit head i; drafts are kept unchecked).
+        no_issue_ahead: nothing is issued behind a head evaluation before its outcome is known."""
         torch = self.torch
         p = np.ascontiguousarray(prompt, dtype=np.int32)
         if temperature > 0:
@@ -358,7 +360,8 @@ class Model:
         gp = GenParams(gamma, max_pending, max_new, eos_id,
                        None if forced_exit is None else forced_exit.ctypes.data,
                        None if scripted_draft is None else scripted_draft.ctypes.data,
-                       temperature, uniforms.ctypes.data if temperature > 0 else None, head_mask, int(no_verify))
+                       temperature, uniforms.ctypes.data if temperature > 0 else None, head_mask, int(no_verify),
+                       int(no_issue_ahead))
         out = np.empty(max_new, dtype=np.int32)
         ev = np.zeros(max_events if want_events else 1, dtype=EVENT_DTYPE)
         n, nev, st = C.c_int32(), C.c_int64(), Stats()
@@ -408,6 +411,8 @@ def sched_test_lib() -> C.CDLL:
                                         C.POINTER(Stats), P, C.c_int64, P, P]
         L.ad_sched_test_stretches.restype = C.c_int64
         L.ad_sched_test_stretches.argtypes = [P, C.c_int64]
+        L.ad_sched_test_hints.restype = C.c_int64
+        L.ad_sched_test_hints.argtypes = [P, C.c_int64]
         _sched = L
     return _sched
 
@@ -422,11 +427,22 @@ def sched_test_stretches() -> np.ndarray:
     return out[:n]
 
 
+def sched_test_hints() -> np.ndarray:
+    """The hints the scheduler gave before the head evaluations of the last sched_test_run (what it would do next
+    under the expected outcome): rows of (kind 1 = next layer / 2 = next token, layer, first row, rows, 1 if the
+    calls after the evaluation asked for exactly that work)."""
+    L = sched_test_lib()
+    n = L.ad_sched_test_hints(None, 0)
+    out = np.zeros((max(int(n), 1), 5), dtype=np.int32)
+    L.ad_sched_test_hints(out.ctypes.data, n)
+    return out[:n]
+
+
 def sched_test_run(n_layers: int, exit_layers: Sequence[int], m_max: int, head_tok: np.ndarray, head_conf: np.ndarray,
                    final_tok: np.ndarray, prompt, max_new: int, gamma: float, max_pending: int, eos_id: int = -1,
                    forced_exit: Optional[np.ndarray] = None, scripted_draft: Optional[np.ndarray] = None, max_events: int = 1 << 18,
                    max_pos: Optional[int] = None, sequence: bool = False, temperature: float = 0.0,
-                   uniforms: Optional[np.ndarray] = None, head_mask: int = 0, no_verify: bool = False):
+                   uniforms: Optional[np.ndarray] = None, head_mask: int = 0, no_verify: bool = False, no_issue_ahead: bool = False):
     """Runs the library's host scheduler over scripted head outputs (no GPU).
 
     Table mode: head_tok/head_conf [max_pos, n_exit], final_tok [max_pos], looked up by position.
@@ -447,7 +463,7 @@ def sched_test_run(n_layers: int, exit_layers: Sequence[int], m_max: int, head_t
         scripted_draft = np.ascontiguousarray(scripted_draft, dtype=np.int32)
     gp = GenParams(gamma, max_pending, max_new, eos_id, None if forced_exit is None else forced_exit.ctypes.data,
                    None if scripted_draft is None else scripted_draft.ctypes.data, temperature,
-                   None if uniforms is None else uniforms.ctypes.data, head_mask, int(no_verify))
+                   None if uniforms is None else uniforms.ctypes.data, head_mask, int(no_verify), int(no_issue_ahead))
     draws = np.full(4, -1.0, dtype=np.float32)
     out = np.empty(max_new + AD_M_MAX, dtype=np.int32)
     ev = np.zeros(max_events, dtype=EVENT_DTYPE)

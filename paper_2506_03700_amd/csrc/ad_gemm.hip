@@ -70,6 +70,10 @@ __global__ void __launch_bounds__(512) k_head_combine(GemmArgs g) {
         *g.n_accept_out = acc;
         *g.next_out = idx_sh[acc];
     }
+    if (g.done_flag && threadIdx.x == 0) {
+        // the other wavefronts' results were written before the barrier above: this release covers them too
+        __hip_atomic_store(g.done_flag, g.done_seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
 }
 
 template <int NPL, int MODE, int NCHMAX, bool F16 = false>

@@ -7,6 +7,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+#include <chrono>
 #include <new>
 #include <vector>
 
@@ -155,7 +157,8 @@ struct ad_model {
     float *qkv, *x1, *rows, *head_part;
     float *samp_stats, *draft_logits, *final_logits;   // sampled decoding
     // pinned host results for ad_generate
-    int32_t *pin;         // [0..8) tok, [8] n_accept, [9] next, [16..24) row argmax
+    int32_t *pin;         // [0..8) tok, [8] n_accept, [9] next, [16..24) row argmax, [28] the head's done word
+    mutable int32_t done_seq = 0;   // last value asked for in the done word (unique per head evaluation of this model)
     float *pin_conf;      // [8]
     // fused layer step: mode, barrier counters (device), barriers completed so far, abort word (pinned host)
     int32_t layer_mode;
@@ -405,6 +408,7 @@ ad_status ad_embed(const ad_model *m, const int32_t *tokens, int32_t n, void *hi
     if (!m || !tokens || !hidden) return (ad_status)fail(AD_EINVAL, "ad_embed: null argument");
     if (n < 1 || n > m->cfg.m_max) return (ad_status)fail(AD_ERANGE, "ad_embed: m = %d outside 1..%d", n, m->cfg.m_max);
     EmbedArgs a;
+    memset(&a, 0, sizeof a);
     a.table = m->embed; a.elem = elem_kind(m->cfg); a.d = m->cfg.d_model; a.m = n; a.out = (float *)hidden;
     for (int i = 0; i < n; ++i) {
         if (tokens[i] < 0 || tokens[i] >= m->cfg.vocab) return (ad_status)fail(AD_ERANGE, "ad_embed: token %d outside the vocabulary", tokens[i]);
@@ -412,6 +416,16 @@ ad_status ad_embed(const ad_model *m, const int32_t *tokens, int32_t n, void *hi
     }
     int rc = launch_embed(a, stream);
     return rc ? (ad_status)hip_fail(rc, "ad_embed") : AD_OK;
+}
+
+// One row's embedding, the token id read by the kernel from *token_src (written by an earlier kernel on the stream).
+static int embed_from(const ad_model *m, const int32_t *token_src, void *hidden, void *stream) {
+    EmbedArgs a;
+    memset(&a, 0, sizeof a);
+    a.table = m->embed; a.elem = elem_kind(m->cfg); a.d = m->cfg.d_model; a.m = 1; a.out = (float *)hidden;
+    a.tok_src = token_src; a.vocab = m->cfg.vocab;
+    const int rc = launch_embed(a, stream);
+    return rc ? hip_fail(rc, "embedding issued ahead") : AD_OK;
 }
 
 // The fused layer step's grid barrier gave up in an earlier launch (it never should: the grid is co-resident):
@@ -435,10 +449,35 @@ static int64_t layer_step_bytes(const ad_config &c, int32_t ctx, int32_t m) {
     return w + 2 * dkv * s * ((int64_t)ctx + m) + 2 * dkv * s * m;
 }
 
+// Step 1 of a layer: q, k, v = W (RMSNorm(x)).  The norm is fused into the GEMM (B operand built from x in its
+// prologue, or taken packed, with the sums of squares, from the previous layer's last step).
+static void qkv_args(const ad_model *m, int32_t ly, const void *hidden, int32_t n, bool from_prev, GemmArgs &gq) {
+    const ad_config &c = m->cfg;
+    const Layout &L = m->lay;
+    const LayerPacked &lp = m->layers[ly - 1];
+    const int ek = elem_kind(c);
+    memset(&gq, 0, sizeof gq);
+    gq.elem = ek;
+    gq.W = lp.wqkv; gq.NT = L.nqkv / 16; gq.KT = L.kt_d; gq.N = L.nqkv; gq.K = L.d; gq.m = n; gq.mode = GEMM_STATIONARY;
+    gq.inv_dim = 1.0f / (float)L.d; gq.eps = c.rms_eps;
+    if (from_prev) { gq.B = m->Bq; gq.ssq_in = m->ssq_q; gq.ssq_tiles = L.d / 16; }
+    else { gq.x = (const float *)hidden; gq.ldx = L.d; gq.norm_w = lp.attn_norm; gq.norm_elem = ek; }
+    gq.epi = EPI_STORE; gq.out = m->qkv; gq.ld = L.nqkv;
+}
+
+// Step 1 of layer `layer` over n rows, issued on its own ahead of the rest of the step (which layer_steps then runs
+// with first_qkv_issued set, provided nothing else used the q/k/v workspace in between).  Separate-kernel mode only.
+static int qkv_ahead(const ad_model *m, int32_t layer, const void *hidden, int32_t n, void *stream) {
+    GemmArgs gq;
+    qkv_args(m, layer, hidden, n, false, gq);
+    const int rc = gemm(m, gq, m->lay.nqkv, m->lay.d, LaunchCtx{stream, m->n_wg});
+    return rc ? hip_fail(rc, "layer step: qkv issued ahead") : AD_OK;
+}
+
 // Layers layer .. layer + count - 1 over the same rows.  The fused mode runs them in one launch (the layers' weights
 // and caches are laid out at a constant distance from one layer to the next); otherwise one layer at a time.
 static int layer_steps(const ad_model *m, ad_kv *kv, int32_t layer, int32_t count, void *hidden, const int32_t *pos, int32_t n,
-                       void *stream, const char *who) {
+                       void *stream, const char *who, bool first_qkv_issued = false) {
     if (!m || !kv || !hidden || !pos) return fail(AD_EINVAL, "%s: null argument", who);
     if (kv->model != m) return fail(AD_EINVAL, "%s: cache belongs to another model", who);
     const ad_config &c = m->cfg;
@@ -462,15 +501,8 @@ static int layer_steps(const ad_model *m, ad_kv *kv, int32_t layer, int32_t coun
     AttnArgs a;
     auto build = [&](int32_t ly, bool from_prev, bool feeds_next) {
         const LayerPacked &lp = m->layers[ly - 1];
-        // 1. q, k, v = W (RMSNorm(x)): the norm is fused into the GEMM (B operand built from x in its prologue, or taken
-        //    packed, with the sums of squares, from the previous layer's last step)
-        memset(&gq, 0, sizeof gq);
-        gq.elem = ek;
-        gq.W = lp.wqkv; gq.NT = L.nqkv / 16; gq.KT = L.kt_d; gq.N = L.nqkv; gq.K = L.d; gq.m = n; gq.mode = GEMM_STATIONARY;
-        gq.inv_dim = 1.0f / (float)L.d; gq.eps = c.rms_eps;
-        if (from_prev) { gq.B = m->Bq; gq.ssq_in = m->ssq_q; gq.ssq_tiles = L.d / 16; }
-        else { gq.x = (const float *)hidden; gq.ldx = L.d; gq.norm_w = lp.attn_norm; gq.norm_elem = ek; }
-        gq.epi = EPI_STORE; gq.out = m->qkv; gq.ld = L.nqkv;
+        // 1. q, k, v = W (RMSNorm(x))
+        qkv_args(m, ly, hidden, n, from_prev, gq);
         // 2. rotary embedding, KV append, attention (partials + combine)
         memset(&a, 0, sizeof a);
         a.qkv = m->qkv; a.ld = L.nqkv; a.rope = kv->rope + (size_t)pos[0] * (L.dh / 2) * 2;
@@ -508,7 +540,7 @@ static int layer_steps(const ad_model *m, ad_kv *kv, int32_t layer, int32_t coun
         // one kernel per phase, layer after layer
         for (int32_t ly = layer; ly < layer + count; ++ly) {
             build(ly, ly > layer, ly + 1 < layer + count);
-            if ((rc = gemm(m, gq, L.nqkv, L.d, ctx))) return hip_fail(rc, "layer step: qkv");
+            if (!(first_qkv_issued && ly == layer) && (rc = gemm(m, gq, L.nqkv, L.d, ctx))) return hip_fail(rc, "layer step: qkv");
             if ((rc = launch_attn(a, ctx))) return hip_fail(rc, "layer step: attention");
             if ((rc = gemm(m, go, L.d, L.dq, ctx))) return hip_fail(rc, "layer step: wo");
             if ((rc = gemm(m, gg, 2 * (int64_t)L.f, L.d, ctx))) return hip_fail(rc, "layer step: gate/up");
@@ -516,6 +548,7 @@ static int layer_steps(const ad_model *m, ad_kv *kv, int32_t layer, int32_t coun
         }
     } else {
         // the whole stretch in one persistent kernel
+        if (first_qkv_issued) return fail(AD_ESTATE, "%s: the fused layer step runs its own QKV projection", who);
         const LayerPacked &lp = m->layers[layer - 1];
         if ((rc = fused_health(m, stream))) return rc;
         // the stretch's first layer as it runs when it is also the last (nothing handed on), then the two variants
@@ -597,24 +630,36 @@ static int run_head(const ad_model *m, int32_t layer, const void *hidden, int32_
     return AD_OK;
 }
 
-ad_status ad_exit_head(const ad_model *m, int32_t layer, const void *hidden_row, int32_t *token, float *conf, void *stream) {
-    if (!m || !hidden_row || !token || !conf) return (ad_status)fail(AD_EINVAL, "ad_exit_head: null argument");
-    if (layer < 1 || layer > m->cfg.n_layers) return (ad_status)fail(AD_ERANGE, "ad_exit_head: layer %d outside 1..%d", layer, m->cfg.n_layers);
+// done_flag / done_seq: see GemmArgs (null: none)
+static int exit_head(const ad_model *m, int32_t layer, const void *hidden_row, int32_t *token, float *conf, void *stream,
+                     int32_t *done_flag, int32_t done_seq) {
+    if (!m || !hidden_row || !token || !conf) return fail(AD_EINVAL, "ad_exit_head: null argument");
+    if (layer < 1 || layer > m->cfg.n_layers) return fail(AD_ERANGE, "ad_exit_head: layer %d outside 1..%d", layer, m->cfg.n_layers);
     GemmArgs g;
     memset(&g, 0, sizeof g);
-    g.tok_out = token; g.conf_out = conf;
-    return (ad_status)run_head(m, layer, hidden_row, 1, g, stream, "ad_exit_head");
+    g.tok_out = token; g.conf_out = conf; g.done_flag = done_flag; g.done_seq = done_seq;
+    return run_head(m, layer, hidden_row, 1, g, stream, "ad_exit_head");
+}
+
+ad_status ad_exit_head(const ad_model *m, int32_t layer, const void *hidden_row, int32_t *token, float *conf, void *stream) {
+    return (ad_status)exit_head(m, layer, hidden_row, token, conf, stream, nullptr, 0);
+}
+
+static int verify(const ad_model *m, const void *hidden, const int32_t *draft, int32_t n, int32_t *n_accept, int32_t *next_token,
+                  int32_t *row_argmax, void *stream, int32_t *done_flag, int32_t done_seq) {
+    if (!m || !hidden || !n_accept || !next_token || (n > 1 && !draft)) return fail(AD_EINVAL, "ad_verify: null argument");
+    if (n < 1 || n > m->cfg.m_max) return fail(AD_ERANGE, "ad_verify: m = %d outside 1..%d", n, m->cfg.m_max);
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.verify = 1; g.n_accept_out = n_accept; g.next_out = next_token; g.tok_out = row_argmax;
+    g.done_flag = done_flag; g.done_seq = done_seq;
+    for (int i = 0; i + 1 < n; ++i) g.draft[i] = draft[i];
+    return run_head(m, m->cfg.n_layers, hidden, n, g, stream, "ad_verify");
 }
 
 ad_status ad_verify(const ad_model *m, const void *hidden, const int32_t *draft, int32_t n, int32_t *n_accept, int32_t *next_token,
                     int32_t *row_argmax, void *stream) {
-    if (!m || !hidden || !n_accept || !next_token || (n > 1 && !draft)) return (ad_status)fail(AD_EINVAL, "ad_verify: null argument");
-    if (n < 1 || n > m->cfg.m_max) return (ad_status)fail(AD_ERANGE, "ad_verify: m = %d outside 1..%d", n, m->cfg.m_max);
-    GemmArgs g;
-    memset(&g, 0, sizeof g);
-    g.verify = 1; g.n_accept_out = n_accept; g.next_out = next_token; g.tok_out = row_argmax;
-    for (int i = 0; i + 1 < n; ++i) g.draft[i] = draft[i];
-    return (ad_status)run_head(m, m->cfg.n_layers, hidden, n, g, stream, "ad_verify");
+    return (ad_status)verify(m, hidden, draft, n, n_accept, next_token, row_argmax, stream, nullptr, 0);
 }
 
 ad_status ad_verify_static(const ad_model *m, const void *hidden, const int32_t *draft, int32_t n, int32_t *n_accept, int32_t *next_token,
@@ -748,11 +793,48 @@ struct GpuBackend : Backend {
 
     float *row(int32_t r) const { return m->rows + (size_t)r * m->cfg.d_model; }
 
+    // The decision after a head evaluation is taken on the host (Algorithm 1's branch on the confidence, the
+    // verification's accept count), so the GPU idles from the head's last kernel until the next launch arrives.
+    // Waiting for the stream to drain adds the runtime's completion path to that gap; instead the head's second
+    // kernel publishes a sequence number in pinned memory after its results, and this thread polls that word.
+    // If it does not appear within kPollMs (a failed launch, a device error), the ordinary wait takes over
+    // and reports what happened.
+    static constexpr int kPollMs = 200;
+    int32_t *done_flag() const { return m->pin + 28; }
+    int32_t next_seq() const {
+        if (++m->done_seq == 0) ++m->done_seq;     // 0 is the word's initial value
+        return m->done_seq;
+    }
+    int wait_done(const char *what) {
+        const volatile int32_t *flag = done_flag();
+        const int32_t want = m->done_seq;
+        const auto t0 = std::chrono::steady_clock::now();
+        for (unsigned spins = 1; *flag != want; ++spins) {
+            __builtin_ia32_pause();
+            if ((spins & 4095) == 0 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(kPollMs)) break;
+        }
+        std::atomic_thread_fence(std::memory_order_acquire);
+        if (*flag == want && ++polled < kSyncEvery) return AD_OK;
+        // now and then, and whenever the word did not appear, drain the stream: the runtime releases what it keeps
+        // per launch, and errors of earlier launches surface here
+        polled = 0;
+        const int rc = stream_sync(stream);
+        if (rc) return hip_fail(rc, what);
+        if (*flag != want) return fail(AD_EDEVICE, "%s: the head finished without publishing its result", what);
+        return AD_OK;
+    }
+    static constexpr int kSyncEvery = 256;
+    int polled = 0;
+
     int layer_step(int32_t layer, int32_t row0, int32_t n, int32_t pos0) override { return layer_steps(layer, 1, row0, n, pos0); }
     int layer_steps(int32_t first_layer, int32_t count, int32_t row0, int32_t n, int32_t pos0) override {
         for (int i = 0; i < n; ++i) pos_buf[i] = pos0 + i;
         if (!in_prefill) bytes += count * layer_step_bytes(m->cfg, pos0, n);
-        return ad_layer_steps(m, kv, first_layer, count, row(row0), pos_buf, n, stream);
+        // the step's QKV projection may already be on the stream
+        const bool qkv_there = issued.kind != AHEAD_NONE && issued.layer == first_layer && issued.row0 == row0 && issued.m == n &&
+                               (issued.kind == AHEAD_LAYER || embed_taken) && m->layer_mode == AD_LAYER_KERNELS;
+        issued.kind = AHEAD_NONE;
+        return ::layer_steps(m, kv, first_layer, count, row(row0), pos_buf, n, stream, "ad_layer_steps", qkv_there);
     }
     int prefill(const int32_t *tokens, int32_t n) override {
         const int32_t chunk = m->cfg.m_max;
@@ -766,11 +848,42 @@ struct GpuBackend : Backend {
         in_prefill = false;
         return rc;
     }
-    int embed(int32_t token, int32_t r) override { return ad_embed(m, &token, 1, row(r), stream); }
-    int exit_head(int32_t layer, int32_t r, int32_t, int32_t *token, float *conf) override {
-        int rc = ad_exit_head(m, layer, row(r), m->pin, m->pin_conf, stream);
+    // ---- work issued ahead of a head's outcome (see Backend::expect) ----
+    Ahead hint{AHEAD_NONE, 0, 0, 0};      // for the next head evaluation
+    Ahead issued{AHEAD_NONE, 0, 0, 0};    // what is in flight or done, not yet taken over by the schedule
+    const int32_t *issued_tok = nullptr;  // AHEAD_TOKEN: the pinned word the embedding kernel read its token from
+    bool embed_taken = false;             // AHEAD_TOKEN: the schedule has asked for exactly that embedding
+
+    void expect(const Ahead &a) override { hint = a; }
+    // Behind the head's kernels: the embedding of the token they produce (tok_src, pinned) if that is what comes
+    // next, and the QKV projection of the step that follows.  Only in separate-kernel mode: the fused layer
+    // kernel has no entry behind its QKV phase.
+    int issue_ahead(const int32_t *tok_src) {
+        const Ahead h = hint;
+        hint.kind = issued.kind = AHEAD_NONE;
+        if (h.kind == AHEAD_NONE || m->layer_mode != AD_LAYER_KERNELS) return AD_OK;
+        if (h.layer < 1 || h.layer > m->cfg.n_layers || h.row0 < 0 || h.m < 1 || h.row0 + h.m > m->cfg.m_max) return AD_OK;
+        int rc = AD_OK;
+        if (h.kind == AHEAD_TOKEN) rc = embed_from(m, tok_src, row(h.row0), stream);
+        if (rc == AD_OK) rc = qkv_ahead(m, h.layer, row(h.row0), h.m, stream);
         if (rc != AD_OK) return rc;
-        if ((rc = stream_sync(stream))) return hip_fail(rc, "ad_generate: exit head");
+        issued = h; issued_tok = tok_src; embed_taken = false;
+        return AD_OK;
+    }
+
+    int embed(int32_t token, int32_t r) override {
+        if (issued.kind == AHEAD_TOKEN && !embed_taken && issued.row0 == r && *(const volatile int32_t *)issued_tok == token) {
+            embed_taken = true;           // the row already holds this token's embedding
+            return AD_OK;
+        }
+        issued.kind = AHEAD_NONE;
+        return ad_embed(m, &token, 1, row(r), stream);
+    }
+    int exit_head(int32_t layer, int32_t r, int32_t, int32_t *token, float *conf) override {
+        int rc = ::exit_head(m, layer, row(r), m->pin, m->pin_conf, stream, done_flag(), next_seq());
+        if (rc == AD_OK) rc = issue_ahead(m->pin);
+        if (rc != AD_OK) return rc;
+        if ((rc = wait_done("ad_generate: exit head"))) return rc;
         if ((rc = fused_health(m, stream))) return rc;
         *token = m->pin[0];
         *conf = m->pin_conf[0];
@@ -779,9 +892,10 @@ struct GpuBackend : Backend {
         return AD_OK;
     }
     int verify(int32_t n, int32_t, const int32_t *draft, int32_t *n_accept, int32_t *next, int32_t *row_argmax) override {
-        int rc = ad_verify(m, row(0), draft, n, m->pin + 8, m->pin + 9, m->pin + 16, stream);
+        int rc = ::verify(m, row(0), draft, n, m->pin + 8, m->pin + 9, m->pin + 16, stream, done_flag(), next_seq());
+        if (rc == AD_OK) rc = issue_ahead(m->pin + 9);
         if (rc != AD_OK) return rc;
-        if ((rc = stream_sync(stream))) return hip_fail(rc, "ad_generate: verify");
+        if ((rc = wait_done("ad_generate: verify"))) return rc;
         if ((rc = fused_health(m, stream))) return rc;
         *n_accept = m->pin[8];
         *next = m->pin[9];
@@ -793,6 +907,7 @@ struct GpuBackend : Backend {
     // Eq. 1 with a sampled token: the head's logits stay in the draft slot of this row until the verification
     int sample_head(int32_t layer, int32_t r, int32_t, float temperature, float u, int32_t *token, float *prob) override {
         float *z = m->draft_logits + (size_t)r * m->cfg.vocab;
+        hint.kind = issued.kind = AHEAD_NONE;
         int rc = ad_head_logits(m, layer, row(r), 1, z, stream);
         if (rc == AD_OK) rc = ad_sample_logits(m, z, temperature, u, m->pin, m->pin_conf, stream);
         if (rc != AD_OK) return rc;
@@ -806,6 +921,7 @@ struct GpuBackend : Backend {
     }
     int verify_sampled(int32_t n, int32_t, const int32_t *draft, float temperature, const float *u_accept, const float *u_resample,
                        float u_final, int32_t *n_accept, int32_t *next, float *ratio) override {
+        hint.kind = issued.kind = AHEAD_NONE;
         int rc = ad_head_logits(m, m->cfg.n_layers, row(0), n, m->final_logits, stream);
         if (rc == AD_OK)
             rc = ad_verify_sampled(m, m->final_logits, m->draft_logits, draft, n, temperature, u_accept, u_resample, u_final, m->pin + 8,

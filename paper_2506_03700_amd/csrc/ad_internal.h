@@ -85,6 +85,10 @@ struct GemmArgs {
     int32_t *n_accept_out, *next_out;   // verify outputs or null
     int32_t draft[8];
     int verify;
+    // optional: host-visible word that the head's second kernel sets to done_seq, at system scope, after its results
+    // are written; a host thread that polls it learns the outcome without waiting for the stream to drain
+    int32_t *done_flag;
+    int32_t done_seq;
 };
 
 static_assert(offsetof(GemmArgs, mode) == 64, "GemmArgs: the first line holds the fields needed first");
@@ -149,6 +153,9 @@ inline unsigned fused_barriers(int n_layers) { return 6u * (unsigned)n_layers - 
 
 struct EmbedArgs {
     const void *table; int elem; int d; int m; int32_t tok[8]; float *out;
+    // null, or where the kernel reads the m token ids instead of tok[] (device-visible memory that an earlier kernel
+    // on the stream wrote); ids outside [0, vocab) are clamped
+    const int32_t *tok_src; int vocab;
 };
 
 // Sampled decoding (Sec. 2.2).  inv_t = 1 / temperature; u, u_accept, u_resample, u_final are uniform draws in [0, 1).

@@ -61,7 +61,9 @@ __global__ void k_zero16(u32x4 *dst, size_t n16) {
 __global__ void k_embed(EmbedArgs a) {
     for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < a.m * a.d; idx += gridDim.x * blockDim.x) {
         const int r = idx / a.d, c = idx % a.d;
-        a.out[idx] = load_w(a.table, a.elem, (size_t)a.tok[r] * a.d + c);
+        int t = a.tok[r];
+        if (a.tok_src) t = min(max(a.tok_src[r], 0), a.vocab - 1);
+        a.out[idx] = load_w(a.table, a.elem, (size_t)t * a.d + c);
     }
 }
 
@@ -138,7 +140,8 @@ int event_elapsed_ms(void *start, void *stop, float *ms) { return (int)hipEventE
 int stream_sync_event(void *ev) { return (int)hipEventSynchronize((hipEvent_t)ev); }
 void *pinned_alloc(size_t bytes) {
     void *p = nullptr;
-    if (hipHostMalloc(&p, bytes, hipHostMallocDefault) != hipSuccess) return nullptr;
+    // coherent: a kernel's system-scope stores reach the host while the kernel (and the stream) is still running
+    if (hipHostMalloc(&p, bytes, hipHostMallocCoherent) != hipSuccess) return nullptr;
     return p;
 }
 void pinned_free(void *p) { if (p) (void)hipHostFree(p); }

@@ -22,6 +22,9 @@
 //    compared with gamma is that token's; the verification applies Eq. 2 in its general form.  The uniform
 //    draws come from the caller's table, one row per position and one column per use (exit head i, final
 //    layer, acceptance, replacement), so that a position that samples at several heads uses fresh draws;
+//  * before a greedy head evaluation the backend is told what follows under the expected outcome (Backend::expect),
+//    so that it can issue the start of that work before the outcome is known; the schedule itself, and every
+//    result, is the same with and without it;
 //  * ablation switches: head_mask switches exit heads off (one bit left = the fixed-layer variant); no_verify keeps
 //    every early prediction unchecked and lets the last layer produce only the next token from the newest row.
 #include "ad_sched.h"
@@ -72,6 +75,8 @@ int run_algorithm1(Backend &be, const SchedConfig &cfg, const ad_gen_params &gp,
     int32_t cur = prompt[n_prompt - 1], pos = n_prompt - 1;
     int32_t n_emitted = 0;      // tokens in out_tokens, verified or not
     bool finished = false;
+    const bool issue_ahead = !gp.no_issue_ahead && !sampled && !gp.no_verify;
+    bool last_take[AD_MAX_EXIT] = {};
 
     while (!finished) {
         open_pos[n_open] = pos;
@@ -109,15 +114,27 @@ int run_algorithm1(Backend &be, const SchedConfig &cfg, const ad_gen_params &gp,
             if (head_due(l)) {
                 int32_t tok = -1;
                 float conf = 0.0f;
-                if (sampled)
+                if (sampled) {
                     rc = be.sample_head(l, n_open - 1, pos, gp.temperature, gp.uniforms[(size_t)pos * ucols + slot], &tok, &conf);
-                else
+                } else {
+                    if (issue_ahead) {
+                        // expected outcome: the forced one, else what this head decided last time
+                        if (gp.forced_exit || last_take[slot]) {
+                            be.expect(Ahead{AHEAD_TOKEN, 1, n_open, 1});
+                        } else {
+                            int32_t f2 = n_open - 1;       // the rows of layer l + 1: those at depth l
+                            while (f2 > 0 && open_depth[f2 - 1] == l) --f2;
+                            be.expect(Ahead{AHEAD_LAYER, l + 1, f2, n_open - f2});
+                        }
+                    }
                     rc = be.exit_head(l, n_open - 1, pos, &tok, &conf);
+                }
                 if (rc != AD_OK) return rc;
                 ++st.head_evals;
                 bool take = gp.forced_exit ? true : (conf > gp.gamma);
                 if (gp.scripted_draft && gp.scripted_draft[pos] >= 0) tok = gp.scripted_draft[pos];
                 if (tok == gp.eos_id) take = false;
+                last_take[slot] = take;
                 tr.add(AD_EV_HEAD, l, pos, 1, tok, take ? 1 : 0, conf);
                 if (take) {
                     out_tokens[n_emitted++] = tok;
@@ -146,6 +163,8 @@ int run_algorithm1(Backend &be, const SchedConfig &cfg, const ad_gen_params &gp,
             tr.add(AD_EV_VERIFY, L, open_pos[0], n_open, next, n_accept, 0.0f);
             for (int32_t k = 0; k < n_open; ++k) tr.add(AD_EV_VERIFY_ROW, L, open_pos[k], 1, k == n_open - 1 ? next : -1, -1, 0.0f);
         } else if (!sampled) {
+            // whatever the verification keeps, its next token starts in row 0 (unless it is certainly the last one)
+            if (issue_ahead && n_emitted - n_draft + 1 < gp.max_new) be.expect(Ahead{AHEAD_TOKEN, 1, 0, 1});
             if ((rc = be.verify(n_open, open_pos[0], open_tok + 1, &n_accept, &next, row_arg)) != AD_OK) return rc;
             ++st.verifies;
             tr.add(AD_EV_VERIFY, L, open_pos[0], n_open, next, n_accept, 0.0f);

@@ -9,8 +9,22 @@
 
 namespace ad {
 
+// What the schedule does right after the head evaluation it is about to ask for, if that evaluation turns out as
+// the schedule expects:
+//   AHEAD_LAYER: rows [row0, row0 + m) go on through layer `layer` (no early prediction is taken);
+//   AHEAD_TOKEN: the token the evaluation produces is embedded into row `row0` and passes layer 1 alone (m = 1):
+//                an early prediction is taken, or the evaluation is the verification.
+// A backend may issue the part of that work that changes no state the other outcome needs (the embedding into a
+// free row, the QKV projection into its workspace) behind the head's kernels, so that it runs while the host
+// still waits for the outcome and decides; when the next calls ask for exactly that work it is not issued again,
+// otherwise it is dropped.  Results are the same either way.
+enum { AHEAD_NONE = 0, AHEAD_LAYER = 1, AHEAD_TOKEN = 2 };
+struct Ahead { int32_t kind, layer, row0, m; };
+
 struct Backend {
     virtual ~Backend() {}
+    // hint for the next exit_head / verify call only
+    virtual void expect(const Ahead &) {}
     // Full-depth pass over prompt tokens [0, n): "KV cache <- LM(x)".
     virtual int prefill(const int32_t *tokens, int32_t n) = 0;
     // hidden row `row` <- embedding of token

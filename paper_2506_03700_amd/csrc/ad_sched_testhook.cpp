@@ -13,7 +13,21 @@ namespace {
 // the calls of Backend::layer_steps of the last run: (first layer, layers, first row, rows, first position)
 std::vector<int32_t> g_stretches;
 
+// the hints of Backend::expect of the last run: (kind, layer, first row, rows, 1 if the calls that followed the
+// head evaluation asked for exactly the hinted work, else 0)
+std::vector<int32_t> g_hints;
+
 struct Scripted : ad::Backend {
+    ad::Ahead hint{ad::AHEAD_NONE, 0, 0, 0}, watch{ad::AHEAD_NONE, 0, 0, 0};
+    bool watch_embedded = false;
+    void expect(const ad::Ahead &a) override { hint = a; }
+    void head_called() { watch = hint; hint.kind = ad::AHEAD_NONE; watch_embedded = false; }
+    void settle(bool hit) {
+        const int32_t rec[5] = {watch.kind, watch.layer, watch.row0, watch.m, hit ? 1 : 0};
+        g_hints.insert(g_hints.end(), rec, rec + 5);
+        watch.kind = ad::AHEAD_NONE;
+    }
+
     int32_t n_layers, n_exit, max_pos;
     const int32_t *exit_layers;
     // table mode: head_tok/head_conf are [max_pos][n_exit] and final_tok is [max_pos], indexed by position.
@@ -33,7 +47,11 @@ struct Scripted : ad::Backend {
         for (int l = 0; l < n_layers; ++l) len[l] = n;
         return AD_OK;
     }
-    int embed(int32_t, int32_t) override { return AD_OK; }
+    int embed(int32_t, int32_t row) override {
+        if (watch.kind == ad::AHEAD_TOKEN && !watch_embedded && row == watch.row0) watch_embedded = true;
+        else if (watch.kind != ad::AHEAD_NONE) settle(false);
+        return AD_OK;
+    }
     int layer_step(int32_t layer, int32_t row0, int32_t m, int32_t pos0) override {
         if (layer < 1 || layer > n_layers || m < 1 || row0 + m > AD_M_MAX) return AD_ERANGE;
         if (pos0 != len[layer - 1]) return AD_ESTATE;                 // must continue the layer's cache
@@ -46,9 +64,12 @@ struct Scripted : ad::Backend {
     int layer_steps(int32_t first_layer, int32_t count, int32_t row0, int32_t m, int32_t pos0) override {
         const int32_t rec[5] = {first_layer, count, row0, m, pos0};
         g_stretches.insert(g_stretches.end(), rec, rec + 5);
+        if (watch.kind != ad::AHEAD_NONE)
+            settle(first_layer == watch.layer && row0 == watch.row0 && m == watch.m && (watch.kind == ad::AHEAD_LAYER || watch_embedded));
         return ad::Backend::layer_steps(first_layer, count, row0, m, pos0);
     }
     int exit_head(int32_t layer, int32_t row, int32_t pos, int32_t *token, float *conf) override {
+        head_called();
         if (layer == n_layers && !seq_mode) {
             // the final head on one row (a run without verification asks for it): the scripted final token
             if (row_pos[row] != pos || len[n_layers - 1] != pos + 1) return AD_ESTATE;
@@ -71,6 +92,7 @@ struct Scripted : ad::Backend {
         return AD_OK;
     }
     int verify(int32_t m, int32_t pos0, const int32_t *draft, int32_t *n_accept, int32_t *next, int32_t *row_argmax) override {
+        head_called();
         for (int l = 1; l < n_layers; ++l)
             if (len[l] != len[0]) return AD_ESTATE;                   // every layer must have caught up
         if (len[0] != pos0 + m) return AD_ESTATE;
@@ -128,6 +150,7 @@ extern "C" int ad_sched_test_run(int32_t n_layers, int32_t n_exit, const int32_t
                                                       draws the backend saw last in a sampled run */) {
     if (n_layers < 1 || n_layers > 256 || n_exit < 0 || n_exit > AD_MAX_EXIT) return AD_EINVAL;
     g_stretches.clear();
+    g_hints.clear();
     Scripted be;
     be.n_layers = n_layers; be.n_exit = n_exit; be.max_pos = max_pos; be.exit_layers = exit_layers;
     be.head_tok = head_tok; be.head_conf = head_conf; be.final_tok = final_tok;
@@ -138,6 +161,7 @@ extern "C" int ad_sched_test_run(int32_t n_layers, int32_t n_exit, const int32_t
     sc.n_layers = n_layers; sc.n_exit = n_exit; sc.m_max = m_max;
     for (int i = 0; i < n_exit; ++i) sc.exit_layers[i] = exit_layers[i];
     const int rc = ad::run_algorithm1(be, sc, *gp, prompt, n_prompt, out_tokens, n_out, stats, events, max_events, n_events);
+    if (be.watch.kind != ad::AHEAD_NONE) be.settle(false);      // hinted work that the end of the run left unasked
     if (last_draws) {
         last_draws[0] = be.last_u_head; last_draws[1] = be.last_u_final; last_draws[2] = be.last_u_accept0; last_draws[3] = be.last_u_resample0;
     }
@@ -151,5 +175,14 @@ extern "C" int64_t ad_sched_test_stretches(int32_t *out, int64_t max_records) {
     const int64_t n = (int64_t)(g_stretches.size() / 5);
     for (int64_t i = 0; i < n && i < max_records; ++i)
         for (int k = 0; k < 5; ++k) out[i * 5 + k] = g_stretches[(size_t)i * 5 + k];
+    return n;
+}
+
+// The hints the scheduler gave before the head evaluations of the last run, in order: records of 5 int32 (kind,
+// layer, first row, rows, 1 if the calls after the evaluation asked for exactly that work).
+extern "C" int64_t ad_sched_test_hints(int32_t *out, int64_t max_records) {
+    const int64_t n = (int64_t)(g_hints.size() / 5);
+    for (int64_t i = 0; i < n && i < max_records; ++i)
+        for (int k = 0; k < 5; ++k) out[i * 5 + k] = g_hints[(size_t)i * 5 + k];
     return n;
 }

@@ -428,6 +428,49 @@ def test_runs_are_reproducible(ad):
     g.close()
 
 
+@pytest.mark.parametrize("shape", [UNTIED.with_(name="tiny-untied-bf16", dtype=synth.BF16), synth.MINI8B], ids=lambda s: s.name)
+def test_work_issued_ahead_of_a_head_outcome_changes_nothing(ad, shape):
+    """The first kernels of the expected continuation are issued behind a head evaluation before its outcome is
+    known; with that switched off the run must be the same event for event, confidences bit for bit and the
+    caches bit for bit: natural exits (expectation sometimes wrong), a forced schedule with scripted wrong drafts
+    (rejections, roll-backs), and an end-of-sequence token (an early prediction that is not taken)."""
+    from compare_runs import events
+    w = synth.make_weights(shape, seed=0, with_T=(shape.name.startswith("tiny")), T_std=0.03)
+    max_pos = 160
+    g = ad.Model(shape, w, max_pos=max_pos)
+    p = synth.make_prompt(shape, 1)
+    forced = synth.make_forced_schedule(shape, 3, max_pos, probs=[0.25] * len(shape.exit_layers))
+    script = np.full(max_pos, -1, dtype=np.int32)
+    script[[len(p) + 3, len(p) + 11, len(p) + 30, len(p) + 41]] = [1, 2, 3, 4]
+    # a threshold that about half of the head evaluations pass: the median confidence of a run without exits
+    _, _, e = g.ad_generate(p, 96, 1.0, 5)
+    natural = float(np.median(e[e["kind"] == ad.EV_HEAD]["conf"]))
+    _, _, e = g.ad_generate(p, 96, natural, 5)
+    taken = e[(e["kind"] == ad.EV_HEAD) & (e["flag"] == 1)]
+    assert len(taken) > 8
+    eos = int(taken[len(taken) // 2]["token"])          # ... and a token that an early prediction produces midway
+    for kw in (dict(gamma=natural), dict(gamma=0.9, forced_exit=forced, scripted_draft=script), dict(gamma=natural, eos_id=eos)):
+        gamma = kw.pop("gamma")
+        print(f"case {shape.name} {sorted(kw)}", flush=True)
+        t1, s1, e1 = g.ad_generate(p, 96, gamma, 5, **kw)
+        lens1 = g.kv_lens()
+        kv1 = [gpu_kv(g, l, min(lens1)) for l in (1, shape.n_layers)]
+        t0, s0, e0 = g.ad_generate(p, 96, gamma, 5, no_issue_ahead=True, **kw)
+        assert g.kv_lens() == lens1
+        kv0 = [gpu_kv(g, l, min(lens1)) for l in (1, shape.n_layers)]
+        np.testing.assert_array_equal(t1, t0)
+        assert s1 == s0 and events(e1) == events(e0)
+        np.testing.assert_array_equal(e1["conf"], e0["conf"])
+        for a, b in zip(kv1, kv0):
+            for x, y in zip(a, b):
+                np.testing.assert_array_equal(x, y)
+        if not kw:
+            assert s1["early_preds"] > 8 and s1["head_evals"] > s1["early_preds"] + 8      # both outcomes occurred
+        if "eos_id" in kw:
+            assert t1[-1] == eos or len(t1) == 96
+    g.close()
+
+
 @pytest.mark.parametrize("shape", [UNTIED, UNTIED.with_(name="tiny-untied-bf16", dtype=synth.BF16)], ids=lambda s: s.name)
 def test_ablation_switches_match_oracle(ad, shape):
     """The variants of Table 3 that are switches of the schedule: a single exit head (head_mask) and no

@@ -296,6 +296,62 @@ def test_ablation_switches_in_the_scheduler():
     assert all(int(r["flag"]) == -1 for r in rows)
 
 
+def test_hints_of_the_expected_continuation_match_what_the_schedule_then_asks_for():
+    """Before a greedy head evaluation the scheduler tells the backend what it will ask for next if the evaluation
+    turns out as expected (the forced outcome, else the head's last decision).  Whenever the outcome is the
+    expected one, the calls that follow must be exactly the hinted work; the hints never change the run."""
+    rng = np.random.default_rng(5)
+    n_pos, L, exits = 400, 12, [3, 6, 9]
+    final_tok = rng.integers(0, 50, n_pos).astype(np.int32)
+    head_tok = np.repeat(final_tok[:, None], 3, axis=1)
+    wrong = rng.random((n_pos, 3)) < 0.15
+    head_tok[wrong] = 77                                            # some drafts get rejected
+    head_conf = rng.random((n_pos, 3)).astype(np.float32)           # about one head in three fires at gamma 0.65
+    prompt = [1, 2, 3]
+    rc, out, st, ev = ad.sched_test_run(L, exits, 8, head_tok, head_conf, final_tok, prompt, 200, 0.65, 5)
+    assert rc == ad.AD_OK and st["early_preds"] > 40 and st["rejections"] > 5
+    hints = ad.sched_test_hints()
+    evs = [e for e in _events(ev) if e[0] in (ad.EV_HEAD, ad.EV_VERIFY)]
+    # one per head evaluation and per verification, except a verification that certainly ends the run
+    assert len(hints) in (len(evs) - 1, len(evs))
+    last = {}
+    n_hit = 0
+    for i, (h, e) in enumerate(zip(hints, evs)):
+        kind, layer, row0, m, hit = (int(v) for v in h)
+        if e[0] == ad.EV_VERIFY:
+            assert (kind, layer, row0, m) == (2, 1, 0, 1)
+            assert hit == (1 if i + 1 < len(evs) else 0)            # the next token starts in row 0, unless the run is over
+        else:
+            take, expected = bool(e[5]), last.get(e[1], False)
+            assert kind == (2 if expected else 1)
+            if kind == 1:
+                assert layer == e[1] + 1
+            assert hit == (1 if take == expected else 0), (i, h, e)
+            last[e[1]] = take
+        n_hit += hit
+    assert 0.4 * len(hints) < n_hit < len(hints)
+    # the run is the same without hints
+    rc, out2, st2, ev2 = ad.sched_test_run(L, exits, 8, head_tok, head_conf, final_tok, prompt, 200, 0.65, 5, no_issue_ahead=True)
+    assert rc == ad.AD_OK and len(ad.sched_test_hints()) == 0
+    np.testing.assert_array_equal(out, out2)
+    assert st == st2 and _events(ev) == _events(ev2)
+    # a forced schedule is known in advance: every hint is right (the last verification's aside)
+    forced = np.zeros(n_pos, dtype=np.uint8)
+    forced[rng.random(n_pos) < 0.5] = 6
+    forced[rng.random(n_pos) < 0.2] = 9
+    rc, out, st, ev = ad.sched_test_run(L, exits, 8, head_tok, head_conf, final_tok, prompt, 120, 0.9, 5, forced_exit=forced)
+    hints = ad.sched_test_hints()
+    n_dec = st["head_evals"] + st["verifies"]
+    assert rc == ad.AD_OK and st["early_preds"] > 30 and len(hints) in (n_dec - 1, n_dec)
+    assert hints[:n_dec - 1, 4].all() and not hints[n_dec - 1:, 4].any()
+    # sampled decoding and the run without verification give no hints
+    u = rng.random((n_pos, 6)).astype(np.float32)
+    rc, *_ = ad.sched_test_run(L, exits, 8, head_tok, head_conf, final_tok, prompt, 40, 0.65, 5, temperature=1.0, uniforms=u)
+    assert rc == ad.AD_OK and len(ad.sched_test_hints()) == 0
+    rc, *_ = ad.sched_test_run(L, exits, 8, head_tok, head_conf, final_tok, prompt, 40, 0.65, 5, no_verify=True)
+    assert rc == ad.AD_OK and len(ad.sched_test_hints()) == 0
+
+
 def test_a_matrix_of_4_gib_or_more_is_refused():
     """The kernels address a packed weight matrix with a 32-bit byte offset: a configuration whose LM head (or any
     other matrix) would reach 4 GiB in the library's layout is an invalid configuration, not a silent wrap."""
