@@ -60,6 +60,7 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-micro", action="store_true")
     ap.add_argument("--skip-forced", action="store_true")
+    ap.add_argument("--skip-decision", action="store_true", help="skip the measurement of the host's cost per exit decision")
     ap.add_argument("--gamma-sweep", action="store_true", help="also run the threshold sweep and the ablation switches")
     ap.add_argument("--layer-mode", default="kernels", choices=["fused", "kernels"],
                     help="layer step as one kernel per phase (default) or as one persistent kernel")
@@ -185,6 +186,46 @@ def main():
                 "achieved_GBps": round(lst["bytes_algorithmic"] / ldt / 1e9, 1),
                 "frac_of_peak": round(lst["bytes_algorithmic"] / ldt / 1e9 / HBM_PEAK_GBS, 4)}
         log(f"[bench] long generation: {long}")
+
+    # What the host's part in an exit decision costs: a token with a head evaluation after each exit layer and the
+    # verification (4 per token on the 8B shape) against a token with the verification only (cap 0: no exit head is
+    # evaluated), per extra evaluation, minus what an evaluation takes when evaluations are queued back to back on
+    # the stream with no host in between.  Both with and without the issue-ahead of the expected continuation.
+    decision = None
+    if not args.skip_decision and shape.exit_layers and not main_is_long:
+        n_dc = min(gen_len, 384)
+
+        def us_per_token(cap_, ahead):
+            g.ad_generate(prompt, 32, shape.gamma, cap_, want_events=False, no_issue_ahead=not ahead)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            _, st, _ = g.ad_generate(prompt, n_dc, shape.gamma, cap_, want_events=False, no_issue_ahead=not ahead)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / n_dc * 1e6, st
+
+        hrow = torch.from_numpy(synth.make_hidden(shape, 7, 1)).to("cuda")
+        for _ in range(20):
+            g.ad_exit_head(shape.exit_layers[0], hrow, sync=False)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(200):
+            g.ad_exit_head(shape.exit_layers[0], hrow, sync=False)
+        e1.record()
+        torch.cuda.synchronize()
+        head_us = e0.elapsed_time(e1) * 1e3 / 200
+        decision = {"tokens": n_dc, "head_evaluation_back_to_back_us": round(head_us, 2)}
+        for ahead in (True, False):
+            t_all, st_all = us_per_token(cap, ahead)
+            t_one, st_one = us_per_token(0, ahead)
+            extra = (st_all["head_evals"] + st_all["verifies"] - st_one["verifies"]) / n_dc      # evaluations per token beyond the verification
+            per_eval = (t_all - t_one) / extra
+            decision["issue_ahead" if ahead else "no_issue_ahead"] = {
+                "us_per_token": round(t_all, 1), "us_per_token_verification_only": round(t_one, 1),
+                "head_evaluations_per_token": round(extra + 1, 3), "us_per_extra_head_evaluation": round(per_eval, 2),
+                "host_decision_us": round(per_eval - head_us, 2),
+                "share_of_token": round((extra + 1) * (per_eval - head_us) / t_all, 5)}
+        log(f"[bench] host decision cost: {decision}")
 
     sweep = None
     if args.gamma_sweep and shape.exit_layers:
@@ -326,7 +367,22 @@ def main():
             log(f"[bench] layer step m={m}: {us:.2f} us (median of batches {us_med:.2f}), {gbs:.1f} GB/s ({gbs / HBM_PEAK_GBS:.1%} of peak)"
                 + (f"; {micro[str(m)]['us_per_layer_in_stretches_of_8']:.2f} us per layer in stretches of 8" if L % 8 == 0 else ""))
             del H, Hw
-        micro = {"ctx": ctx_micro, "calls_per_m": micro_calls, "distinct_weight_copies": L,
+        # what the machine gives kernels that only read a layer step's bytes: as one launch, and as one launch per phase
+        probe = {}
+        for nm, mode in (("one_kernel", binding.AD_PROBE_ONE_KERNEL), ("one_kernel_per_phase", binding.AD_PROBE_PER_PHASE)):
+            def pr(i, mode=mode):
+                g.ad_probe_stream(i % L + 1, ctx_micro, mode)
+            for i in range(64):
+                pr(i)
+            torch.cuda.synchronize()
+            pus, _ = timed_batches(pr, micro_calls)
+            probe[nm + "_us"] = round(pus, 2)
+            probe[nm + "_frac"] = round(layer_step_bytes(shape, ctx_micro, 0) / (pus * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+        probe["note"] = ("kernels that read a layer's packed weights and its cached K/V rows and drop them (ad_probe_stream), rotating over "
+                         "the layers like the calls above: the bytes alone, and the bytes with a kernel boundary between the five "
+                         "phases that read memory; no arithmetic, no activations, no dependence through data")
+        log(f"[bench] stream probe: {probe}")
+        micro = {"ctx": ctx_micro, "calls_per_m": micro_calls, "distinct_weight_copies": L, "stream_probe": probe,
                  "rows": "N(0,1), drawn afresh for every call from a pre-generated device buffer (the first 10 calls of each m are the "
                          "rows of the parity test)",
                  "algorithmic_bytes_m1": layer_step_bytes(shape, ctx_micro, 1), "by_m": micro}
@@ -407,7 +463,8 @@ def main():
                                   f"cap {cap}, prompt {prompt_len}, generate {gen_len}, batch 1, random-init N(0,0.02)"
                                   + (", exits forced from a seeded 0.2/0.2/0.2 schedule, verification on" if main_is_long else ""),
                       "global_batch": 1, "seq_len": prompt_len + gen_len},
-           "roofline": roofline, "end_to_end": e2e, "forced": forced, "long": long, "layer_step": micro, "cpu_baseline": cpu}
+           "roofline": roofline, "end_to_end": e2e, "forced": forced, "long": long, "decision": decision, "layer_step": micro,
+           "cpu_baseline": cpu}
     if sweep is not None:
         out["gamma_sweep"] = sweep
     print(json.dumps(out), flush=True)

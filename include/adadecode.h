@@ -261,6 +261,16 @@ ad_status ad_profile_stop(ad_model *, int64_t *n_launches, int64_t *n_samples, d
  * through the pointers (either may be NULL); bytes is the size of the buffer. */
 ad_status ad_layer_trace(ad_model *, void *ticks, size_t bytes, int32_t *n_workgroups, int32_t *n_stamps);
 
+/* Measurement aid, no part of the method: kernels that only read the bytes one layer step has to read (layer
+ * `layer`'s packed weights and 2 * n_kv_heads * head_dim * ctx cache elements of that layer) and drop them, on the
+ * same grid as the layer step's kernels.  AD_PROBE_ONE_KERNEL: one launch reads all of it: the time the machine
+ * needs for the bytes alone.  AD_PROBE_PER_PHASE: five launches queued behind each other, one per phase of the
+ * layer step that reads from memory (QKV weights; cache rows; Wo; gate/up; down weights), each reading that phase's
+ * bytes: the same bytes with the phases' dependence kept (a kernel boundary between them), nothing else.  The
+ * caller times the calls (events on `stream`).  ctx in 0..max_pos. */
+enum { AD_PROBE_ONE_KERNEL = 0, AD_PROBE_PER_PHASE = 1 };
+ad_status ad_probe_stream(const ad_model *, const ad_kv *, int32_t layer, int32_t ctx, int32_t mode, void *stream);
+
 const char *ad_last_error(void);   /* thread-local, never NULL */
 const char *ad_version(void);
 

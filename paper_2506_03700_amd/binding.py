@@ -22,11 +22,13 @@ AD_MAX_EXIT, AD_M_MAX = 8, 8
 EV_LAYER_STEP, EV_HEAD, EV_VERIFY, EV_VERIFY_ROW = 1, 2, 3, 4
 AD_LAYER_KERNELS, AD_LAYER_FUSED = 0, 1
 AD_PROF_GEMM, AD_PROF_LAYER = 0, 1
+AD_PROBE_ONE_KERNEL, AD_PROBE_PER_PHASE = 0, 1
 
 EXPORTS = ["ad_workspace_bytes", "ad_model_create", "ad_model_destroy", "ad_kv_bytes", "ad_kv_create", "ad_kv_destroy",
            "ad_kv_len", "ad_kv_set_len", "ad_kv_truncate", "ad_embed", "ad_layer_step", "ad_layer_steps", "ad_set_layer_mode", "ad_exit_head", "ad_verify",
            "ad_verify_static",
-           "ad_head_logits", "ad_sample_logits", "ad_verify_sampled", "ad_generate", "ad_layer_trace", "ad_profile_start", "ad_profile_stop", "ad_last_error", "ad_version"]
+           "ad_head_logits", "ad_sample_logits", "ad_verify_sampled", "ad_generate", "ad_layer_trace", "ad_profile_start", "ad_profile_stop", "ad_probe_stream",
+           "ad_last_error", "ad_version"]
 
 
 class Config(C.Structure):
@@ -108,6 +110,7 @@ def lib() -> C.CDLL:
         L.ad_set_layer_mode.argtypes = [P, i32]
         L.ad_layer_trace.argtypes = [P, P, C.c_size_t, P, P]
         L.ad_profile_stop.argtypes = [P, P, P, P, P, P]
+        L.ad_probe_stream.argtypes = [P, P, i32, i32, i32, P]
         L.ad_last_error.restype = C.c_char_p
         L.ad_version.restype = C.c_char_p
         for n in EXPORTS:
@@ -274,12 +277,15 @@ class Model:
         _check(self.L.ad_layer_steps(self.model, self.kv, first_layer, n_layers, C.c_void_p(hidden.data_ptr()), p.ctypes.data, p.size,
                                      _stream_ptr(torch)))
 
-    def ad_exit_head(self, layer: int, hidden_row):
+    def ad_exit_head(self, layer: int, hidden_row, sync: bool = True):
+        """sync=False: only enqueues the evaluation (for timing launches back to back) and returns None."""
         torch = self.torch
         assert hidden_row.dtype == torch.float32 and hidden_row.is_contiguous() and hidden_row.numel() == self.shape.d_model
         out = self._pinned
         _check(self.L.ad_exit_head(self.model, layer, C.c_void_p(hidden_row.data_ptr()), C.c_void_p(out.data_ptr()),
                                    C.c_void_p(out.data_ptr() + 4), _stream_ptr(torch)))
+        if not sync:
+            return None
         torch.cuda.current_stream().synchronize()
         return int(out[0]), float(out[1:2].view(torch.float32)[0])
 
@@ -386,6 +392,10 @@ class Model:
         self._trace = torch.zeros((nwg.value, ns.value), dtype=torch.int64, device="cuda:0")
         _check(self.L.ad_layer_trace(self.model, self._trace.data_ptr(), self._trace.numel() * 8, None, None))
         return self._trace
+
+    def ad_probe_stream(self, layer: int, ctx: int, mode: int) -> None:
+        """Enqueues kernels that only read what one step of `layer` at context `ctx` must read (see the header)."""
+        _check(self.L.ad_probe_stream(self.model, self.kv, layer, ctx, mode, _stream_ptr(self.torch)))
 
     def ad_profile_start(self, kind: int = AD_PROF_GEMM, period: int = 1, max_samples: int = 65536) -> None:
         _check(self.L.ad_profile_start(self.model, kind, period, max_samples))

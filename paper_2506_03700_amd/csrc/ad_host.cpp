@@ -738,6 +738,34 @@ ad_status ad_set_layer_mode(ad_model *m, int32_t mode) {
     return AD_OK;
 }
 
+ad_status ad_probe_stream(const ad_model *m, const ad_kv *kv, int32_t layer, int32_t ctx, int32_t mode, void *stream) {
+    if (!m || !kv) return (ad_status)fail(AD_EINVAL, "ad_probe_stream: null argument");
+    if (kv->model != m) return (ad_status)fail(AD_EINVAL, "ad_probe_stream: cache belongs to another model");
+    if (layer < 1 || layer > m->cfg.n_layers) return (ad_status)fail(AD_ERANGE, "ad_probe_stream: layer %d outside 1..%d", layer, m->cfg.n_layers);
+    if (ctx < 0 || ctx > kv->max_pos) return (ad_status)fail(AD_ERANGE, "ad_probe_stream: ctx %d outside 0..%d", ctx, kv->max_pos);
+    if (mode != AD_PROBE_ONE_KERNEL && mode != AD_PROBE_PER_PHASE) return (ad_status)fail(AD_EINVAL, "ad_probe_stream: unknown mode %d", mode);
+    const Layout &L = m->lay;
+    const LayerPacked &lp = m->layers[layer - 1];
+    const char *cache = (const char *)kv->storage + (size_t)(layer - 1) * kv->layer_bytes;
+    // as many bytes of the layer's cache as ctx positions of K and V hold (the cache is position-major per head;
+    // the probe reads the same number of bytes from the start of the layer's block)
+    size_t kv_bytes = 2 * (size_t)m->cfg.n_kv_heads * m->cfg.head_dim * (m->cfg.dtype == AD_F32 ? 4 : 2) * (size_t)ctx;
+    kv_bytes = (kv_bytes < kv->layer_bytes ? kv_bytes : kv->layer_bytes) & ~(size_t)15;
+    unsigned *sink = m->bar_ctr + 24;       // a word of the model's scratch that nothing reads; the probe never writes it
+    int rc;
+    if (mode == AD_PROBE_ONE_KERNEL) {
+        // the four matrices of a layer are adjacent in the packed model
+        rc = launch_probe_stream(lp.wqkv, L.sz_wqkv + L.sz_wo + L.sz_wgu + L.sz_wd, cache, kv_bytes, sink, m->n_wg, stream);
+    } else {
+        rc = launch_probe_stream(lp.wqkv, L.sz_wqkv, nullptr, 0, sink, m->n_wg, stream);
+        if (!rc && kv_bytes) rc = launch_probe_stream(cache, kv_bytes, nullptr, 0, sink, m->n_wg, stream);
+        if (!rc) rc = launch_probe_stream(lp.wo, L.sz_wo, nullptr, 0, sink, m->n_wg, stream);
+        if (!rc) rc = launch_probe_stream(lp.wgu, L.sz_wgu, nullptr, 0, sink, m->n_wg, stream);
+        if (!rc) rc = launch_probe_stream(lp.wd, L.sz_wd, nullptr, 0, sink, m->n_wg, stream);
+    }
+    return rc ? (ad_status)hip_fail(rc, "ad_probe_stream") : AD_OK;
+}
+
 ad_status ad_layer_trace(ad_model *m, void *ticks, size_t bytes, int32_t *n_workgroups, int32_t *n_stamps) {
     if (!m) return (ad_status)fail(AD_EINVAL, "ad_layer_trace: null model");
     if (n_workgroups) *n_workgroups = m->n_wg;

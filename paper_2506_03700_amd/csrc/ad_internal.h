@@ -184,6 +184,8 @@ struct LaunchCtx { void *stream; int n_wg; };
 // mode 0: W [N, K] -> packed.  mode 1: gate (src) and up (src2), each [N, K], interleaved 8 rows at a time.
 int launch_pack_weights(const void *src, const void *src2, int src_elem, int64_t N, int64_t K, int mode, void *dst,
                         void *stream);
+// reads the two ranges (bytes, multiples of 16) on n_wg workgroups and drops the data; sink: any device word
+int launch_probe_stream(const void *p0, size_t bytes0, const void *p1, size_t bytes1, unsigned *sink, int n_wg, void *stream);
 int launch_copy(const void *src, void *dst, size_t bytes, void *stream);
 int launch_zero(void *dst, size_t bytes, void *stream);
 int launch_embed(const EmbedArgs &, void *stream);

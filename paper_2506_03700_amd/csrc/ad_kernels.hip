@@ -58,6 +58,35 @@ __global__ void k_zero16(u32x4 *dst, size_t n16) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) dst[i] = z;
 }
 
+// Measurement aid: every workgroup reads its contiguous share of up to two ranges with 16 independent 128-bit loads
+// per thread in flight and folds what it read into a word that is never stored (the condition below cannot hold for
+// a range of more than 16 bytes, which the compiler cannot know).
+struct ProbeArgs {
+    const u32x4 *p[2];
+    size_t n16[2];
+    unsigned *sink;
+};
+__global__ void __launch_bounds__(512) k_probe_stream(ProbeArgs a) {
+    constexpr int U = 16;
+    u32x4 acc = {0, 0, 0, 0};
+    for (int r = 0; r < 2; ++r) {
+        const size_t n = a.n16[r];
+        const size_t begin = n * blockIdx.x / gridDim.x, end = n * (blockIdx.x + 1) / gridDim.x;
+        const u32x4 *p = a.p[r];
+        for (size_t i = begin + threadIdx.x; i < end; i += (size_t)512 * U) {
+            u32x4 v[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                const size_t j = i + (size_t)k * 512;
+                v[k] = p[j < end ? j : i];
+            }
+#pragma unroll
+            for (int k = 0; k < U; ++k) acc ^= v[k];
+        }
+    }
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u && a.n16[0] == 1) *a.sink = acc[0];
+}
+
 __global__ void k_embed(EmbedArgs a) {
     for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < a.m * a.d; idx += gridDim.x * blockDim.x) {
         const int r = idx / a.d, c = idx % a.d;
@@ -93,6 +122,15 @@ int launch_pack_weights(const void *src, const void *src2, int src_elem, int64_t
     const int64_t threads = NT * KT * 64;
     hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, S(stream), src, src2, src_elem,
                        N, K, NT, KT, mode, (uint16_t *)dst);
+    return (int)hipGetLastError();
+}
+
+int launch_probe_stream(const void *p0, size_t bytes0, const void *p1, size_t bytes1, unsigned *sink, int n_wg, void *stream) {
+    ProbeArgs a;
+    a.p[0] = (const u32x4 *)p0; a.n16[0] = bytes0 / 16;
+    a.p[1] = (const u32x4 *)p1; a.n16[1] = p1 ? bytes1 / 16 : 0;
+    a.sink = sink;
+    hipLaunchKernelGGL(k_probe_stream, dim3(n_wg), dim3(512), 0, S(stream), a);
     return (int)hipGetLastError();
 }
 

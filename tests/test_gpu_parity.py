@@ -358,6 +358,40 @@ def test_generate_full_width_reduced_depth(ad, shape, mode):
     g.close()
 
 
+def test_stream_probe_only_reads(ad):
+    """The measurement aid reads a layer's weights and cache rows and changes nothing: a layer step gives the same
+    bits before and after it, and arguments outside the model are refused."""
+    import torch
+    shape = synth.MINI8B
+    w = synth.make_weights(shape, seed=0)
+    g = ad.Model(shape, w, max_pos=64)
+    h0 = synth.make_hidden(shape, 3, 5)
+
+    def run():
+        g.kv_truncate(0)
+        h = torch.from_numpy(h0).to("cuda:0")
+        for l in range(1, shape.n_layers + 1):
+            g.ad_layer_step(l, h, np.arange(5))
+        return h.cpu().numpy().copy(), [gpu_kv(g, l, 5) for l in (1, shape.n_layers)]
+
+    a, kva = run()
+    for mode in (ad.AD_PROBE_ONE_KERNEL, ad.AD_PROBE_PER_PHASE):
+        for l in range(1, shape.n_layers + 1):
+            for ctx in (0, 5, 64):
+                g.ad_probe_stream(l, ctx, mode)
+    torch.cuda.synchronize()
+    kvb = [gpu_kv(g, l, 5) for l in (1, shape.n_layers)]
+    b, _ = run()
+    np.testing.assert_array_equal(a, b)
+    for x, y in zip(kva, kvb):
+        np.testing.assert_array_equal(x[0], y[0])
+        np.testing.assert_array_equal(x[1], y[1])
+    for bad in ((0, 4, 0), (shape.n_layers + 1, 4, 0), (1, 65, 0), (1, -1, 1), (1, 4, 2)):
+        with pytest.raises(ad.AdError):
+            g.ad_probe_stream(*bad)
+    g.close()
+
+
 def test_abi_error_paths(ad):
     import torch
     shape = synth.TINY
