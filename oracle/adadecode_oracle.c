@@ -526,9 +526,14 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
     const int sampled = gp->temperature > 0.0;
     if (sampled && (!gp->uniforms || cap_rows > 9)) return -1;
 
+    /* the open tokens (early predictions that still owe deeper layers, oldest first, then the current token t_i):
+     * position, token id, hidden row; a token is named by its slot in these arrays */
     int32_t *row_pos = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap_rows);
     int32_t *row_tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap_rows);
-    int32_t *row_depth = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap_rows);
+    /* P[l], 1 <= l <= L: the tokens to be processed in parallel at layer l (Algorithm 1), as slots in arrival order;
+     * nP[l] of them, stored at P + l * cap_rows */
+    int32_t *P = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap_rows * (size_t)(L + 1));
+    int32_t *nP = (int32_t *)calloc((size_t)(L + 1), sizeof(int32_t));
     int32_t *row_arg = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap_rows);
     double *row_margin = (double *)malloc(sizeof(double) * (size_t)cap_rows);
     double *row_h = (double *)malloc(sizeof(double) * (size_t)cap_rows * d);
@@ -554,25 +559,31 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
     int32_t n_rows = 0, n_y = 0, n_verified = 0, done = 0;
 
     while (rc == 0 && !done) {
-        /* the current token enters at layer 1 */
-        row_pos[n_rows] = pos;
-        row_tok[n_rows] = cur;
-        row_depth[n_rows] = 0;
-        orc_embed(model, &cur, 1, row_h + (size_t)n_rows * d);
+        /* the current token t_i takes the next slot */
+        const int32_t ti = n_rows;
+        row_pos[ti] = pos;
+        row_tok[ti] = cur;
+        orc_embed(model, &cur, 1, row_h + (size_t)ti * d);
         ++n_rows;
         const int exits_ok = (n_rows - 1 < gp->max_pending) && (n_y + 1 < gp->max_new);
 
         for (int32_t l = 1; l <= L && rc == 0; ++l) {
-            /* pending list of layer l: the rows that have been through exactly l-1 layers */
-            int32_t first = n_rows - 1;
-            while (first > 0 && row_depth[first - 1] == l - 1) --first;
-            const int32_t m = n_rows - first;
-            for (int32_t r = 0; r < first; ++r)
-                if (row_depth[r] < l) rc = -4; /* would mean a token skipped a layer: never happens */
+            /* P[l] <- P[l] (+) t_i */
+            int32_t *Pl = P + (size_t)l * cap_rows;
+            Pl[nP[l]++] = ti;
+            /* update the KV cache at layer l by processing all tokens in P[l] in parallel.  Tokens enter the lists in
+             * order and leave them together, so P[l] is a run of neighbouring slots that ends with t_i, at consecutive
+             * positions that continue the layer's cache (checked: anything else would mean a token skipped a layer) */
+            const int32_t m = nP[l], first = Pl[0];
+            for (int32_t k = 0; k < m; ++k)
+                if (Pl[k] != first + k) rc = -4;
+            if (Pl[m - 1] != ti) rc = -4;
             if (rc != 0) break;
             rc = orc_layer_step(model, kv, l, row_h + (size_t)first * d, row_pos + first, m);
             if (rc != 0) break;
-            for (int32_t r = first; r < n_rows; ++r) row_depth[r] = l;
+            /* a token has passed layer l once it has been processed there: it leaves P[l] (Fig. 2, left).  P[L] is kept
+             * until the verification below has looked at its tokens */
+            if (l < L) nP[l] = 0;
             ++st.layer_steps;
             st.layer_step_rows += m;
             if (m <= 8) ++st.steps_by_m[m];
@@ -599,18 +610,26 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
                 if (tok == gp->eos_id) fire = 0;
                 emit(events, max_events, &n_events, (orc_event){ORC_EV_HEAD, l, pos, 1, tok, fire, conf, margin});
                 if (fire) {
-                    /* early prediction: emit it, leave this token's deeper layers owed, start the next token */
+                    /* early prediction: y <- y (+) t_{i+1}; P[l'] <- P[l'] (+) t_i for all deeper layers l' (they are
+                     * owed to t_i and run together with later tokens); start the next token at once */
                     out_tokens[n_y++] = tok;
                     ++st.early_preds;
+                    for (int32_t l2 = l + 1; l2 <= L; ++l2) P[(size_t)l2 * cap_rows + nP[l2]++] = ti;
                     cur = tok;
                     ++pos;
                     break;
                 }
             }
             if (l == L) {
-                /* every row is now complete at every layer: verify the early predictions in order */
+                /* the final layer is reached: P[L] holds every open token, each now complete at every layer; verify
+                 * them in order, then empty P[L] */
                 int32_t n_accept, next;
                 const int32_t n_draft = n_rows - 1;
+                if (nP[L] != n_rows || Pl[0] != 0) { rc = -4; break; }
+                for (int32_t l2 = 1; l2 < L; ++l2)
+                    if (nP[l2] != 0) rc = -4;
+                if (rc != 0) break;
+                nP[L] = 0;
                 if (gp->no_verify) {
                     /* ablation: the drafts stand unchecked; the newest row's final head gives the next token */
                     const int32_t r = n_rows - 1;
@@ -689,7 +708,7 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
     *n_out = n_verified;
     if (stats) *stats = st;
     if (n_events_out) *n_events_out = n_events;
-    free(row_pos); free(row_tok); free(row_depth); free(row_arg); free(row_margin); free(row_h);
+    free(row_pos); free(row_tok); free(P); free(nP); free(row_arg); free(row_margin); free(row_h);
     free(row_q); free(zbuf); free(pbuf);
     return rc;
 }
