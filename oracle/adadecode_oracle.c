@@ -489,11 +489,12 @@ static int32_t exit_head_index(const orc_config *c, int32_t layer) {
 /*
  * Algorithm 1 (adaptive layer parallelism), greedy decoding or, with temperature > 0, sampled decoding.
  *
- * State.  `rows` are the tokens whose deeper layers are still owed, oldest first: the early-predicted
- * tokens since the last verification plus the current token.  depth[r] is the number of layers row r
- * has been through, so the pending list of layer l is exactly the rows with depth == l-1; because a
- * token can only leave the layer loop at a head layer and the next token then re-enters at layer 1,
- * that set is always a suffix of `rows` ending at the current token.
+ * State, in the listing's notation.  The open tokens (the early predictions since the last verification,
+ * oldest first, then the current token t_i) keep their position, id and hidden row in slots; P[l] is the
+ * list of tokens to be processed in parallel at layer l.  The loop is the listing's: t_i is appended to
+ * P[l], layer l processes all of P[l], the head of that layer may predict t_{i+1} early, in which case t_i
+ * is appended to every deeper list and the next token starts; at the last layer the tokens of P[L] are
+ * verified and the list is emptied.
  *
  * Readings of points the pseudo-code leaves open:
  *  - a token leaves a layer's pending list once the layer has processed it (the listing only empties
