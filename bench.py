@@ -214,7 +214,9 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         head_us = e0.elapsed_time(e1) * 1e3 / 200
-        decision = {"tokens": n_dc, "head_evaluation_back_to_back_us": round(head_us, 2)}
+        decision = {"tokens": n_dc, "head_evaluation_back_to_back_us": round(head_us, 2),
+                    "note": "us_per_token figures include the prompt's prefill spread over the run's tokens (the same in both runs of a "
+                            "pair, so it cancels in us_per_extra_head_evaluation)"}
         for ahead in (True, False):
             t_all, st_all = us_per_token(cap, ahead)
             t_one, st_one = us_per_token(0, ahead)
