@@ -491,10 +491,9 @@ static int32_t exit_head_index(const orc_config *c, int32_t layer) {
  *
  * State, in the listing's notation.  The open tokens (the early predictions since the last verification,
  * oldest first, then the current token t_i) keep their position, id and hidden row in slots; P[l] is the
- * list of tokens to be processed in parallel at layer l.  The loop is the listing's: t_i is appended to
- * P[l], layer l processes all of P[l], the head of that layer may predict t_{i+1} early, in which case t_i
- * is appended to every deeper list and the next token starts; at the last layer the tokens of P[L] are
- * verified and the list is emptied.
+ * pending list of layer l.  The loop follows the listing step by step: t_i joins P[l], layer l runs over the
+ * whole list at once, the head of that layer may predict t_{i+1} early, in which case t_i joins every deeper
+ * list and the next token starts; at the last layer the tokens of P[L] are verified and the list is emptied.
  *
  * Readings of points the pseudo-code leaves open:
  *  - a token leaves a layer's pending list once the layer has processed it (the listing only empties
@@ -531,7 +530,7 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
      * position, token id, hidden row; a token is named by its slot in these arrays */
     int32_t *row_pos = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap_rows);
     int32_t *row_tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap_rows);
-    /* P[l], 1 <= l <= L: the tokens to be processed in parallel at layer l (Algorithm 1), as slots in arrival order;
+    /* P[l], 1 <= l <= L: the per-layer pending lists of Algorithm 1 (the tokens layer l still has to run), as slots in arrival order;
      * nP[l] of them, stored at P + l * cap_rows */
     int32_t *P = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap_rows * (size_t)(L + 1));
     int32_t *nP = (int32_t *)calloc((size_t)(L + 1), sizeof(int32_t));
@@ -572,9 +571,10 @@ int orc_generate_ada(const orc_model *model, orc_kv *kv, const int32_t *prompt, 
             /* P[l] <- P[l] (+) t_i */
             int32_t *Pl = P + (size_t)l * cap_rows;
             Pl[nP[l]++] = ti;
-            /* update the KV cache at layer l by processing all tokens in P[l] in parallel.  Tokens enter the lists in
-             * order and leave them together, so P[l] is a run of neighbouring slots that ends with t_i, at consecutive
-             * positions that continue the layer's cache (checked: anything else would mean a token skipped a layer) */
+            /* layer l runs once over every token of P[l] together; their K/V entries join the layer's cache.  Tokens
+             * enter the lists in order and leave them together, so P[l] is a run of neighbouring slots that ends with
+             * t_i, at consecutive positions that continue the layer's cache (checked: anything else would mean a token
+             * skipped a layer) */
             const int32_t m = nP[l], first = Pl[0];
             for (int32_t k = 0; k < m; ++k)
                 if (Pl[k] != first + k) rc = -4;
