@@ -46,6 +46,20 @@ static inline double f16_value(uint16_t bits) {
     return sign ? -v : v;
 }
 
+/* The same values from a table indexed by the 16 bits (filled once from f16_value, which stays the definition): the
+ * two ldexp calls per element made fp16 models twenty times slower to check than bf16 ones. */
+static double f16_table[65536];
+static int f16_table_ready = 0;
+static void f16_table_init(void) {
+#pragma omp critical(orc_f16_table)
+    {
+        if (!f16_table_ready) {
+            for (uint32_t b = 0; b < 65536u; ++b) f16_table[b] = f16_value((uint16_t)b);
+            f16_table_ready = 1;
+        }
+    }
+}
+
 static inline double weight_at(const void *w, int32_t wdtype, size_t i) {
     if (wdtype == ORC_F32) return (double)((const float *)w)[i];
     return wdtype == ORC_BF16 ? bf16_value(((const uint16_t *)w)[i]) : f16_value(((const uint16_t *)w)[i]);
@@ -86,7 +100,9 @@ static double dot_w(const void *w, int32_t wdtype, size_t off, const double *x, 
         for (int32_t i = 0; i < n; ++i) acc += bf16_value(p[i]) * x[i];
     } else {
         const uint16_t *p = (const uint16_t *)w + off;
-        for (int32_t i = 0; i < n; ++i) acc += f16_value(p[i]) * x[i];
+        if (!f16_table_ready) f16_table_init();
+#pragma omp simd reduction(+ : acc)
+        for (int32_t i = 0; i < n; ++i) acc += f16_table[p[i]] * x[i];
     }
     return acc;
 }
@@ -208,6 +224,7 @@ orc_model *orc_model_new(const orc_config *cfg, const orc_layer_weights *layers,
         cfg->head_dim % 2 != 0 || cfg->n_exit < 0 || cfg->n_exit > ORC_MAX_EXIT)
         return NULL;
     orc_model *m = (orc_model *)calloc(1, sizeof *m);
+    f16_table_init();
     m->cfg = *cfg;
     m->layers = (orc_layer_weights *)malloc(sizeof(orc_layer_weights) * (size_t)cfg->n_layers);
     memcpy(m->layers, layers, sizeof(orc_layer_weights) * (size_t)cfg->n_layers);
