@@ -990,6 +990,8 @@ ad_status ad_generate(const ad_model *m, ad_kv *kv, const int32_t *prompt, int32
     be.m = m; be.kv = kv; be.stream = stream;
     int rc = run_algorithm1(be, sc, *gp, prompt, n_prompt, out_tokens, n_out, stats, events, max_events, n_events);
     if (stats) stats->bytes_algorithmic = be.bytes;
+    // nothing the call enqueued (work issued ahead of an outcome included) is still running when it returns
+    if (rc != AD_OK) (void)stream_sync(stream);
     if (rc == AD_OK && (rc = stream_sync(stream))) return (ad_status)hip_fail(rc, "ad_generate");
     if (rc == AD_OK) rc = fused_health(m, stream);
     return (ad_status)rc;
