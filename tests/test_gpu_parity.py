@@ -328,6 +328,57 @@ def test_generate_matches_oracle_decisions(ad, shape, mode):
     g.close()
 
 
+@pytest.mark.parametrize("shape,mode", with_modes([UNTIED, UNTIED.with_(name="tiny-untied-bf16", dtype=synth.BF16)]))
+def test_generate_edge_cases_match_oracle(ad, shape, mode):
+    """Degenerate runs of Algorithm 1 against the oracle: a prompt of one token (no prefill, the first layer step
+    runs on an empty cache), a budget of one token (nothing may be drafted), a cap of zero (plain decoding: no head
+    is evaluated), a run that fills the cache to its last position with every token leaving early, and an
+    end-of-sequence token that the last layer emits."""
+    w = synth.make_weights(shape, seed=0)
+    max_pos = 64
+    o = orc.Oracle(shape, w, max_pos=max_pos)
+    g = ad.Model(shape, w, max_pos=max_pos, layer_mode=mode)
+    p = synth.make_prompt(shape, 5)
+    k = len(shape.exit_layers)
+    forced = synth.make_forced_schedule(shape, 4, max_pos, probs=[0.9 / k] * k)
+    for what, prompt, n_new, gamma, cap, kw in [
+            ("one-token prompt", p[:1], 24, 0.0045, 7, {}),
+            ("one-token prompt, forced", p[:1], 24, 0.9, 7, dict(forced_exit=forced)),
+            ("budget of one token", p[:9], 1, 0.0, 7, {}),
+            ("budget of two tokens", p[:9], 2, 0.0, 7, {}),
+            ("cap 0", p[:9], 24, 0.0, 0, {}),
+            ("cap 1", p[:9], 24, 0.0, 1, {}),
+            ("cache filled to the last position", p[:16], max_pos - 16, 0.9, 7, dict(forced_exit=forced)),
+            ("cache filled to the last position, natural", p[:16], max_pos - 16, 0.0045, 7, {})]:
+        print(f"case {shape.name} layer mode {mode}: {what}", flush=True)
+        r = compare_runs(shape, g, o, prompt, n_new, gamma, cap, **kw)
+        if what == "cap 0":
+            assert r.stats["head_evals"] == 0 and r.stats["layer_steps"] == n_new * shape.n_layers
+        if what == "budget of one token":
+            assert r.stats["early_preds"] == 0
+    # one position too many is refused before anything runs
+    with pytest.raises(ad.AdError) as e:
+        g.ad_generate(p[:16], max_pos - 15, 0.9, 7)
+    assert e.value.status == ad.AD_ERANGE
+    # end of sequence: the token the plain run emits 10th stops the run there, on both sides
+    tg, _, _ = g.ad_generate(p[:9], 24, 0.0045, 7)
+    to, _, _ = o.generate_ada(p[:9], 24, 0.0045, 7)
+    eos = int(to[9])
+    first = int(np.nonzero(to == eos)[0][0])
+    print(f"case {shape.name} layer mode {mode}: end of sequence (token {eos}, first at {first})", flush=True)
+    tg, sg, eg = g.ad_generate(p[:9], 24, 0.0045, 7, eos_id=eos)
+    to2, so2, eo2 = o.generate_ada(p[:9], 24, 0.0045, 7, eos_id=eos)
+    assert len(to2) == first + 1 and int(to2[-1]) == eos
+    from compare_runs import events
+    if events(eg) == events(eo2):
+        np.testing.assert_array_equal(tg, to2)
+    else:
+        # a near tie may part the two runs (16-bit models); the GPU's run must still end with its first EOS
+        assert shape.dtype != synth.F32
+        assert int(tg[-1]) == eos and eos not in [int(t) for t in tg[:-1]]
+    g.close()
+
+
 @pytest.mark.parametrize("shape,mode", with_modes([synth.MINI8B, synth.MINI13B, synth.MINI8B.with_(name="8b-mini-f16", dtype=synth.F16),
                                                     synth.WIDE_MINI]))
 def test_generate_full_width_reduced_depth(ad, shape, mode):
