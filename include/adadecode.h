@@ -236,7 +236,10 @@ typedef struct { int32_t kind, layer, pos, m, token, flag; float conf; float res
 
 /* Runs Algorithm 1 from an empty cache: prompt (host [n_prompt]) -> out_tokens (host [max_new]).
  * events: NULL, or host [max_events]; *n_events counts every event even beyond max_events.
- * Synchronises the stream internally. */
+ * The host thread takes every exit decision: after each head evaluation it polls a word in pinned memory that the
+ * head's last kernel sets (falling back to a stream synchronisation if the word does not appear), so the call
+ * occupies one host core while it runs.  When it returns, on success or with an error, nothing it enqueued is still
+ * running on the stream.  Calls on one model must not overlap (they share the model's workspace and result words). */
 ad_status ad_generate(const ad_model *, ad_kv *, const int32_t *prompt, int32_t n_prompt, const ad_gen_params *,
                       int32_t *out_tokens, int32_t *n_out, ad_stats *stats, ad_event *events, int64_t max_events,
                       int64_t *n_events, void *stream);
